@@ -1,0 +1,167 @@
+"""Seeded synthetic workloads: model shapes, layout degrees and raw buffer fills.
+
+This module is shared by the tests, the benchmark and the smoke check.  It holds
+no layout arithmetic at all: a workload is a set of plain integers (the shape of
+a model and the parallel degrees of its training and generation layouts), and a
+fill writes pseudo-random 16-bit words into a flat buffer by (buffer index,
+offset) only.  Both the CPU oracle and the HIP library translate the plain
+dictionaries below into their own structures.
+
+The shapes stand in for the checkpoints the paper trains (Qwen2.5-7B/32B,
+Qwen3-MoE-30B, DeepSeek-R1-671B; Evaluation section): a byte-moving path depends
+on shapes and degrees only, never on weight values.
+"""
+
+from __future__ import annotations
+
+import torch
+
+# Keys of a model shape.  `family`: "dense_gqa", "moe_gqa" or "moe_mla".
+_SPEC_DEFAULTS = dict(
+    family="dense_gqa", L=1, H=0, nq=0, nkv=0, d=0, I=0, V=0, qkv_bias=0,
+    has_embeddings=1, E=0, Ie=0, n_shared=0, q_lora=0, kv_lora=0, nope=0,
+    rope=0, v_dim=0, elem_bytes=2,
+)
+# Keys of a layout.  `kind`: "train" or "gen"; `expert_layout`: "per_expert" or
+# "grouped"; the two filters select one rank of the layout (-1 = every rank).
+_LAYOUT_DEFAULTS = dict(kind="train", tp=1, pp=1, ep=1,
+                        expert_layout="per_expert", tp_filter=-1, ep_filter=-1)
+
+
+def make_spec(**kw) -> dict:
+    s = dict(_SPEC_DEFAULTS)
+    s.update(kw)
+    return s
+
+
+def make_layout(**kw) -> dict:
+    l = dict(_LAYOUT_DEFAULTS)
+    l.update(kw)
+    return l
+
+
+def _wl(name, spec, src, dst, seed, note):
+    return dict(name=name, spec=spec, src=src, dst=dst, seed=seed, note=note)
+
+
+WORKLOADS = {
+    # Toy dense decoder, training TP2 -> generation TP1.
+    "C0": _wl(
+        "C0",
+        make_spec(family="dense_gqa", L=2, H=256, nq=4, nkv=2, d=64, I=688, V=1024),
+        make_layout(kind="train", tp=2, pp=1),
+        make_layout(kind="gen", tp=1),
+        1000, "toy dense, TP2 -> TP1"),
+    # Qwen2.5-7B-shaped dense decoder, training TP4 PP2 -> generation TP2.
+    "C1": _wl(
+        "C1",
+        make_spec(family="dense_gqa", L=28, H=3584, nq=28, nkv=4, d=128, I=18944,
+                  V=152064, qkv_bias=1),
+        make_layout(kind="train", tp=4, pp=2),
+        make_layout(kind="gen", tp=2),
+        1001, "Qwen2.5-7B-shaped, TP4 PP2 -> TP2"),
+    # Qwen2.5-32B-shaped dense decoder, training TP8 PP4 -> generation TP4.
+    "C2": _wl(
+        "C2",
+        make_spec(family="dense_gqa", L=64, H=5120, nq=40, nkv=8, d=128, I=27648,
+                  V=152064, qkv_bias=1),
+        make_layout(kind="train", tp=8, pp=4),
+        make_layout(kind="gen", tp=4),
+        1002, "Qwen2.5-32B-shaped, TP8 PP4 -> TP4"),
+    # Qwen3-30B-A3B-shaped MoE, training EP8 TP1 PP2 -> generation EP4 TP2.
+    # Source experts in the grouped-matmul orientation (transposing repack).
+    "C3": _wl(
+        "C3",
+        make_spec(family="moe_gqa", L=48, H=2048, nq=32, nkv=4, d=128, V=151936,
+                  E=128, Ie=768),
+        make_layout(kind="train", tp=1, pp=2, ep=8, expert_layout="grouped"),
+        make_layout(kind="gen", tp=2, ep=4),
+        1003, "Qwen3-30B-A3B-shaped, EP8 TP1 PP2 (grouped experts) -> EP4 TP2"),
+    # The same model with per-expert [out][in] source experts (pure regrouping).
+    "C3P": _wl(
+        "C3P",
+        make_spec(family="moe_gqa", L=48, H=2048, nq=32, nkv=4, d=128, V=151936,
+                  E=128, Ie=768),
+        make_layout(kind="train", tp=1, pp=2, ep=8, expert_layout="per_expert"),
+        make_layout(kind="gen", tp=2, ep=4),
+        1003, "Qwen3-30B-A3B-shaped, EP8 TP1 PP2 (per-expert) -> EP4 TP2"),
+    # DeepSeek-671B-shaped share: 8 MoE layers, EP64 -> rank 0 of EP8.
+    "C4": _wl(
+        "C4",
+        make_spec(family="moe_mla", L=8, H=7168, nq=128, V=0, has_embeddings=0,
+                  E=256, Ie=2048, n_shared=1, q_lora=1536, kv_lora=512, nope=128,
+                  rope=64, v_dim=128),
+        make_layout(kind="train", tp=1, pp=1, ep=64),
+        make_layout(kind="gen", tp=1, ep=8, ep_filter=0),
+        1004, "DeepSeek-671B-shaped share, EP64 -> one rank of EP8"),
+}
+
+# Small shapes for exhaustive checks (every element traced).
+TINY = {
+    # Dense GQA with bias, several KV groups per rank on both sides.
+    "tiny_dense": _wl(
+        "tiny_dense",
+        make_spec(family="dense_gqa", L=4, H=48, nq=8, nkv=4, d=8, I=40, V=64,
+                  qkv_bias=1),
+        make_layout(kind="train", tp=4, pp=2),
+        make_layout(kind="gen", tp=2),
+        2000, "tiny dense TP4 PP2 -> TP2"),
+    # The degrees of the paper's redundant-memory example (TP2 EP2 -> TP1 EP4).
+    "tiny_moe": _wl(
+        "tiny_moe",
+        make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=2, d=8, V=48, E=8, Ie=24,
+                  n_shared=1),
+        make_layout(kind="train", tp=2, pp=1, ep=2),
+        make_layout(kind="gen", tp=1, ep=4),
+        2001, "tiny MoE TP2 EP2 -> TP1 EP4"),
+    "tiny_moe_grouped": _wl(
+        "tiny_moe_grouped",
+        make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=2, d=8, V=48, E=8, Ie=24,
+                  n_shared=1),
+        make_layout(kind="train", tp=2, pp=2, ep=2, expert_layout="grouped"),
+        make_layout(kind="gen", tp=1, ep=4),
+        2002, "tiny MoE, grouped experts, TP2 PP2 EP2 -> TP1 EP4"),
+    "tiny_mla": _wl(
+        "tiny_mla",
+        make_spec(family="moe_mla", L=2, H=40, nq=4, V=0, has_embeddings=0, E=8,
+                  Ie=16, n_shared=1, q_lora=24, kv_lora=16, nope=8, rope=8,
+                  v_dim=8),
+        make_layout(kind="train", tp=2, pp=1, ep=8),
+        make_layout(kind="gen", tp=1, ep=2, ep_filter=1),
+        2003, "tiny MLA MoE TP2 EP8 -> TP1, rank 1 of EP2"),
+}
+
+
+def fill_buffer(nbytes: int, seed: int, device="cpu", mode: str = "normal") -> torch.Tensor:
+    """A flat int16 tensor of nbytes/2 words filled from `seed`.
+
+    mode "normal": bf16 words drawn from N(0, 0.02) (round-to-nearest-even by
+    torch's cast); mode "raw16": uniformly random 16-bit patterns, which include
+    NaN payloads, negative zero and subnormals.
+    """
+    assert nbytes % 2 == 0
+    n = nbytes // 2
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(int(seed))
+    if mode == "normal":
+        t = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        step = 1 << 28  # bounded temporaries for multi-GB buffers
+        for s in range(0, n, step):
+            t[s:s + step].normal_(0.0, 0.02, generator=g)
+        return t.view(torch.int16)
+    if mode == "raw16":
+        t = torch.empty(n, dtype=torch.int16, device=dev)
+        step = 1 << 28
+        for s in range(0, n, step):
+            t[s:s + step].random_(-32768, 32768, generator=g)
+        return t
+    raise ValueError(mode)
+
+
+def fill_buffers(sizes, seed: int, device="cpu", mode: str = "normal"):
+    """One filled buffer per entry of `sizes` (bytes); buffer i uses seed+i."""
+    return [fill_buffer(int(n), seed * 1000 + i, device, mode) for i, n in enumerate(sizes)]
+
+
+BF16_ONE = 0x3F80  # the 16-bit word of bf16 1.0, written over norm vectors
