@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the resharding hot path on one MI355X.
+
+One step = one pass of the whole path over one workload: swap-out of the
+training-side buffers (device-to-host, on the library's side stream) overlapped
+with the repack kernel, release of the training copy, re-allocation, swap-in
+(host-to-device).  Inputs are synthetic and already resident in HBM when the
+timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C1", help="C0, C1, C2, C3, C3P or C4")
+    ap.add_argument("--no-swap", action="store_true", help="time the repack alone (not a valid headline run)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-link-probe", action="store_true")
+    ap.add_argument("--tuning", default="", help="e.g. tile_bytes=65536,unroll=8")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, plan, src):
+    """The loop oracle, as it stands, on the host cores, on a bounded sample:
+    destination tensor rank 0 (and expert rank 0) of the same workload."""
+    import numpy as np
+
+    from oracle import fast
+    from paper_2507_19017_amd import Plan
+
+    only = dict(wl["dst"])
+    if only["tp"] > 1:
+        only["tp_filter"] = 0
+    if only["ep"] > 1 and only["ep_filter"] < 0:
+        only["ep_filter"] = 0
+    sub = Plan(wl["spec"], wl["src"], only)
+    used_src = sub.buf_used(0)
+    host_src = [s.cpu().numpy() if (u and s is not None) else None for s, u in zip(src, used_src)]
+    sizes, used = fast.buffer_sizes(wl["spec"], only), fast.buffers_used(wl["spec"], only)
+    dst = [np.zeros(n // 2, dtype=np.int16) if u else None for n, u in zip(sizes, used)]
+    threads = min(fast.max_threads(), 16)
+    fast.reshard(wl["spec"], wl["src"], only, host_src, dst, threads=threads)  # warm the pages
+    t0 = time.perf_counter()
+    nbytes = fast.reshard(wl["spec"], wl["src"], only, host_src, dst, threads=threads)
+    dt = time.perf_counter() - t0
+    return {
+        "value": round(2 * nbytes / dt / 1e9, 3), "unit": "GB/s (read+write)", "cores": threads,
+        "kind": "oracle",
+        "sample": "%s, destination rank 0 only: %.2f GB written, one run after a page-warming run" % (wl["name"], nbytes / 1e9),
+    }
+
+
+def link_probe(nbytes=1 << 30):
+    """Best of plain pinned hipMemcpyAsync D2H / H2D (torch copies), GB/s each way."""
+    import torch
+
+    dev = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+    best = {"d2h": 0.0, "h2d": 0.0}
+    for _ in range(4):
+        for name, (a, b) in (("d2h", (host, dev)), ("h2d", (dev, host))):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            a.copy_(b, non_blocking=True)
+            torch.cuda.synchronize()
+            best[name] = max(best[name], nbytes / (time.perf_counter() - t0) / 1e9)
+    del dev, host
+    return best
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2507_19017_amd import Plan, copy_baseline, get_tuning, set_tuning
+    from synth_inputs import BF16_ONE, WORKLOADS, fill_buffer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if a.tuning:
+        set_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in a.tuning.split(","))})
+    wl = WORKLOADS[a.workload]
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    info = plan.info()
+    sizes_s, used_s = plan.buf_bytes(0), plan.buf_used(0)
+    sizes_d, used_d = plan.buf_bytes(1), plan.buf_used(1)
+
+    def alloc_src(fill):
+        out = []
+        for i, (n, u) in enumerate(zip(sizes_s, used_s)):
+            if not u:
+                out.append(None)
+            elif fill:
+                out.append(fill_buffer(n, wl["seed"] * 1000 + i, "cuda"))
+            else:
+                out.append(torch.empty(n // 2, dtype=torch.int16, device="cuda"))
+        return out
+
+    src = alloc_src(True)
+    for t in plan.tensors(0):  # norm vectors are ones
+        if (t["name"].endswith("ln") or t["name"] in ("ln1", "ln2")) and src[t["buffer"]] is not None:
+            src[t["buffer"]][t["offset"] // 2:(t["offset"] + t["bytes"]) // 2] = BF16_ONE
+    dst = [torch.empty(n // 2, dtype=torch.int16, device="cuda") if u else None for n, u in zip(sizes_d, used_d)]
+    ptrs = lambda bufs: [0 if b is None else b.data_ptr() for b in bufs]
+    stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+    src_bytes = sum(n for n, u in zip(sizes_s, used_s) if u)
+    torch.cuda.reset_peak_memory_stats()
+
+    kernel_ms, out_s, in_s, freed = [], [], [], []
+
+    def step(record):
+        nonlocal src
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        if not a.no_swap:
+            plan.swap_out(h)            # D2H starts now on the side stream ...
+        e0.record(stream)
+        plan.execute(ptrs(src), ptrs(dst), h)   # ... and overlaps the repack
+        e1.record(stream)
+        if not a.no_swap:
+            plan.swap_wait()
+            t1 = time.perf_counter()
+            plan.mark_src_released()
+            before = torch.cuda.memory_allocated()
+            src = None
+            torch.cuda.empty_cache()
+            after = torch.cuda.memory_allocated()
+            src = alloc_src(False)      # "before the next update": new device home
+            plan.bind_src(ptrs(src))
+            t2 = time.perf_counter()
+            plan.swap_in(h)
+            plan.swap_wait()
+            t3 = time.perf_counter()
+        torch.cuda.synchronize()
+        if record:
+            kernel_ms.append(e0.elapsed_time(e1))
+            if not a.no_swap:
+                out_s.append(t1 - t0)
+                in_s.append(t3 - t2)
+                freed.append(before - after)
+
+    for _ in range(a.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(a.steps):
+        step(True)
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t_begin
+
+    moved = info["bytes_moved"]
+    k_avg = sum(kernel_ms) / len(kernel_ms) / 1e3
+    repack_gbps = 2 * moved / k_avg / 1e9
+    stats = plan.mem_stats()
+    peak_torch = torch.cuda.max_memory_allocated()
+
+    # plain copy of the same byte count class, same load/store code: the ceiling next to it
+    big_s = max((s for s in src if s is not None), key=lambda t: t.numel())
+    big_d = max((d for d in dst if d is not None), key=lambda t: t.numel())
+    cp_n = min(big_s.numel() * 2, big_d.numel() * 2, 8 << 30) // 4096 * 4096
+    evs = []
+    for _ in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        copy_baseline(big_d.data_ptr(), big_s.data_ptr(), cp_n, h)
+        e1.record(stream)
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    plain_gbps = 2 * cp_n / (min(x.elapsed_time(y) for x, y in evs[1:]) / 1e3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(a.workload)
+
+    link = None if a.no_link_probe or a.no_swap else link_probe()
+    out = {
+        "metric": "reshard repack GB/s (read+write)",
+        "value": round(repack_gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(total_s / a.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u16", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (wl["name"], wl["note"]), "bytes_moved_one_way": moved,
+                   "src_buffers": sum(used_s), "dst_buffers": sum(used_d),
+                   "descriptors": info["num_descs"], "tiles": info["num_tiles"], "tuning": get_tuning()},
+        "roofline": {"bound": "hbm", "achieved": round(repack_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(repack_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "kernel_ms_avg": round(k_avg * 1e3, 4), "kernel_ms_min": round(min(kernel_ms), 4),
+                     "plain_copy_GBps": round(plain_gbps, 1)},
+        "pct_hbm_peak": round(100 * repack_gbps / HBM_PEAK_GBPS, 2),
+        "peak_hbm_bytes": {"ledger": stats["peak_device"], "torch_max_allocated": peak_torch,
+                           "freed_after_swap_out": (sum(freed) // len(freed)) if freed else None},
+    }
+    if not a.no_swap:
+        so, si = sum(out_s) / len(out_s), sum(in_s) / len(in_s)
+        out["swap"] = {"bytes_each_way": src_bytes, "out_GBps": round(src_bytes / so / 1e9, 2),
+                       "in_GBps": round(src_bytes / si / 1e9, 2),
+                       "link_probe_GBps": None if link is None else {k: round(v, 2) for k, v in link.items()}}
+        if link:
+            out["swap"]["out_frac_of_link"] = round(src_bytes / so / 1e9 / link["d2h"], 3)
+            out["swap"]["in_frac_of_link"] = round(src_bytes / si / 1e9 / link["h2d"], 3)
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, plan, src)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,300 @@
+/*
+ * reshard.h - C ABI of the MI355X weight-resharding library.
+ *
+ * Scope: the on-device part of the resharding flow of MindSpeed RL (paper
+ * sections "Allgather-Swap Technique" and "Problem Statement", redundant-memory
+ * example).  After an actor update the training-layout weight shards (already
+ * gathered in HBM: step 1 of the technique) are repacked into the generation
+ * engine's layout at a different tensor/expert-parallel degree (step 2: "select
+ * and copy"), the training-side buffers are swapped to pinned host memory so
+ * their HBM can be released for generation (step 3, device-to-host), and swapped
+ * back before the next update (host-to-device) instead of resharding again.
+ *
+ * Conventions shared by every call
+ *   - All pointers named *_ptrs / spec / layout / out are HOST pointers.  The
+ *     entries of src_ptrs[] / dst_ptrs[] are DEVICE pointers owned by the caller.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every function returns RESHARD_OK (0) or a negative RESHARD_ERR_* code and
+ *     never throws.  reshard_last_error() returns a thread-local message for the
+ *     last failing call on the calling thread.
+ *   - A plan is not thread-safe: calls on one plan must be serialised by the
+ *     caller.  Different plans are independent.
+ *
+ * Layouts (the paper prints none; these are the Megatron-style conventions this
+ * library fixes).  Logical matrices are row-major [out, in]; elements are
+ * opaque words of elem_bytes bytes (2 for bf16) and are moved bit for bit.
+ *   Buffers.  A layout with tensor-parallel degree T, pipeline degree P and
+ *   expert-parallel degree X owns P*T "dense" buffers, index p*T + t, followed
+ *   (MoE families) by P*X "expert" buffers, index P*T + p*X + x.  Replicas along
+ *   data parallelism are not represented.  Every stored tensor starts on a
+ *   256-byte boundary; gap bytes are never read or written.
+ *   Dense buffer (p, t), in order: [embedding rows t*V/T..] (stage 0 only); per
+ *   layer of the stage: ln1, attention block, ln2, feed-forward block;
+ *   [final_ln, lm_head rows t*V/T..] (last stage only).
+ *     attention, GQA families: qkv weight, [qkv bias], o_proj columns
+ *       t*nq*d/T.. stored [H, nq*d/T].  TRAIN qkv: rank t owns KV groups
+ *       t*nkv/T.. ; each group is stored as its nq/nkv query heads, then its key
+ *       head, then its value head.  GEN qkv: rank t stores its query rows, then
+ *       its key rows, then its value rows.
+ *     attention, MLA family: q_a, q_a_ln, q_b (rows of heads t*nq/T..), kv_a,
+ *       kv_a_ln, kv_b (rows of heads t*nq/T..), o_proj columns t*nq*v_dim/T.. .
+ *     feed-forward, dense family: gate_up = gate rows t*I/T.. then up rows of the
+ *       same range; down = columns t*I/T.. stored [H, I/T].
+ *     feed-forward, MoE families: router [E, H] (replicated); if n_shared > 0 the
+ *       shared expert of width n_shared*Ie as fused gate_up and down, split like
+ *       the dense feed-forward.
+ *   Replicated ("common") tensors: ln1, ln2, final_ln, router, q_a, q_a_ln, kv_a,
+ *     kv_a_ln.  They are READ from tensor rank 0 of the owning stage and WRITTEN
+ *     to every destination tensor rank.
+ *   Expert buffer (p, x) holds whole experts x*E/X .. (never tensor-split), per
+ *   layer of the stage:
+ *     TRAIN, RESHARD_PER_EXPERT: for each local expert fc1 = [gate; up] stored
+ *       [2*Ie, H], then fc2 = down stored [H, Ie].
+ *     TRAIN, RESHARD_GROUPED (grouped-matmul orientation): w1[E/X][H][2*Ie] with
+ *       w1[e][h][c] = (c < Ie ? gate_e[c][h] : up_e[c-Ie][h]), then
+ *       w2[E/X][Ie][H] with w2[e][i][h] = down_e[h][i].
+ *     GEN: w13[E/X][2*Ie][H] (gate rows then up rows), then w2[E/X][H][Ie].
+ */
+#ifndef RESHARD_H
+#define RESHARD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct reshard_plan reshard_plan;
+
+enum {
+    RESHARD_OK = 0,
+    RESHARD_ERR_INVALID_ARG = -1, /* NULL/misaligned pointer, bad struct_size, bad index */
+    RESHARD_ERR_UNSUPPORTED = -2, /* shape not divisible by a degree, tp > nkv, too many buffers */
+    RESHARD_ERR_OOM = -3,         /* host or device allocation for the plan failed */
+    RESHARD_ERR_HOST_OOM = -4,    /* pinned host memory for the swap could not be allocated */
+    RESHARD_ERR_BAD_STATE = -5,   /* call not allowed in the plan's current swap state */
+    RESHARD_ERR_HIP = -6          /* a HIP runtime call failed; message has the HIP error */
+};
+
+enum { RESHARD_DENSE_GQA = 0, RESHARD_MOE_GQA = 1, RESHARD_MOE_MLA = 2 };
+enum { RESHARD_TRAIN = 0, RESHARD_GEN = 1 };
+enum { RESHARD_PER_EXPERT = 0, RESHARD_GROUPED = 1 };
+
+/* Shape of the model whose weights are resharded.  Set struct_size = sizeof. */
+typedef struct reshard_model_spec {
+    uint32_t struct_size;
+    int32_t family;         /* RESHARD_DENSE_GQA / MOE_GQA / MOE_MLA */
+    int32_t L, H;           /* decoder layers, hidden size */
+    int32_t nq, nkv, d;     /* query heads, KV heads, head dim (GQA families) */
+    int32_t I;              /* dense feed-forward width (dense family) */
+    int32_t V;              /* vocabulary rows (when has_embeddings) */
+    int32_t qkv_bias;       /* 1: fused qkv bias present (GQA families) */
+    int32_t has_embeddings; /* 1: embedding, final norm and lm_head present (untied) */
+    int32_t E, Ie;          /* routed experts per layer, expert feed-forward width */
+    int32_t n_shared;       /* shared experts (0 = none); shared width = n_shared*Ie */
+    int32_t q_lora, kv_lora, nope, rope, v_dim; /* MLA family */
+    int32_t elem_bytes;     /* bytes per weight element: 1, 2, 4 or 8 */
+} reshard_model_spec;
+
+/* One side of the resharding.  Set struct_size = sizeof. */
+typedef struct reshard_layout {
+    uint32_t struct_size;
+    int32_t kind;           /* RESHARD_TRAIN or RESHARD_GEN (GEN requires pp == 1) */
+    int32_t tp, pp, ep;     /* degrees, each >= 1 (ep must be 1 for the dense family) */
+    int32_t expert_layout;  /* TRAIN only: RESHARD_PER_EXPERT or RESHARD_GROUPED */
+    int32_t tp_rank_filter; /* destination only: keep this tensor rank's dense buffers (-1 = all) */
+    int32_t ep_rank_filter; /* destination only: keep this expert rank's buffers (-1 = all) */
+} reshard_layout;
+
+/* One stored tensor of a layout (for loading weights into / reading them out of the buffers). */
+typedef struct reshard_tensor_info {
+    char name[24];          /* "ln1", "qkv_w", "qkv_b", "wo", "gate_up", "down", "fc1", "w13", ... */
+    int32_t layer;          /* -1 for embedding / final norm / lm_head */
+    int32_t expert;         /* global expert index of a per-expert tensor, else -1 */
+    int32_t buffer;         /* index into src_ptrs / dst_ptrs */
+    int32_t replicated;     /* 1 for a common (replicated) tensor */
+    int64_t offset, bytes;  /* placement inside the buffer */
+} reshard_tensor_info;
+
+/*
+ * One copy descriptor of a plan (host-side view, for inspection and tests).
+ * kind 0 (strided copy): for i in [0, rows):
+ *     memcpy(dst + dst_off + i*dst_stride, src + src_off + i*src_stride, row_bytes)
+ * kind 1 (transposing copy of elem_bytes words): for i in [0, rows), k in [0, row_bytes/elem_bytes):
+ *     dst[dst_off + k*dst_stride + i*elem_bytes] = src[src_off + i*src_stride + k*elem_bytes]
+ * All offsets and strides are bytes.
+ */
+typedef struct reshard_desc {
+    int32_t src_buf, dst_buf;
+    int32_t kind, elem_bytes;
+    int64_t src_off, dst_off;
+    int64_t rows, row_bytes;
+    int64_t src_stride, dst_stride;
+} reshard_desc;
+
+typedef struct reshard_plan_info {
+    int32_t num_src_bufs, num_dst_bufs;
+    int64_t num_descs;      /* copy descriptors after merging */
+    int64_t num_tiles;      /* device work items the descriptors were cut into */
+    int64_t num_transpose_tiles;
+    int64_t bytes_moved;    /* destination bytes written by one execute (== bytes read) */
+    int64_t table_bytes;    /* device memory held by the plan (tile table) */
+} reshard_plan_info;
+
+/* Swap / residency state of the source (training-side) buffers of a plan. */
+enum {
+    RESHARD_SRC_UNBOUND = 0,      /* no source pointers known yet */
+    RESHARD_SRC_RESIDENT = 1,     /* bound, valid in HBM */
+    RESHARD_SRC_SWAPPING_OUT = 2, /* device-to-host copies in flight */
+    RESHARD_SRC_ON_HOST = 3,      /* host copy complete; device copy may be released */
+    RESHARD_SRC_RELEASED = 4,     /* caller freed the device copy; rebind before swap-in */
+    RESHARD_SRC_SWAPPING_IN = 5   /* host-to-device copies in flight */
+};
+
+/* Byte ledger of a plan (pure host bookkeeping of what the caller told the plan). */
+typedef struct reshard_mem_stats_t {
+    int64_t src_live;     /* bytes of bound, not released source buffers */
+    int64_t dst_live;     /* bytes of bound, not released destination buffers */
+    int64_t host_pinned;  /* pinned host bytes the plan currently owns */
+    int64_t peak_device;  /* max over time of src_live + dst_live (the plan's own table is in plan_info) */
+    int64_t released;     /* bytes returned by the last reshard_mark_src_released */
+    int32_t state;        /* RESHARD_SRC_* */
+} reshard_mem_stats_t;
+
+/* Knobs of the repack kernel; zero fields keep the built-in default. */
+typedef struct reshard_tuning {
+    int32_t tile_bytes;     /* bytes of work per tile (power of two, 4 KiB .. 512 KiB) */
+    int32_t block_threads;  /* 64, 128, 256, 512 or 1024 */
+    int32_t blocks_per_cu;  /* persistent grid = blocks_per_cu * CU count */
+    int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4 or 8 */
+    int32_t nontemporal;    /* bit 0: loads, bit 1: stores bypass-hint */
+} reshard_tuning;
+
+/* Thread-local message of the last failing call on this thread ("" if none). */
+const char *reshard_last_error(void);
+
+/*
+ * Process-wide tuning used by plans created afterwards (tile_bytes) and by
+ * executes issued afterwards (the launch shape).  NULL restores the defaults.
+ * Returns INVALID_ARG for a value outside the ranges above.
+ */
+int reshard_set_tuning(const reshard_tuning *t);
+int reshard_get_tuning(reshard_tuning *out);
+
+/*
+ * Step "select and copy", compile time (host only, no GPU needed): validates the
+ * shape against both layouts and compiles the src -> dst mapping into a flat
+ * table of copy descriptors, cut into equal-work tiles.  Any (kind, degrees)
+ * pair is allowed, so TRAIN -> GEN is the resharding, TRAIN -> TRAIN with equal
+ * degrees is the identity and GEN -> TRAIN is the way back.  Rank filters must
+ * be -1 on the source.  *out is owned by the library until reshard_plan_destroy.
+ * Errors: INVALID_ARG (NULL, struct_size), UNSUPPORTED (divisibility, tp > nkv,
+ * more than RESHARD_MAX_BUFFERS buffers, sizes beyond 32-bit strides), OOM.
+ */
+#define RESHARD_MAX_BUFFERS 384
+int reshard_plan_create(const reshard_model_spec *spec, const reshard_layout *src,
+                        const reshard_layout *dst, reshard_plan **out);
+
+/* Frees the plan, its device tile table and its pinned host memory.  Waits for
+ * swap copies still in flight.  NULL is allowed. */
+int reshard_plan_destroy(reshard_plan *plan);
+
+/* Buffer tables.  side: 0 = source, 1 = destination.  Counts are >= 0; a negative
+ * return is an error code.  `used` is 0 for a buffer the plan never touches (its
+ * pointer may then be NULL): destination buffers removed by a rank filter, source
+ * buffers that no kept destination needs. */
+int reshard_plan_num_bufs(const reshard_plan *plan, int side);
+int64_t reshard_plan_buf_bytes(const reshard_plan *plan, int side, int index);
+int reshard_plan_buf_used(const reshard_plan *plan, int side, int index);
+
+/* Stored-tensor table of one side, in (buffer, offset) order. */
+int64_t reshard_plan_num_tensors(const reshard_plan *plan, int side);
+int reshard_plan_tensor(const reshard_plan *plan, int side, int64_t index, reshard_tensor_info *out);
+
+/* Plan statistics and the descriptor table (copied into caller memory). */
+int reshard_plan_get_info(const reshard_plan *plan, reshard_plan_info *out);
+int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshard_desc *out);
+
+/*
+ * Step "select and copy", run time: one asynchronous kernel launch on `stream`
+ * that fills every used destination buffer from the source buffers.
+ * src_ptrs[num_src_bufs], dst_ptrs[num_dst_bufs]: device pointers, each aligned to
+ * 256 bytes and at least buf_bytes long; NULL allowed only where used == 0.  The
+ * two sets must not overlap.  The memory stays caller-owned and must remain valid
+ * until `stream` has run the launch.  On the first call the tile table is uploaded
+ * to device memory owned by the plan (a synchronous copy).  Remembers both pointer
+ * sets for the swap calls and the ledger (source state becomes RESIDENT).  Also
+ * allowed while a swap-out of the same source pointers is in flight (state stays
+ * SWAPPING_OUT): both only read the sources.
+ * Errors: INVALID_ARG, BAD_STATE (sources are on the host, released, or being
+ * swapped in), OOM, HIP.
+ */
+int reshard_execute(reshard_plan *plan, const void *const *src_ptrs, void *const *dst_ptrs,
+                    void *stream);
+
+/* Bind (or re-bind, after the caller re-allocated) the source pointers without
+ * running the repack.  Allowed in UNBOUND, RESIDENT, ON_HOST and RELEASED; from
+ * RELEASED the state becomes ON_HOST again (a device home for swap-in exists). */
+int reshard_bind_src(reshard_plan *plan, const void *const *src_ptrs);
+
+/*
+ * Step 3, device-to-host: copies every used source buffer into pinned host
+ * memory owned by the plan (allocated on first use, one block per buffer) with
+ * hipMemcpyAsync on the plan's own side stream.  The side stream first waits for
+ * the work already queued on `stream` at the time of the call (which may have
+ * written the sources), and for nothing queued later: call reshard_swap_out
+ * first and reshard_execute second (or use two streams) and the copies overlap
+ * the repack, which only reads the sources.
+ * State RESIDENT -> SWAPPING_OUT.  Call reshard_swap_wait before freeing the
+ * device buffers.  Errors: BAD_STATE, HOST_OOM (state unchanged), HIP.
+ */
+int reshard_swap_out(reshard_plan *plan, void *stream);
+
+/*
+ * Before the next update, host-to-device: copies the pinned host copy back into
+ * the currently bound source pointers on the side stream and makes `stream` wait
+ * for it, so work queued on `stream` afterwards sees the weights.
+ * State ON_HOST -> SWAPPING_IN.  Errors: BAD_STATE (not swapped out, or the
+ * device copy was released and not re-bound), HIP.
+ */
+int reshard_swap_in(reshard_plan *plan, void *stream);
+
+/* Blocks the host until the swap copies in flight are done and completes the
+ * state change (SWAPPING_OUT -> ON_HOST, SWAPPING_IN -> RESIDENT).  A no-op in
+ * any other state. */
+int reshard_swap_wait(reshard_plan *plan);
+
+/* Ledger: the caller has freed the device copy of the sources (allowed in
+ * ON_HOST) / of the destinations.  The source pointers are forgotten. */
+int reshard_mark_src_released(reshard_plan *plan);
+int reshard_mark_dst_released(reshard_plan *plan);
+
+/* Frees the pinned host copy (allowed in UNBOUND, RESIDENT). */
+int reshard_release_host(reshard_plan *plan);
+
+/* Host pointer of the pinned copy of source buffer `index` (NULL before the first
+ * swap-out).  The memory is owned by the plan; valid until release/destroy. */
+const void *reshard_host_copy(const reshard_plan *plan, int index);
+
+/* Test hook: refuse pinned allocations once the plan would own more than `limit`
+ * pinned bytes (negative = no limit).  Process-wide. */
+void reshard_set_host_limit(int64_t limit);
+
+int reshard_mem_stats(const reshard_plan *plan, reshard_mem_stats_t *out);
+
+/*
+ * Plain device-to-device copy of `bytes` (multiple of 16, pointers 16-byte
+ * aligned) with the same load/store code path as the repack kernel, one launch on
+ * `stream`.  Used as the bandwidth ceiling next to the repack and to calibrate
+ * hardware byte counters against a transfer of known size.
+ */
+int reshard_copy_baseline(void *dst, const void *src, int64_t bytes, void *stream);
+
+/* Library build tag, e.g. "reshard 0.1 gfx950". */
+const char *reshard_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RESHARD_H */

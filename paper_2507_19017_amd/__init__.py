@@ -1,0 +1,13 @@
+"""MI355X-native weight resharding (allgather-swap hot path): Python binding of libreshard.so."""
+
+from .binding import (  # noqa: F401
+    Plan,
+    ReshardError,
+    copy_baseline,
+    get_tuning,
+    last_error,
+    lib,
+    set_host_limit,
+    set_tuning,
+    version,
+)

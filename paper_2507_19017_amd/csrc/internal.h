@@ -1,0 +1,114 @@
+// Internal structures of the resharding library (not part of the C ABI).
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "reshard.h"
+
+namespace reshard {
+
+// Logical weight tensors (row-major [out, in]).
+enum LogicalId : int {
+    LT_EMB, LT_FINAL_LN, LT_LM_HEAD, LT_LN1, LT_LN2,
+    LT_WQ, LT_WK, LT_WV, LT_BQ, LT_BK, LT_BV, LT_WO,
+    LT_GATE, LT_UP, LT_DOWN, LT_ROUTER, LT_SH_GATE, LT_SH_UP, LT_SH_DOWN,
+    LT_EX_GATE, LT_EX_UP, LT_EX_DOWN,
+    LT_QA, LT_QA_LN, LT_QB, LT_KVA, LT_KVA_LN, LT_KVB
+};
+
+// A rectangle [r0,r1) x [c0,c1) of a logical tensor and where a layout stores it.
+// Element (r, c) lives at byte  off + ((r-r0)*ld + (c-c0))*eb   (transposed == false)
+//                          or   off + ((c-c0)*ld + (r-r0))*eb   (transposed == true).
+struct Fragment {
+    uint64_t key;  // (logical id, layer, expert) packed; equal keys = same logical tensor
+    int64_t r0, r1, c0, c1;
+    int32_t buf;
+    int64_t off;
+    int64_t ld;
+    bool transposed;
+};
+
+struct Side {
+    reshard_layout layout{};
+    int nd = 0, ne = 0;  // dense / expert buffer counts
+    std::vector<int64_t> buf_bytes;
+    std::vector<uint8_t> used;
+    std::vector<reshard_tensor_info> tensors;
+    std::vector<Fragment> frags;
+};
+
+// Device work item: 48 bytes, read with scalar loads by a whole workgroup.
+struct alignas(16) Tile {
+    uint64_t src_off;     // bytes from the start of the source buffer
+    uint64_t dst_off;     // bytes from the start of the destination buffer
+    uint32_t src_stride;  // bytes between rows
+    uint32_t dst_stride;
+    uint32_t rows;        // copy: rows of the tile.  transpose: source rows (i extent)
+    uint32_t row_units;   // copy: vector units per row.  transpose: elements per source row (k extent)
+    uint32_t magic;       // copy: floor(2^32/row_units)+1, or 0 when rows == 1
+    uint16_t src_buf;
+    uint16_t dst_buf;     // index into the pointer table (already offset past the sources)
+    uint8_t kind;         // 0 strided copy, 1 transposing copy
+    uint8_t vec_log2;     // copy: log2 of the vector width in bytes.  transpose: log2(elem_bytes)
+    uint8_t pad_[2];
+};
+static_assert(sizeof(Tile) == 48, "tile record layout");
+
+constexpr int kMaxTileUnits = 32768;  // keeps the multiply-high row split exact
+constexpr int kTransposeDim = 64;     // transposing tiles are at most 64 x 64 elements
+
+struct Tuning {
+    int tile_bytes = 128 * 1024;
+    int block_threads = 256;
+    int blocks_per_cu = 8;
+    int unroll = 4;
+    int nontemporal = 3;
+};
+Tuning current_tuning();
+
+void set_error(const std::string &msg);
+int fail(int code, const std::string &msg);
+
+// Host plan builder.
+int build_side(const reshard_model_spec &spec, const reshard_layout &lay, bool is_source, Side &out);
+int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
+                        std::vector<reshard_desc> &descs);
+int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, int tile_bytes,
+              std::vector<Tile> &copy_tiles, std::vector<Tile> &transpose_tiles);
+
+}  // namespace reshard
+
+struct reshard_plan {
+    reshard_model_spec spec{};
+    reshard::Side src, dst;
+    std::vector<reshard_desc> descs;
+    std::vector<reshard::Tile> copy_tiles, transpose_tiles;
+    reshard_plan_info info{};
+
+    // device side (created lazily by the first execute)
+    int device = -1;
+    void *d_tiles = nullptr;  // copy tiles followed by transposing tiles
+    int num_cus = 0;
+
+    // bound pointers
+    std::vector<const void *> src_ptrs;
+    std::vector<void *> dst_ptrs;
+    bool dst_bound = false;
+
+    // swap path
+    int state = RESHARD_SRC_UNBOUND;
+    std::vector<void *> host_copy;  // pinned, one per used source buffer (else nullptr)
+    int64_t host_pinned = 0;
+    void *side_stream = nullptr;
+    void *ev_ready = nullptr;  // recorded on the caller's stream
+    void *ev_done = nullptr;   // recorded on the side stream
+
+    // ledger
+    int64_t src_live = 0, dst_live = 0, peak_device = 0, released = 0;
+    void touch_peak() {
+        int64_t now = src_live + dst_live;
+        if (now > peak_device) peak_device = now;
+    }
+};

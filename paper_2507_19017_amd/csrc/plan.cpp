@@ -1,0 +1,465 @@
+// Host-side plan builder: compiles (model shape, source layout, destination
+// layout) into a flat table of copy descriptors and equal-work tiles.
+//
+// This is the "select" half of step 2 of the allgather-swap technique (paper
+// section "Allgather-Swap Technique": each device selects and copies the weight
+// slices it needs for generation), done once per layout pair instead of per
+// iteration.  Formulation: each layout is described as a list of FRAGMENTS
+// (rectangles of logical tensors with a storage address); the mapping is the set
+// of pairwise intersections of source and destination fragments of the same
+// logical tensor.  Nothing here depends on which two layout kinds are paired.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "internal.h"
+
+namespace reshard {
+
+namespace {
+
+thread_local std::string g_error;
+
+constexpr int64_t kAlign = 256;
+
+uint64_t make_key(int id, int layer, int expert) {
+    return (uint64_t(id) << 48) | (uint64_t(uint32_t(layer + 1) & 0xFFFFFF) << 24) |
+           uint64_t(uint32_t(expert + 1) & 0xFFFFFF);
+}
+
+bool is_replicated(int id) {
+    switch (id) {
+        case LT_LN1: case LT_LN2: case LT_FINAL_LN: case LT_ROUTER:
+        case LT_QA: case LT_QA_LN: case LT_KVA: case LT_KVA_LN:
+            return true;
+        default:
+            return false;
+    }
+}
+
+// Lays stored tensors out in one buffer and records the fragments they hold.
+class BufferBuilder {
+  public:
+    BufferBuilder(Side &side, int buf, int eb, bool record_frags, bool record_replicated)
+        : side_(side), buf_(buf), eb_(eb), frags_(record_frags), repl_(record_replicated) {}
+
+    // Starts a stored tensor of `elems` elements; returns its byte offset.
+    int64_t begin(const char *name, int layer, int expert, int64_t elems, bool replicated) {
+        off_ = (off_ + kAlign - 1) / kAlign * kAlign;
+        reshard_tensor_info ti{};
+        std::snprintf(ti.name, sizeof ti.name, "%s", name);
+        ti.layer = layer;
+        ti.expert = expert;
+        ti.buffer = buf_;
+        ti.replicated = replicated ? 1 : 0;
+        ti.offset = off_;
+        ti.bytes = elems * eb_;
+        side_.tensors.push_back(ti);
+        int64_t at = off_;
+        off_ += elems * eb_;
+        return at;
+    }
+
+    // Rows [r0,r1) x cols [c0,c1) of logical tensor `id` stored row-major (ld elements
+    // per row) at byte offset `off`; transposed = stored column-major with that ld.
+    void frag(int id, int layer, int expert, int64_t r0, int64_t r1, int64_t c0, int64_t c1,
+              int64_t off, int64_t ld, bool transposed = false) {
+        if (!frags_) return;
+        if (is_replicated(id) && !repl_) return;
+        side_.frags.push_back(Fragment{make_key(id, layer, expert), r0, r1, c0, c1, buf_, off, ld, transposed});
+    }
+
+    // A whole stored tensor that is one fragment.
+    void whole(const char *name, int id, int layer, int64_t r0, int64_t rows, int64_t c0,
+               int64_t cols) {
+        int64_t at = begin(name, layer, -1, rows * cols, is_replicated(id));
+        frag(id, layer, -1, r0, r0 + rows, c0, c0 + cols, at, cols);
+    }
+
+    int64_t finish() const { return (off_ + kAlign - 1) / kAlign * kAlign; }
+
+  private:
+    Side &side_;
+    int buf_, eb_;
+    bool frags_, repl_;
+    int64_t off_ = 0;
+};
+
+int check_shape(const reshard_model_spec &s, const reshard_layout &l) {
+    auto bad = [](const char *what) { return fail(RESHARD_ERR_UNSUPPORTED, what); };
+    if (s.family < RESHARD_DENSE_GQA || s.family > RESHARD_MOE_MLA)
+        return fail(RESHARD_ERR_INVALID_ARG, "unknown model family");
+    if (l.kind != RESHARD_TRAIN && l.kind != RESHARD_GEN)
+        return fail(RESHARD_ERR_INVALID_ARG, "unknown layout kind");
+    if (l.expert_layout != RESHARD_PER_EXPERT && l.expert_layout != RESHARD_GROUPED)
+        return fail(RESHARD_ERR_INVALID_ARG, "unknown expert layout");
+    if (s.L <= 0 || s.H <= 0 || s.nq <= 0) return fail(RESHARD_ERR_INVALID_ARG, "L, H, nq must be positive");
+    if (s.elem_bytes != 1 && s.elem_bytes != 2 && s.elem_bytes != 4 && s.elem_bytes != 8)
+        return fail(RESHARD_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8");
+    if (l.tp < 1 || l.pp < 1 || l.ep < 1) return fail(RESHARD_ERR_INVALID_ARG, "degrees must be >= 1");
+    if (l.kind == RESHARD_GEN && l.pp != 1) return bad("a generation layout has one pipeline stage");
+    if (s.L % l.pp) return bad("layers not divisible by pp");
+    if (s.nq % l.tp) return bad("query heads not divisible by tp");
+    if (s.family != RESHARD_MOE_MLA) {
+        if (s.nkv <= 0 || s.d <= 0) return fail(RESHARD_ERR_INVALID_ARG, "nkv, d must be positive");
+        if (s.nq % s.nkv) return bad("query heads not divisible by KV heads");
+        if (s.nkv % l.tp) return bad("KV heads not divisible by tp (KV-head replication is unsupported)");
+    } else if (s.q_lora <= 0 || s.kv_lora <= 0 || s.nope <= 0 || s.rope <= 0 || s.v_dim <= 0) {
+        return fail(RESHARD_ERR_INVALID_ARG, "MLA dimensions must be positive");
+    }
+    if (s.family == RESHARD_DENSE_GQA) {
+        if (s.I <= 0) return fail(RESHARD_ERR_INVALID_ARG, "I must be positive");
+        if (s.I % l.tp) return bad("feed-forward width not divisible by tp");
+        if (l.ep != 1) return bad("a dense model has no expert parallelism");
+    } else {
+        if (s.E <= 0 || s.Ie <= 0) return fail(RESHARD_ERR_INVALID_ARG, "E, Ie must be positive");
+        if (s.E % l.ep) return bad("experts not divisible by ep");
+        if (s.n_shared < 0) return fail(RESHARD_ERR_INVALID_ARG, "n_shared must be >= 0");
+        if ((int64_t(s.n_shared) * s.Ie) % l.tp) return bad("shared-expert width not divisible by tp");
+    }
+    if (s.has_embeddings) {
+        if (s.V <= 0) return fail(RESHARD_ERR_INVALID_ARG, "V must be positive");
+        if (s.V % l.tp) return bad("vocabulary not divisible by tp (padded vocabularies are unsupported)");
+    }
+    return RESHARD_OK;
+}
+
+}  // namespace
+
+void set_error(const std::string &msg) { g_error = msg; }
+int fail(int code, const std::string &msg) {
+    g_error = msg;
+    return code;
+}
+const char *last_error_cstr() { return g_error.c_str(); }
+
+int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_source, Side &out) {
+    if (int rc = check_shape(s, l)) return rc;
+    if (is_source && (l.tp_rank_filter >= 0 || l.ep_rank_filter >= 0))
+        return fail(RESHARD_ERR_INVALID_ARG, "rank filters apply to the destination only");
+    if (l.tp_rank_filter >= l.tp || l.ep_rank_filter >= l.ep)
+        return fail(RESHARD_ERR_INVALID_ARG, "rank filter out of range");
+    const int T = l.tp, P = l.pp, X = l.ep, eb = s.elem_bytes;
+    const bool moe = s.family != RESHARD_DENSE_GQA, mla = s.family == RESHARD_MOE_MLA;
+    const bool gen = l.kind == RESHARD_GEN;
+    const bool grouped = !gen && l.expert_layout == RESHARD_GROUPED;
+    const int64_t H = s.H, Lp = s.L / P;
+    out = Side{};
+    out.layout = l;
+    out.nd = P * T;
+    out.ne = moe ? P * X : 0;
+    if (out.nd + out.ne > RESHARD_MAX_BUFFERS) return fail(RESHARD_ERR_UNSUPPORTED, "too many buffers in one layout");
+    out.buf_bytes.assign(out.nd + out.ne, 0);
+    out.used.assign(out.nd + out.ne, 0);
+
+    for (int p = 0; p < P; ++p) {
+        for (int t = 0; t < T; ++t) {
+            const int b = p * T + t;
+            const bool kept = is_source || l.tp_rank_filter < 0 || l.tp_rank_filter == t;
+            // a source reads replicated tensors from tensor rank 0 only
+            BufferBuilder bb(out, b, eb, kept, !is_source || t == 0);
+            if (!is_source) out.used[b] = kept;
+            if (s.has_embeddings && p == 0) {
+                int64_t n = s.V / T;
+                bb.whole("emb", LT_EMB, -1, t * n, n, 0, H);
+            }
+            for (int64_t ly = p * Lp; ly < (p + 1) * Lp; ++ly) {
+                const int L_ = int(ly);
+                bb.whole("ln1", LT_LN1, L_, 0, 1, 0, H);
+                if (mla) {
+                    const int64_t heads = s.nq / T;
+                    const int64_t qrows = heads * (s.nope + s.rope), kvrows = heads * (s.nope + s.v_dim);
+                    bb.whole("q_a", LT_QA, L_, 0, s.q_lora, 0, H);
+                    bb.whole("q_a_ln", LT_QA_LN, L_, 0, 1, 0, s.q_lora);
+                    bb.whole("q_b", LT_QB, L_, t * qrows, qrows, 0, s.q_lora);
+                    bb.whole("kv_a", LT_KVA, L_, 0, s.kv_lora + s.rope, 0, H);
+                    bb.whole("kv_a_ln", LT_KVA_LN, L_, 0, 1, 0, s.kv_lora);
+                    bb.whole("kv_b", LT_KVB, L_, t * kvrows, kvrows, 0, s.kv_lora);
+                    bb.whole("wo", LT_WO, L_, 0, H, t * heads * s.v_dim, heads * s.v_dim);
+                } else {
+                    const int64_t d = s.d, g = s.nq / s.nkv;
+                    const int64_t groups = s.nkv / T;           // KV groups owned by this rank
+                    const int64_t qrows = groups * g * d, krows = groups * d;
+                    for (int pass = 0; pass < (s.qkv_bias ? 2 : 1); ++pass) {
+                        const bool bias = pass == 1;
+                        const int64_t w = bias ? 1 : H;         // a bias is a one-column matrix
+                        const int iq = bias ? LT_BQ : LT_WQ, ik = bias ? LT_BK : LT_WK, iv = bias ? LT_BV : LT_WV;
+                        const int64_t at = bb.begin(bias ? "qkv_b" : "qkv_w", L_, -1, (qrows + 2 * krows) * w, false);
+                        if (gen) {
+                            // blocked: this rank's query rows, key rows, value rows
+                            bb.frag(iq, L_, -1, t * qrows, (t + 1) * qrows, 0, w, at, w);
+                            bb.frag(ik, L_, -1, t * krows, (t + 1) * krows, 0, w, at + qrows * w * eb, w);
+                            bb.frag(iv, L_, -1, t * krows, (t + 1) * krows, 0, w, at + (qrows + krows) * w * eb, w);
+                        } else {
+                            // interleaved per KV group: g query heads, key head, value head
+                            const int64_t span = (g + 2) * d;
+                            for (int64_t j = 0; j < groups; ++j) {
+                                const int64_t G = t * groups + j, base = at + j * span * w * eb;
+                                bb.frag(iq, L_, -1, G * g * d, (G + 1) * g * d, 0, w, base, w);
+                                bb.frag(ik, L_, -1, G * d, (G + 1) * d, 0, w, base + g * d * w * eb, w);
+                                bb.frag(iv, L_, -1, G * d, (G + 1) * d, 0, w, base + (g + 1) * d * w * eb, w);
+                            }
+                        }
+                    }
+                    const int64_t ocols = int64_t(s.nq) * d / T;
+                    bb.whole("wo", LT_WO, L_, 0, H, t * ocols, ocols);
+                }
+                bb.whole("ln2", LT_LN2, L_, 0, 1, 0, H);
+                // fused gate/up (column-parallel halves) and down (row-parallel)
+                auto ffn = [&](const char *n1, const char *n2, int ig, int iu, int idn, int64_t width) {
+                    const int64_t n = width / T;
+                    const int64_t at = bb.begin(n1, L_, -1, 2 * n * H, false);
+                    bb.frag(ig, L_, -1, t * n, (t + 1) * n, 0, H, at, H);
+                    bb.frag(iu, L_, -1, t * n, (t + 1) * n, 0, H, at + n * H * eb, H);
+                    bb.whole(n2, idn, L_, 0, H, t * n, n);
+                };
+                if (!moe) {
+                    ffn("gate_up", "down", LT_GATE, LT_UP, LT_DOWN, s.I);
+                } else {
+                    bb.whole("router", LT_ROUTER, L_, 0, s.E, 0, H);
+                    if (s.n_shared) ffn("sh_fc1", "sh_fc2", LT_SH_GATE, LT_SH_UP, LT_SH_DOWN, int64_t(s.n_shared) * s.Ie);
+                }
+            }
+            if (s.has_embeddings && p == P - 1) {
+                int64_t n = s.V / T;
+                bb.whole("final_ln", LT_FINAL_LN, -1, 0, 1, 0, H);
+                bb.whole("lm_head", LT_LM_HEAD, -1, t * n, n, 0, H);
+            }
+            out.buf_bytes[b] = bb.finish();
+        }
+        if (!moe) continue;
+        const int64_t Ie = s.Ie, El = s.E / X;
+        for (int x = 0; x < X; ++x) {
+            const int b = out.nd + p * X + x;
+            const bool kept = is_source || l.ep_rank_filter < 0 || l.ep_rank_filter == x;
+            BufferBuilder bb(out, b, eb, kept, true);
+            if (!is_source) out.used[b] = kept;
+            for (int64_t ly = p * Lp; ly < (p + 1) * Lp; ++ly) {
+                const int L_ = int(ly);
+                if (gen || grouped) {
+                    const int64_t a1 = bb.begin(gen ? "w13" : "w1", L_, -1, El * 2 * Ie * H, false);
+                    const int64_t a2 = bb.begin("w2", L_, -1, El * Ie * H, false);
+                    for (int64_t j = 0; j < El; ++j) {
+                        const int e = int(x * El + j);
+                        if (gen) {
+                            const int64_t base = a1 + j * 2 * Ie * H * eb;
+                            bb.frag(LT_EX_GATE, L_, e, 0, Ie, 0, H, base, H);
+                            bb.frag(LT_EX_UP, L_, e, 0, Ie, 0, H, base + Ie * H * eb, H);
+                            bb.frag(LT_EX_DOWN, L_, e, 0, H, 0, Ie, a2 + j * H * Ie * eb, Ie);
+                        } else {
+                            // [expert][in][out]: logical (out r, in c) sits at column-major position
+                            const int64_t base = a1 + j * H * 2 * Ie * eb;
+                            bb.frag(LT_EX_GATE, L_, e, 0, Ie, 0, H, base, 2 * Ie, true);
+                            bb.frag(LT_EX_UP, L_, e, 0, Ie, 0, H, base + Ie * eb, 2 * Ie, true);
+                            bb.frag(LT_EX_DOWN, L_, e, 0, H, 0, Ie, a2 + j * Ie * H * eb, H, true);
+                        }
+                    }
+                } else {
+                    for (int64_t j = 0; j < El; ++j) {
+                        const int e = int(x * El + j);
+                        const int64_t a1 = bb.begin("fc1", L_, e, 2 * Ie * H, false);
+                        bb.frag(LT_EX_GATE, L_, e, 0, Ie, 0, H, a1, H);
+                        bb.frag(LT_EX_UP, L_, e, 0, Ie, 0, H, a1 + Ie * H * eb, H);
+                        const int64_t a2 = bb.begin("fc2", L_, e, H * Ie, false);
+                        bb.frag(LT_EX_DOWN, L_, e, 0, H, 0, Ie, a2, Ie);
+                    }
+                }
+            }
+            out.buf_bytes[b] = bb.finish();
+        }
+    }
+    std::stable_sort(out.tensors.begin(), out.tensors.end(),
+                     [](const reshard_tensor_info &a, const reshard_tensor_info &b) { return a.buffer < b.buffer; });
+    return RESHARD_OK;
+}
+
+namespace {
+
+// Folds a descriptor whose rows are back to back on both sides into one long row.
+void normalise(reshard_desc &d) {
+    if (d.kind == 0 && d.rows > 1 && d.src_stride == d.row_bytes && d.dst_stride == d.row_bytes) {
+        d.row_bytes *= d.rows;
+        d.rows = 1;
+    }
+    if (d.kind == 0 && d.rows == 1) d.src_stride = d.dst_stride = d.row_bytes;
+    if (d.kind == 1) {
+        // a one-row or one-column transpose is a strided copy of single elements; a
+        // 1 x n or n x 1 block with unit strides is a plain run
+        const int64_t cols = d.row_bytes / d.elem_bytes;
+        if (d.rows == 1 && d.dst_stride == d.elem_bytes) {
+            d.kind = 0;
+            d.src_stride = d.dst_stride = d.row_bytes;
+        } else if (cols == 1 && d.src_stride == d.elem_bytes) {
+            d.kind = 0;
+            d.row_bytes = d.rows * d.elem_bytes;
+            d.rows = 1;
+            d.src_stride = d.dst_stride = d.row_bytes;
+        }
+    }
+}
+
+// Appends `d` to the table, merging it into the previous descriptor when the two
+// are adjacent on both sides.
+void append_merged(std::vector<reshard_desc> &out, reshard_desc d) {
+    normalise(d);
+    if (!out.empty()) {
+        reshard_desc &p = out.back();
+        if (p.kind == 0 && d.kind == 0 && p.src_buf == d.src_buf && p.dst_buf == d.dst_buf) {
+            if (p.rows == 1 && d.rows == 1 && p.src_off + p.row_bytes == d.src_off &&
+                p.dst_off + p.row_bytes == d.dst_off) {
+                p.row_bytes += d.row_bytes;
+                p.src_stride = p.dst_stride = p.row_bytes;
+                return;
+            }
+            if (p.row_bytes == d.row_bytes && p.rows >= 1 && d.rows >= 1) {
+                // stack row blocks with equal pitch
+                const bool p_multi = p.rows > 1, d_multi = d.rows > 1;
+                int64_t ss = p_multi ? p.src_stride : d_multi ? d.src_stride : d.src_off - p.src_off;
+                int64_t ds = p_multi ? p.dst_stride : d_multi ? d.dst_stride : d.dst_off - p.dst_off;
+                const bool pitch_ok = ss >= p.row_bytes && ds >= p.row_bytes &&
+                                      (!p_multi || (p.src_stride == ss && p.dst_stride == ds)) &&
+                                      (!d_multi || (d.src_stride == ss && d.dst_stride == ds));
+                if (pitch_ok && d.src_off == p.src_off + p.rows * ss && d.dst_off == p.dst_off + p.rows * ds &&
+                    !(ss == p.row_bytes && ds == p.row_bytes)) {
+                    p.rows += d.rows;
+                    p.src_stride = ss;
+                    p.dst_stride = ds;
+                    return;
+                }
+            }
+        }
+    }
+    out.push_back(d);
+}
+
+}  // namespace
+
+int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
+                        std::vector<reshard_desc> &descs) {
+    const int64_t eb = spec.elem_bytes;
+    // index the source fragments by logical tensor
+    std::vector<uint32_t> order(src.frags.size());
+    for (uint32_t i = 0; i < order.size(); ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](uint32_t a, uint32_t b) { return src.frags[a].key < src.frags[b].key; });
+    auto first_of = [&](uint64_t key) {
+        return std::lower_bound(order.begin(), order.end(), key,
+                                [&](uint32_t a, uint64_t k) { return src.frags[a].key < k; });
+    };
+    std::fill(src.used.begin(), src.used.end(), 0);
+    descs.clear();
+    for (const Fragment &D : dst.frags) {
+        int64_t covered = 0;
+        for (auto it = first_of(D.key); it != order.end() && src.frags[*it].key == D.key; ++it) {
+            const Fragment &S = src.frags[*it];
+            const int64_t ra = std::max(S.r0, D.r0), rb = std::min(S.r1, D.r1);
+            const int64_t ca = std::max(S.c0, D.c0), cb = std::min(S.c1, D.c1);
+            if (ra >= rb || ca >= cb) continue;
+            covered += (rb - ra) * (cb - ca);
+            auto address = [&](const Fragment &F) {
+                return F.transposed ? F.off + ((ca - F.c0) * F.ld + (ra - F.r0)) * eb
+                                    : F.off + ((ra - F.r0) * F.ld + (ca - F.c0)) * eb;
+            };
+            reshard_desc d{};
+            d.src_buf = S.buf;
+            d.dst_buf = D.buf;
+            d.elem_bytes = int32_t(eb);
+            d.src_off = address(S);
+            d.dst_off = address(D);
+            d.src_stride = S.ld * eb;
+            d.dst_stride = D.ld * eb;
+            if (S.transposed == D.transposed) {
+                d.kind = 0;
+                // walk along whichever logical axis is contiguous on both sides
+                d.rows = S.transposed ? cb - ca : rb - ra;
+                d.row_bytes = (S.transposed ? rb - ra : cb - ca) * eb;
+            } else {
+                d.kind = 1;
+                // i runs along the source's slow axis, k along its fast axis
+                d.rows = S.transposed ? cb - ca : rb - ra;
+                d.row_bytes = (S.transposed ? rb - ra : cb - ca) * eb;
+            }
+            src.used[S.buf] = 1;
+            append_merged(descs, d);
+        }
+        if (covered != (D.r1 - D.r0) * (D.c1 - D.c0))
+            return fail(RESHARD_ERR_UNSUPPORTED, "internal: a destination fragment is not covered exactly once");
+    }
+    return RESHARD_OK;
+}
+
+int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, int tile_bytes,
+              std::vector<Tile> &copy_tiles, std::vector<Tile> &transpose_tiles) {
+    copy_tiles.clear();
+    transpose_tiles.clear();
+    auto fits32 = [](int64_t v) { return v >= 0 && v <= 0xFFFFFFFFll; };
+    for (const reshard_desc &d : descs) {
+        if (!fits32(d.src_stride) || !fits32(d.dst_stride))
+            return fail(RESHARD_ERR_UNSUPPORTED, "a row pitch exceeds 4 GiB");
+        Tile t{};
+        t.src_buf = uint16_t(d.src_buf);
+        t.dst_buf = uint16_t(num_src_bufs + d.dst_buf);
+        t.src_stride = uint32_t(d.src_stride);
+        t.dst_stride = uint32_t(d.dst_stride);
+        if (d.kind == 1) {
+            int lg = 0;
+            while ((1 << lg) < d.elem_bytes) ++lg;
+            const int64_t cols = d.row_bytes / d.elem_bytes;
+            t.kind = 1;
+            t.vec_log2 = uint8_t(lg);
+            for (int64_t i = 0; i < d.rows; i += kTransposeDim)
+                for (int64_t k = 0; k < cols; k += kTransposeDim) {
+                    t.rows = uint32_t(std::min<int64_t>(kTransposeDim, d.rows - i));
+                    t.row_units = uint32_t(std::min<int64_t>(kTransposeDim, cols - k));
+                    t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
+                    t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
+                    transpose_tiles.push_back(t);
+                }
+            continue;
+        }
+        // widest vector that every row start and the row length allow
+        int vec = 16;
+        auto misfit = [&](int v) {
+            if (d.row_bytes % v || d.src_off % v || d.dst_off % v) return true;
+            return d.rows > 1 && (d.src_stride % v || d.dst_stride % v);
+        };
+        while (vec > 1 && misfit(vec)) vec >>= 1;
+        int64_t units = d.row_bytes / vec;
+        if (units == 1 && d.rows > 1 && vec > 1) {  // keep the row split well defined
+            vec >>= 1;
+            units = 2;
+        }
+        int lg = 0;
+        while ((1 << lg) < vec) ++lg;
+        t.kind = 0;
+        t.vec_log2 = uint8_t(lg);
+        const int64_t max_units = std::max<int64_t>(1, std::min<int64_t>(tile_bytes / vec, kMaxTileUnits));
+        if (d.rows == 1 || units >= max_units || units == 1) {
+            // long rows: cut every row into runs
+            for (int64_t r = 0; r < d.rows; ++r)
+                for (int64_t u = 0; u < units; u += max_units) {
+                    t.rows = 1;
+                    t.row_units = uint32_t(std::min(max_units, units - u));
+                    t.magic = 0;
+                    t.src_off = uint64_t(d.src_off + r * d.src_stride + u * vec);
+                    t.dst_off = uint64_t(d.dst_off + r * d.dst_stride + u * vec);
+                    copy_tiles.push_back(t);
+                }
+        } else {
+            // short rows: several whole rows per tile
+            const int64_t rows_per_tile = std::max<int64_t>(1, max_units / units);
+            for (int64_t r = 0; r < d.rows; r += rows_per_tile) {
+                t.rows = uint32_t(std::min(rows_per_tile, d.rows - r));
+                t.row_units = uint32_t(units);
+                t.magic = t.rows == 1 ? 0u : uint32_t((uint64_t(1) << 32) / uint64_t(units)) + 1u;
+                t.src_off = uint64_t(d.src_off + r * d.src_stride);
+                t.dst_off = uint64_t(d.dst_off + r * d.dst_stride);
+                copy_tiles.push_back(t);
+            }
+        }
+    }
+    return RESHARD_OK;
+}
+
+}  // namespace reshard

@@ -1,0 +1,380 @@
+// Repack kernels for gfx950 (MI355X) and the execute entry point.
+//
+// Step 2 of the allgather-swap technique (paper section "Allgather-Swap
+// Technique": select and copy the weight slices needed for generation) is pure
+// data movement, so the bound is HBM bandwidth: there is no MFMA work here.
+// Design: a persistent grid (a few workgroups per compute unit) walks the tile
+// table with a static stride; every tile is an equal amount of work.  Copy tiles
+// move 16 bytes per lane per access with several loads in flight per lane before
+// the first store; rows shorter than a tile are addressed through a flat unit
+// index split by a multiply-high, so all 64 lanes of a wavefront stay busy for
+// any row length.  Transposing tiles are staged through LDS so that both the
+// global loads and the global stores stay contiguous.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+
+#include "internal.h"
+
+namespace reshard {
+
+namespace {
+
+std::mutex g_tuning_mutex;
+Tuning g_tuning;
+
+struct PtrTable {
+    char *p[RESHARD_MAX_BUFFERS];  // sources first, then destinations
+};
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename V, int NT>
+__device__ __forceinline__ V ld(const char *p) {
+    if (NT & 1) return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
+    return *reinterpret_cast<const V *>(p);
+}
+template <typename V, int NT>
+__device__ __forceinline__ void st(char *p, V v) {
+    if (NT & 2)
+        __builtin_nontemporal_store(v, reinterpret_cast<V *>(p));
+    else
+        *reinterpret_cast<V *>(p) = v;
+}
+
+// Copies one tile: n = rows*row_units vector units; unit u is column u % row_units
+// of row u / row_units.  magic == 0 marks a single contiguous row.
+template <typename V, int UNROLL, int NT>
+__device__ __forceinline__ void copy_tile(const char *__restrict__ s, char *__restrict__ d,
+                                          uint32_t n, uint32_t row_units, uint32_t magic,
+                                          uint32_t sstride, uint32_t dstride, uint32_t tid,
+                                          uint32_t nthreads) {
+    const uint32_t step = nthreads * UNROLL;
+    uint32_t base = tid;
+    // whole groups: no bounds checks
+    for (; base + (UNROLL - 1) * nthreads < n && base < n; base += step) {
+        V v[UNROLL];
+        uint64_t doff[UNROLL];
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const uint32_t u = base + k * nthreads;
+            const uint32_t row = __umulhi(u, magic);
+            const uint32_t col = u - row * row_units;
+            v[k] = ld<V, NT>(s + (uint64_t(row) * sstride + uint64_t(col) * sizeof(V)));
+            doff[k] = uint64_t(row) * dstride + uint64_t(col) * sizeof(V);
+        }
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) st<V, NT>(d + doff[k], v[k]);
+    }
+    // ragged tail
+#pragma unroll
+    for (int k = 0; k < UNROLL; ++k) {
+        const uint32_t u = base + k * nthreads;
+        if (u < n) {
+            const uint32_t row = __umulhi(u, magic);
+            const uint32_t col = u - row * row_units;
+            V v = ld<V, NT>(s + (uint64_t(row) * sstride + uint64_t(col) * sizeof(V)));
+            st<V, NT>(d + (uint64_t(row) * dstride + uint64_t(col) * sizeof(V)), v);
+        }
+    }
+}
+
+template <int UNROLL, int NT>
+__global__ __launch_bounds__(1024) void repack_copy_kernel(const Tile *__restrict__ tiles,
+                                                           uint32_t ntiles, PtrTable ptrs) {
+    const uint32_t tid = threadIdx.x, nthreads = blockDim.x;
+    for (uint32_t ti = blockIdx.x; ti < ntiles; ti += gridDim.x) {
+        const Tile t = tiles[ti];  // uniform address: scalar loads
+        const char *s = ptrs.p[t.src_buf] + t.src_off;
+        char *d = ptrs.p[t.dst_buf] + t.dst_off;
+        const uint32_t n = t.rows * t.row_units;
+        switch (t.vec_log2) {
+            case 4: copy_tile<u32x4, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
+            case 3: copy_tile<u32x2, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
+            case 2: copy_tile<uint32_t, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
+            case 1: copy_tile<uint16_t, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
+            default: copy_tile<uint8_t, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
+        }
+    }
+}
+
+// Transposing tiles: at most 64 x 64 elements of type E, staged through LDS.
+// dst[k][i] = src[i][k]; loads walk source rows, stores walk destination rows.
+template <typename E>
+__global__ __launch_bounds__(256) void repack_transpose_kernel(const Tile *__restrict__ tiles,
+                                                               uint32_t ntiles, PtrTable ptrs) {
+    constexpr int TD = kTransposeDim;
+    constexpr int PITCH = TD + (sizeof(E) >= 4 ? 1 : 2);  // keeps rows off a common bank
+    __shared__ E lds[TD * PITCH];
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t ti = blockIdx.x; ti < ntiles; ti += gridDim.x) {
+        const Tile t = tiles[ti];
+        const char *s = ptrs.p[t.src_buf] + t.src_off;
+        char *d = ptrs.p[t.dst_buf] + t.dst_off;
+        const uint32_t nr = t.rows, nc = t.row_units;
+        constexpr int VE = 16 / sizeof(E);  // elements per 16-byte access
+        const bool wide = sizeof(E) < 16 && (nr % VE == 0) && (nc % VE == 0) &&
+                          ((t.src_off | t.dst_off | t.src_stride | t.dst_stride) % 16 == 0);
+        if (wide) {
+            // load: unit = (row i, 16-byte column group)
+            const uint32_t upr = nc / VE;
+            for (uint32_t u = tid; u < nr * upr; u += 256) {
+                const uint32_t i = u / upr, kg = u - i * upr;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(s + uint64_t(i) * t.src_stride + kg * 16);
+                E e[VE];
+                __builtin_memcpy(e, &v, 16);
+#pragma unroll
+                for (int j = 0; j < VE; ++j) lds[i * PITCH + kg * VE + j] = e[j];
+            }
+            __syncthreads();
+            // store: unit = (destination row k, 16-byte group of i)
+            const uint32_t upo = nr / VE;
+            for (uint32_t u = tid; u < nc * upo; u += 256) {
+                const uint32_t k = u / upo, ig = u - k * upo;
+                E e[VE];
+#pragma unroll
+                for (int j = 0; j < VE; ++j) e[j] = lds[(ig * VE + j) * PITCH + k];
+                u32x4 v;
+                __builtin_memcpy(&v, e, 16);
+                *reinterpret_cast<u32x4 *>(d + uint64_t(k) * t.dst_stride + ig * 16) = v;
+            }
+        } else {
+            for (uint32_t u = tid; u < TD * TD; u += 256) {
+                const uint32_t i = u / TD, k = u % TD;
+                if (i < nr && k < nc)
+                    lds[i * PITCH + k] = *reinterpret_cast<const E *>(s + uint64_t(i) * t.src_stride + k * sizeof(E));
+            }
+            __syncthreads();
+            for (uint32_t u = tid; u < TD * TD; u += 256) {
+                const uint32_t k = u / TD, i = u % TD;
+                if (i < nr && k < nc)
+                    *reinterpret_cast<E *>(d + uint64_t(k) * t.dst_stride + i * sizeof(E)) = lds[i * PITCH + k];
+            }
+        }
+        __syncthreads();  // the tile buffer is reused by the next tile
+    }
+}
+
+template <int UNROLL, int NT>
+__global__ __launch_bounds__(1024) void plain_copy_kernel(const char *__restrict__ src,
+                                                          char *__restrict__ dst, uint64_t units) {
+    // grid-stride over 16-byte units, UNROLL loads in flight per lane
+    const uint64_t nthreads = uint64_t(gridDim.x) * blockDim.x;
+    uint64_t base = uint64_t(blockIdx.x) * blockDim.x * UNROLL + threadIdx.x;
+    const uint64_t step = nthreads * UNROLL;
+    for (; base < units; base += step) {
+        u32x4 v[UNROLL];
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const uint64_t u = base + uint64_t(k) * blockDim.x;
+            if (u < units) v[k] = ld<u32x4, NT>(src + u * 16);
+        }
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const uint64_t u = base + uint64_t(k) * blockDim.x;
+            if (u < units) st<u32x4, NT>(dst + u * 16, v[k]);
+        }
+    }
+}
+
+template <int U, int NT>
+void launch_copy_u_nt(dim3 grid, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n,
+                      const PtrTable &pt) {
+    hipLaunchKernelGGL((repack_copy_kernel<U, NT>), grid, block, 0, st, tiles, n, pt);
+}
+template <int U>
+void launch_copy_u(int nt, dim3 grid, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n,
+                   const PtrTable &pt) {
+    switch (nt & 3) {
+        case 0: launch_copy_u_nt<U, 0>(grid, block, st, tiles, n, pt); break;
+        case 1: launch_copy_u_nt<U, 1>(grid, block, st, tiles, n, pt); break;
+        case 2: launch_copy_u_nt<U, 2>(grid, block, st, tiles, n, pt); break;
+        default: launch_copy_u_nt<U, 3>(grid, block, st, tiles, n, pt); break;
+    }
+}
+void launch_copy(const Tuning &tn, dim3 grid, dim3 block, hipStream_t st, const Tile *tiles,
+                 uint32_t n, const PtrTable &pt) {
+    switch (tn.unroll) {
+        case 1: launch_copy_u<1>(tn.nontemporal, grid, block, st, tiles, n, pt); break;
+        case 2: launch_copy_u<2>(tn.nontemporal, grid, block, st, tiles, n, pt); break;
+        case 8: launch_copy_u<8>(tn.nontemporal, grid, block, st, tiles, n, pt); break;
+        default: launch_copy_u<4>(tn.nontemporal, grid, block, st, tiles, n, pt); break;
+    }
+}
+
+template <int U, int NT>
+void launch_plain_u_nt(dim3 grid, dim3 block, hipStream_t st, const char *s, char *d, uint64_t units) {
+    hipLaunchKernelGGL((plain_copy_kernel<U, NT>), grid, block, 0, st, s, d, units);
+}
+template <int U>
+void launch_plain_u(int nt, dim3 grid, dim3 block, hipStream_t st, const char *s, char *d, uint64_t units) {
+    switch (nt & 3) {
+        case 0: launch_plain_u_nt<U, 0>(grid, block, st, s, d, units); break;
+        case 1: launch_plain_u_nt<U, 1>(grid, block, st, s, d, units); break;
+        case 2: launch_plain_u_nt<U, 2>(grid, block, st, s, d, units); break;
+        default: launch_plain_u_nt<U, 3>(grid, block, st, s, d, units); break;
+    }
+}
+
+int hip_fail(hipError_t e, const char *what) {
+    return fail(RESHARD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+}  // namespace
+
+Tuning current_tuning() {
+    std::lock_guard<std::mutex> g(g_tuning_mutex);
+    return g_tuning;
+}
+
+// Uploads the tile table on first use; returns RESHARD_OK or an error code.
+int ensure_device_table(reshard_plan *plan) {
+    if (plan->d_tiles || plan->info.num_tiles == 0) {
+        if (plan->device < 0) {
+            int dev = 0;
+            if (hipError_t e = hipGetDevice(&dev)) return hip_fail(e, "hipGetDevice");
+            plan->device = dev;
+        }
+        if (plan->num_cus == 0) {
+            int cus = 0;
+            if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, plan->device))
+                return hip_fail(e, "hipDeviceGetAttribute");
+            plan->num_cus = cus;
+        }
+        return RESHARD_OK;
+    }
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return hip_fail(e, "hipGetDevice");
+    int cus = 0;
+    if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))
+        return hip_fail(e, "hipDeviceGetAttribute");
+    const size_t nc = plan->copy_tiles.size(), nt = plan->transpose_tiles.size();
+    void *mem = nullptr;
+    if (hipError_t e = hipMalloc(&mem, (nc + nt) * sizeof(Tile))) {
+        (void)hipGetLastError();
+        return fail(RESHARD_ERR_OOM, std::string("hipMalloc of the tile table: ") + hipGetErrorString(e));
+    }
+    hipError_t e = hipSuccess;
+    if (nc) e = hipMemcpy(mem, plan->copy_tiles.data(), nc * sizeof(Tile), hipMemcpyHostToDevice);
+    if (!e && nt)
+        e = hipMemcpy(static_cast<Tile *>(mem) + nc, plan->transpose_tiles.data(), nt * sizeof(Tile),
+                      hipMemcpyHostToDevice);
+    if (e) {
+        (void)hipFree(mem);
+        return hip_fail(e, "hipMemcpy of the tile table");
+    }
+    plan->d_tiles = mem;
+    plan->device = dev;
+    plan->num_cus = cus;
+    return RESHARD_OK;
+}
+
+int launch_repack(reshard_plan *plan, hipStream_t stream) {
+    const Tuning tn = current_tuning();
+    PtrTable pt;
+    std::memset(&pt, 0, sizeof pt);
+    const int ns = plan->info.num_src_bufs, nd = plan->info.num_dst_bufs;
+    for (int i = 0; i < ns; ++i) pt.p[i] = const_cast<char *>(static_cast<const char *>(plan->src_ptrs[i]));
+    for (int i = 0; i < nd; ++i) pt.p[ns + i] = static_cast<char *>(plan->dst_ptrs[i]);
+    const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
+    const uint32_t nc = uint32_t(plan->copy_tiles.size()), nt = uint32_t(plan->transpose_tiles.size());
+    const uint32_t wanted = uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu);
+    if (nc) {
+        dim3 grid(std::min(nc, wanted)), block(tn.block_threads);
+        launch_copy(tn, grid, block, stream, tiles, nc, pt);
+        if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
+    }
+    if (nt) {
+        dim3 grid(std::min(nt, wanted)), block(256);
+        const Tile *tt = tiles + nc;
+        switch (plan->spec.elem_bytes) {
+            case 1: hipLaunchKernelGGL(repack_transpose_kernel<uint8_t>, grid, block, 0, stream, tt, nt, pt); break;
+            case 2: hipLaunchKernelGGL(repack_transpose_kernel<uint16_t>, grid, block, 0, stream, tt, nt, pt); break;
+            case 4: hipLaunchKernelGGL(repack_transpose_kernel<uint32_t>, grid, block, 0, stream, tt, nt, pt); break;
+            default: hipLaunchKernelGGL(repack_transpose_kernel<uint64_t>, grid, block, 0, stream, tt, nt, pt); break;
+        }
+        if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the transpose kernel");
+    }
+    return RESHARD_OK;
+}
+
+}  // namespace reshard
+
+using namespace reshard;
+
+extern "C" int reshard_set_tuning(const reshard_tuning *t) {
+    Tuning n;  // defaults
+    if (t) {
+        if (t->tile_bytes) {
+            if (t->tile_bytes < 4096 || t->tile_bytes > 512 * 1024 || (t->tile_bytes & (t->tile_bytes - 1)))
+                return fail(RESHARD_ERR_INVALID_ARG, "tile_bytes must be a power of two in [4 KiB, 512 KiB]");
+            n.tile_bytes = t->tile_bytes;
+        }
+        if (t->block_threads) {
+            const int b = t->block_threads;
+            if (b != 64 && b != 128 && b != 256 && b != 512 && b != 1024)
+                return fail(RESHARD_ERR_INVALID_ARG, "block_threads must be 64, 128, 256, 512 or 1024");
+            n.block_threads = b;
+        }
+        if (t->blocks_per_cu) {
+            if (t->blocks_per_cu < 1 || t->blocks_per_cu > 64)
+                return fail(RESHARD_ERR_INVALID_ARG, "blocks_per_cu must be in [1, 64]");
+            n.blocks_per_cu = t->blocks_per_cu;
+        }
+        if (t->unroll) {
+            const int u = t->unroll;
+            if (u != 1 && u != 2 && u != 4 && u != 8) return fail(RESHARD_ERR_INVALID_ARG, "unroll must be 1, 2, 4 or 8");
+            n.unroll = u;
+        }
+        if (t->nontemporal < -1 || t->nontemporal > 3) return fail(RESHARD_ERR_INVALID_ARG, "nontemporal must be in [-1, 3]");
+        // 0 keeps the default like every other field; -1 asks for plain loads and stores
+        if (t->nontemporal > 0) n.nontemporal = t->nontemporal;
+        if (t->nontemporal == -1) n.nontemporal = 0;
+    }
+    std::lock_guard<std::mutex> g(g_tuning_mutex);
+    g_tuning = n;
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_get_tuning(reshard_tuning *out) {
+    if (!out) return fail(RESHARD_ERR_INVALID_ARG, "out is NULL");
+    const Tuning t = current_tuning();
+    out->tile_bytes = t.tile_bytes;
+    out->block_threads = t.block_threads;
+    out->blocks_per_cu = t.blocks_per_cu;
+    out->unroll = t.unroll;
+    out->nontemporal = t.nontemporal;
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_copy_baseline(void *dst, const void *src, int64_t bytes, void *stream) {
+    if (!dst || !src || bytes <= 0 || bytes % 16 || (reinterpret_cast<uintptr_t>(dst) % 16) ||
+        (reinterpret_cast<uintptr_t>(src) % 16))
+        return fail(RESHARD_ERR_INVALID_ARG, "copy_baseline needs 16-byte aligned pointers and a positive multiple of 16 bytes");
+    const Tuning tn = current_tuning();
+    int dev = 0, cus = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return hip_fail(e, "hipGetDevice");
+    if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))
+        return hip_fail(e, "hipDeviceGetAttribute");
+    const uint64_t units = uint64_t(bytes) / 16;
+    const uint64_t per_block = uint64_t(tn.block_threads) * tn.unroll;
+    const uint64_t blocks = std::min<uint64_t>((units + per_block - 1) / per_block, uint64_t(cus) * tn.blocks_per_cu);
+    dim3 grid{uint32_t(blocks)}, block{uint32_t(tn.block_threads)};
+    const char *s = static_cast<const char *>(src);
+    char *d = static_cast<char *>(dst);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    switch (tn.unroll) {
+        case 1: launch_plain_u<1>(tn.nontemporal, grid, block, st, s, d, units); break;
+        case 2: launch_plain_u<2>(tn.nontemporal, grid, block, st, s, d, units); break;
+        case 8: launch_plain_u<8>(tn.nontemporal, grid, block, st, s, d, units); break;
+        default: launch_plain_u<4>(tn.nontemporal, grid, block, st, s, d, units); break;
+    }
+    if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the plain copy kernel");
+    return RESHARD_OK;
+}

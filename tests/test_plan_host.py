@@ -1,0 +1,299 @@
+"""Host logic of the library, checked without a GPU.
+
+The plan builder's output (buffer tables, tensor tables, copy descriptors) is
+interpreted here by a few lines of numpy and compared with the CPU oracles.
+Nothing in this file launches a kernel; the interpreter below lives in the
+tests only and is not a product path.
+"""
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import np_pack
+from oracle import fast, locate
+from paper_2507_19017_amd import Plan, ReshardError, binding, get_tuning, set_tuning
+from synth_inputs import TINY, WORKLOADS, make_layout, make_spec
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SENT = 0xA5
+
+
+def with_eb(spec, eb):
+    s = dict(spec)
+    s["elem_bytes"] = eb
+    return s
+
+
+def run_descs(descs, src, dst, counts=None):
+    """Interpret the descriptor table on byte arrays, exactly as reshard.h words it."""
+    for d in descs:
+        s, t = src[d["src_buf"]], dst[d["dst_buf"]]
+        eb = d["elem_bytes"]
+        if d["kind"] == 0:
+            for i in range(d["rows"]):
+                a, b = d["src_off"] + i * d["src_stride"], d["dst_off"] + i * d["dst_stride"]
+                t[b:b + d["row_bytes"]] = s[a:a + d["row_bytes"]]
+                if counts is not None:
+                    counts[d["dst_buf"]][b:b + d["row_bytes"]] += 1
+        else:
+            cols = d["row_bytes"] // eb
+            for i in range(d["rows"]):
+                for k in range(cols):
+                    a = d["src_off"] + i * d["src_stride"] + k * eb
+                    b = d["dst_off"] + k * d["dst_stride"] + i * eb
+                    t[b:b + eb] = s[a:a + eb]
+                    if counts is not None:
+                        counts[d["dst_buf"]][b:b + eb] += 1
+
+
+CASES = [(n, eb) for n in sorted(TINY) for eb in (1, 2, 4, 8)]
+
+
+@pytest.mark.parametrize("name,eb", CASES)
+def test_descriptors_reproduce_the_oracle_on_tiny_models(name, eb):
+    w = TINY[name]
+    spec = with_eb(w["spec"], eb)
+    plan = Plan(spec, w["src"], w["dst"])
+    S = locate.Layout(spec, w["src"])
+    D = locate.Layout(spec, w["dst"])
+    assert plan.buf_bytes(0) == S.buf_bytes and plan.buf_bytes(1) == D.buf_bytes
+    assert plan.buf_used(1) == [D.buffer_used(b) for b in range(D.nbufs)]
+    rng = np.random.default_rng(w["seed"] + eb)
+    src = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in S.buf_bytes]
+    dst = [np.full(n, SENT, dtype=np.uint8) for n in D.buf_bytes]
+    cnt = [np.zeros(n, dtype=np.int32) for n in D.buf_bytes]
+    run_descs(plan.descs(), src, dst, cnt)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    want = [np.full(n, SENT, dtype=np.uint8) if D.buffer_used(b) else None for b, n in enumerate(D.buf_bytes)]
+    read = locate.reshard_definition(spec, w["src"], w["dst"], [s.view(dt) for s in src],
+                                     [x.view(dt) if x is not None else None for x in want])
+    total = 0
+    for b in range(D.nbufs):
+        if want[b] is None:
+            assert np.all(dst[b] == SENT) and not cnt[b].any()
+            continue
+        assert np.array_equal(dst[b], want[b]), f"buffer {b}"
+        owned = np.zeros(D.buf_bytes[b], dtype=bool)
+        for _, _, _, off, nb in D.stored[b]:
+            owned[off:off + nb] = True
+        assert np.all(cnt[b][owned] == 1) and np.all(cnt[b][~owned] == 0)  # exactly once, pads never
+        total += int(owned.sum())
+    assert plan.info()["bytes_moved"] == total
+    assert {i for i, u in enumerate(plan.buf_used(0)) if u} == read
+
+
+@pytest.mark.parametrize("pair", ["identity", "back"])
+@pytest.mark.parametrize("name", sorted(TINY))
+def test_identity_and_way_back_plans(name, pair):
+    w = TINY[name]
+    spec = with_eb(w["spec"], 2)
+    train = w["src"]
+    gen = dict(w["dst"], tp_filter=-1, ep_filter=-1)
+    a, b = (train, train) if pair == "identity" else (gen, train)
+    plan = Plan(spec, a, b)
+    A, B = locate.Layout(spec, a), locate.Layout(spec, b)
+    rng = np.random.default_rng(3)
+    lg = np_pack.make_logical(spec, locate.logical_tensors(spec), rng, np.uint16)
+    src = [x.view(np.uint8) for x in np_pack.pack(spec, a, lg, np.uint16, 0xA5A5)]
+    want = [x.view(np.uint8) for x in np_pack.pack(spec, b, lg, np.uint16, 0xA5A5)]
+    dst = [np.full(n, SENT, dtype=np.uint8) for n in B.buf_bytes]
+    run_descs(plan.descs(), src, dst)
+    for x, y in zip(dst, want):
+        assert np.array_equal(x, y)
+    if pair == "identity":
+        # one contiguous run per stored tensor at most: nothing is cut finer than a tensor
+        assert all(d["kind"] == 0 for d in plan.descs())
+
+
+def test_tensor_table_matches_the_oracle_layout():
+    for w in list(TINY.values()) + [WORKLOADS["C0"], WORKLOADS["C1"], WORKLOADS["C4"]]:
+        plan = Plan(w["spec"], w["src"], w["dst"])
+        for side, lay in ((0, w["src"]), (1, w["dst"])):
+            L = locate.Layout(w["spec"], lay)
+            got = [(t["buffer"], t["name"], t["layer"], t["offset"], t["bytes"]) for t in plan.tensors(side)]
+            want = [(b, n, l, off, nb) for b in range(L.nbufs) for (n, l, j, off, nb) in L.stored[b]]
+            assert got == want
+            for t in plan.tensors(side):
+                assert t["replicated"] == (t["name"] in locate.REPLICATED)
+                assert t["offset"] % 256 == 0
+
+
+@pytest.mark.parametrize("name", ["C0", "C1", "C2", "C3", "C3P", "C4"])
+def test_full_size_plans_cover_every_destination_byte_once(name):
+    """Interval analysis at the benchmark shapes: the destination intervals of all
+    descriptor rows are pairwise disjoint and their union is exactly the stored
+    tensors of the used buffers (so pads are never written and no byte twice);
+    source rows stay inside their buffers."""
+    w = WORKLOADS[name]
+    plan = Plan(w["spec"], w["src"], w["dst"])
+    D = locate.Layout(w["spec"], w["dst"])
+    S = locate.Layout(w["spec"], w["src"])
+    assert plan.buf_bytes(0) == S.buf_bytes and plan.buf_bytes(1) == D.buf_bytes
+    starts, ends = {}, {}
+    moved = 0
+    for d in plan.descs():
+        moved += d["rows"] * d["row_bytes"]
+        eb = d["elem_bytes"]
+        if d["kind"] == 0:
+            n, nb, st = d["rows"], d["row_bytes"], d["dst_stride"]
+        else:  # destination side of a transposing descriptor: one row per source column
+            n, nb, st = d["row_bytes"] // eb, d["rows"] * eb, d["dst_stride"]
+        shi = d["src_off"] + (d["rows"] - 1) * d["src_stride"] + d["row_bytes"]
+        assert 0 <= d["src_off"] and shi <= S.buf_bytes[d["src_buf"]]
+        assert n >= 1 and nb >= 1 and (n == 1 or st >= nb)
+        if n > 1 and st == nb:
+            n, nb = 1, n * nb
+        a = d["dst_off"] + st * np.arange(n, dtype=np.int64)
+        starts.setdefault(d["dst_buf"], []).append(a)
+        ends.setdefault(d["dst_buf"], []).append(a + nb)
+    assert moved == plan.info()["bytes_moved"]
+    total = 0
+    for b in range(D.nbufs):
+        if not D.buffer_used(b):
+            assert b not in starts
+            continue
+        a = np.concatenate(starts[b])
+        e = np.concatenate(ends[b])
+        order = np.argsort(a, kind="stable")
+        a, e = a[order], e[order]
+        assert np.all(a[1:] >= e[:-1]), "two descriptor rows overlap"
+        # union of the written intervals, merged where they touch
+        brk = np.flatnonzero(a[1:] != e[:-1])
+        ua = np.concatenate([a[:1], a[brk + 1]])
+        ue = np.concatenate([e[brk], e[-1:]])
+        # union of the stored tensors, merged where they touch
+        ta = np.array([off for *_, off, nb in D.stored[b]], dtype=np.int64)
+        te = ta + np.array([nb for *_, off, nb in D.stored[b]], dtype=np.int64)
+        tb = np.flatnonzero(ta[1:] != te[:-1])
+        wa = np.concatenate([ta[:1], ta[tb + 1]])
+        we = np.concatenate([te[tb], te[-1:]])
+        assert np.array_equal(ua, wa) and np.array_equal(ue, we)
+        total += int((te - ta).sum())
+    assert moved == total
+
+
+def test_sampled_descriptor_rows_agree_with_the_definition_oracle_at_full_size():
+    """For C1 and C3: pick random logical elements, find the descriptor row that writes
+    their destination byte, and check it reads the oracle's source byte."""
+    rng = np.random.default_rng(9)
+    for name in ("C1", "C3"):
+        w = WORKLOADS[name]
+        plan = Plan(w["spec"], w["src"], w["dst"])
+        descs = plan.descs()
+        sb, so, db, do = locate.sample_pairs(w["spec"], w["src"], w["dst"], 6, rng, max_tensors=400)
+        by_buf = {}
+        for d in descs:
+            by_buf.setdefault(d["dst_buf"], []).append(d)
+        for b in by_buf:
+            by_buf[b].sort(key=lambda d: d["dst_off"])
+        for a, ao, b, bo in zip(sb, so, db, do):
+            hit = None
+            for d in by_buf[int(b)]:
+                eb = d["elem_bytes"]
+                if d["kind"] == 0:
+                    span = (d["rows"] - 1) * d["dst_stride"] + d["row_bytes"]
+                    if not (d["dst_off"] <= bo < d["dst_off"] + span):
+                        continue
+                    i, rem = divmod(int(bo) - d["dst_off"], d["dst_stride"])
+                    if rem < d["row_bytes"]:
+                        hit = (d["src_buf"], d["src_off"] + i * d["src_stride"] + rem)
+                        break
+                else:
+                    cols = d["row_bytes"] // eb
+                    span = (cols - 1) * d["dst_stride"] + d["rows"] * eb
+                    if not (d["dst_off"] <= bo < d["dst_off"] + span):
+                        continue
+                    k, rem = divmod(int(bo) - d["dst_off"], d["dst_stride"])
+                    if rem < d["rows"] * eb:
+                        i = rem // eb
+                        hit = (d["src_buf"], d["src_off"] + i * d["src_stride"] + k * eb)
+                        break
+            assert hit == (int(a), int(ao)), (name, int(b), int(bo))
+
+
+def test_invalid_requests_return_error_codes():
+    spec = dict(WORKLOADS["C0"]["spec"])
+    gen = make_layout(kind="gen", tp=1)
+    cases = [
+        (spec, make_layout(kind="train", tp=3), gen, binding.ERR_UNSUPPORTED),   # heads % tp
+        (spec, make_layout(kind="train", tp=4), gen, binding.ERR_UNSUPPORTED),   # tp > nkv
+        (spec, make_layout(kind="train", tp=2, pp=3), gen, binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2), make_layout(kind="gen", tp=1, pp=2), binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2, ep=2), gen, binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2, tp_filter=0), gen, binding.ERR_INVALID_ARG),
+        (spec, make_layout(kind="train", tp=2), make_layout(kind="gen", tp=1, tp_filter=1), binding.ERR_INVALID_ARG),
+        (dict(spec, elem_bytes=3), make_layout(kind="train", tp=2), gen, binding.ERR_INVALID_ARG),
+        (dict(spec, V=1023), make_layout(kind="train", tp=2), gen, binding.ERR_UNSUPPORTED),
+        (dict(spec, L=0), make_layout(kind="train", tp=2), gen, binding.ERR_INVALID_ARG),
+    ]
+    for s, a, b, code in cases:
+        with pytest.raises(ReshardError) as e:
+            Plan(s, a, b)
+        assert e.value.code == code, (a, b, e.value)
+        assert binding.last_error()
+    # too many buffers
+    big = make_spec(family="moe_gqa", L=4, H=64, nq=4, nkv=4, d=8, V=64, E=512, Ie=8)
+    with pytest.raises(ReshardError) as e:
+        Plan(big, make_layout(kind="train", ep=512), make_layout(kind="gen", ep=1))
+    assert e.value.code == binding.ERR_UNSUPPORTED
+    # struct_size mismatch and NULLs through the raw ABI
+    l = binding.lib()
+    s, a, b = binding.make_spec(spec), binding.make_layout(make_layout(kind="train", tp=2)), binding.make_layout(gen)
+    out = C.c_void_p()
+    s.struct_size = 4
+    assert l.reshard_plan_create(C.byref(s), C.byref(a), C.byref(b), C.byref(out)) == binding.ERR_INVALID_ARG
+    assert l.reshard_plan_create(None, C.byref(a), C.byref(b), C.byref(out)) == binding.ERR_INVALID_ARG
+    assert l.reshard_plan_destroy(None) == 0
+
+
+def test_state_machine_errors_without_a_device():
+    """Calls that need bound pointers are refused before any HIP call is made."""
+    w = WORKLOADS["C0"]
+    plan = Plan(w["spec"], w["src"], w["dst"])
+    assert plan.mem_stats() == dict(src_live=0, dst_live=0, host_pinned=0, peak_device=0, released=0, state="unbound")
+    for call in (plan.swap_out, plan.swap_in, plan.mark_src_released):
+        with pytest.raises(ReshardError) as e:
+            call()
+        assert e.value.code == binding.ERR_BAD_STATE
+    with pytest.raises(ReshardError) as e:
+        plan.execute([0, 0], [0])
+    assert e.value.code == binding.ERR_INVALID_ARG  # NULL pointers for used buffers
+    with pytest.raises(ReshardError) as e:
+        plan.execute([256, 512 + 8], [4096])
+    assert e.value.code == binding.ERR_INVALID_ARG  # misaligned
+    with pytest.raises(ReshardError) as e:
+        plan.execute([1 << 20, 1 << 30], [(1 << 20) + 256])
+    assert e.value.code == binding.ERR_INVALID_ARG  # overlap
+    plan.swap_wait()  # no-op
+    plan.release_host()
+    assert plan.host_copy(0) == 0
+
+
+def test_tuning_is_validated():
+    set_tuning()
+    base = get_tuning()
+    assert base == dict(tile_bytes=131072, block_threads=256, blocks_per_cu=8, unroll=4, nontemporal=3)
+    set_tuning(tile_bytes=65536, unroll=8)
+    assert get_tuning()["tile_bytes"] == 65536 and get_tuning()["unroll"] == 8
+    w = WORKLOADS["C1"]
+    n64 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
+    set_tuning()
+    n128 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
+    assert n64 > 1.8 * n128
+    for bad in (dict(tile_bytes=1000), dict(block_threads=96), dict(unroll=3), dict(blocks_per_cu=100)):
+        with pytest.raises(ReshardError):
+            set_tuning(**bad)
+    assert get_tuning() == base
+
+
+def test_library_exports_every_symbol_the_header_declares():
+    text = open(os.path.join(ROOT, "include", "reshard.h")).read()
+    declared = set(re.findall(r"\b(reshard_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    l = binding.lib()
+    for name in sorted(declared):
+        assert getattr(l, name) is not None
