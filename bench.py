@@ -126,6 +126,7 @@ def main():
     stream = torch.cuda.current_stream()
     h = stream.cuda_stream
     src_bytes = sum(n for n, u in zip(sizes_s, used_s) if u)
+    plan.bind_src(ptrs(src))
     torch.cuda.reset_peak_memory_stats()
 
     kernel_ms, out_s, in_s, freed = [], [], [], []
