@@ -60,11 +60,11 @@ constexpr int kMaxTileUnits = 32768;  // keeps the multiply-high row split exact
 constexpr int kTransposeDim = 64;     // transposing tiles are at most 64 x 64 elements
 
 struct Tuning {
-    int tile_bytes = 128 * 1024;
-    int block_threads = 256;
-    int blocks_per_cu = 8;
-    int unroll = 4;
-    int nontemporal = 3;
+    int tile_bytes = 256 * 1024;  // two rounds of block_threads * unroll * 16 bytes
+    int block_threads = 1024;
+    int blocks_per_cu = 0;        // 0: one tile per workgroup; > 0: persistent grid
+    int unroll = 8;
+    int flags = 7;                // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts
 };
 Tuning current_tuning();
 

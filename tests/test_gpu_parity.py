@@ -73,11 +73,13 @@ def test_identity_and_round_trip_on_device(name):
 
 
 TUNINGS = [
-    dict(tile_bytes=4096, block_threads=64, unroll=1, nontemporal=-1),
-    dict(tile_bytes=8192, block_threads=128, unroll=2, nontemporal=1),
-    dict(tile_bytes=32768, block_threads=512, unroll=8, nontemporal=2),
+    dict(tile_bytes=4096, block_threads=64, unroll=1, flags=-1),
+    dict(tile_bytes=8192, block_threads=128, unroll=2, flags=1),
+    dict(tile_bytes=32768, block_threads=512, unroll=8, flags=2),
+    dict(tile_bytes=16384, block_threads=256, unroll=16, flags=4),
     dict(tile_bytes=524288, block_threads=1024, unroll=4, blocks_per_cu=1),
-    dict(tile_bytes=65536, block_threads=256, unroll=8, blocks_per_cu=16),
+    dict(tile_bytes=65536, block_threads=256, unroll=8, blocks_per_cu=16, flags=7),
+    dict(tile_bytes=131072, block_threads=1024, unroll=16, flags=7),
 ]
 
 
