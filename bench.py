@@ -145,10 +145,9 @@ def main():
             t1 = time.perf_counter()
             plan.mark_src_released()
             before = torch.cuda.memory_allocated()
-            src = None
-            torch.cuda.empty_cache()
+            src = None                  # the training copy goes back to the allocator
             after = torch.cuda.memory_allocated()
-            src = alloc_src(False)      # "before the next update": new device home
+            src = alloc_src(False)      # "before the next update": a device home again
             plan.bind_src(ptrs(src))
             t2 = time.perf_counter()
             plan.swap_in(h)
@@ -170,6 +169,26 @@ def main():
         step(True)
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_begin
+
+    # untimed: the same release, this time all the way back to the driver, to show the
+    # HBM really becomes free (a fresh allocation is slow on first touch, which is
+    # why the timed steps above recycle the allocator's blocks instead)
+    driver_freed = None
+    if not a.no_swap:
+        check = [None if s is None else int(s[::4099].to(torch.int64).sum()) for s in src]
+        plan.swap_out(h)
+        plan.swap_wait()
+        plan.mark_src_released()
+        free0 = torch.cuda.mem_get_info()[0]
+        src = None
+        torch.cuda.empty_cache()
+        driver_freed = torch.cuda.mem_get_info()[0] - free0
+        src = alloc_src(False)
+        plan.bind_src(ptrs(src))
+        plan.swap_in(h)
+        plan.swap_wait()
+        torch.cuda.synchronize()
+        assert check == [None if s is None else int(s[::4099].to(torch.int64).sum()) for s in src], "swap round trip changed the weights"
 
     moved = info["bytes_moved"]
     k_avg = sum(kernel_ms) / len(kernel_ms) / 1e3
@@ -214,7 +233,8 @@ def main():
                      "plain_copy_GBps": round(plain_gbps, 1)},
         "pct_hbm_peak": round(100 * repack_gbps / HBM_PEAK_GBPS, 2),
         "peak_hbm_bytes": {"ledger": stats["peak_device"], "torch_max_allocated": peak_torch,
-                           "freed_after_swap_out": (sum(freed) // len(freed)) if freed else None},
+                           "freed_after_swap_out": (sum(freed) // len(freed)) if freed else None,
+                           "returned_to_driver_after_swap_out": driver_freed},
     }
     if not a.no_swap:
         so, si = sum(out_s) / len(out_s), sum(in_s) / len(in_s)
