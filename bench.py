@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the resharding hot path on one MI355X.
 
-One step = one pass of the whole path over one workload: swap-out of the
-training-side buffers (device-to-host, on the library's side stream) overlapped
-with the repack kernel, release of the training copy, re-allocation, swap-in
-(host-to-device).  Inputs are synthetic and already resident in HBM when the
+One step = one pass of the whole path over one workload: the repack kernel,
+swap-out of the training-side buffers (device-to-host, on the library's side
+stream; --overlap queues it before the repack so the two run concurrently),
+release of the training copy, re-allocation, swap-in (host-to-device).  Inputs are synthetic and already resident in HBM when the
 timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1]
@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C1", help="C0, C1, C2, C3, C3P or C4")
     ap.add_argument("--no-swap", action="store_true", help="time the repack alone (not a valid headline run)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="queue the swap-out before the repack so the two overlap (under rocprofv3 the runtime "
+                         "copies with shader kernels instead of the DMA engines, which starves the repack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--tuning", default="", help="e.g. tile_bytes=65536,unroll=8")
@@ -135,12 +138,14 @@ def main():
         nonlocal src
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
-        if not a.no_swap:
-            plan.swap_out(h)            # D2H starts now on the side stream ...
+        if a.overlap and not a.no_swap:
+            plan.swap_out(h)            # D2H starts now on the side stream and overlaps the repack
         e0.record(stream)
-        plan.execute(ptrs(src), ptrs(dst), h)   # ... and overlaps the repack
+        plan.execute(ptrs(src), ptrs(dst), h)
         e1.record(stream)
         if not a.no_swap:
+            if not a.overlap:
+                plan.swap_out(h)        # D2H starts when the repack queued above has finished
             plan.swap_wait()
             t1 = time.perf_counter()
             plan.mark_src_released()
@@ -211,7 +216,7 @@ def main():
     plain_gbps = 2 * cp_n / (min(x.elapsed_time(y) for x, y in evs[1:]) / 1e3) / 1e9
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "repack_hbm_traffic.json")  # from rocprofv3 --pmc runs
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(a.workload)
 
@@ -226,7 +231,8 @@ def main():
         "dtype": "u16", "data": "synthetic",
         "config": {"workload": "%s: %s" % (wl["name"], wl["note"]), "bytes_moved_one_way": moved,
                    "src_buffers": sum(used_s), "dst_buffers": sum(used_d),
-                   "descriptors": info["num_descs"], "tiles": info["num_tiles"], "tuning": get_tuning()},
+                   "descriptors": info["num_descs"], "tiles": info["num_tiles"], "tuning": get_tuning(),
+                   "swap_overlaps_repack": bool(a.overlap and not a.no_swap)},
         "roofline": {"bound": "hbm", "achieved": round(repack_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(repack_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "kernel_ms_avg": round(k_avg * 1e3, 4), "kernel_ms_min": round(min(kernel_ms), 4),
