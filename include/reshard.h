@@ -137,7 +137,7 @@ typedef struct reshard_plan_info {
     int32_t num_src_bufs, num_dst_bufs;
     int64_t num_descs;      /* copy descriptors after merging */
     int64_t num_tiles;      /* device work items the descriptors were cut into */
-    int64_t num_transpose_tiles;
+    int64_t num_transpose_tiles; /* of which transposing tiles (register path + generic path) */
     int64_t bytes_moved;    /* destination bytes written by one execute (== bytes read) */
     int64_t table_bytes;    /* device memory held by the plan (tile table) */
 } reshard_plan_info;
@@ -171,6 +171,8 @@ typedef struct reshard_tuning {
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
                                barrier between a tile's load burst and its store burst (default 7);
                                -1 = none of them */
+    int32_t transpose_rows; /* shape of a register-transposed tile of 2-byte elements: source rows */
+    int32_t transpose_cols; /* ... and source columns; each 64, 128 or 256 (default 256 x 256) */
 } reshard_tuning;
 
 /* Thread-local message of the last failing call on this thread ("" if none). */

@@ -58,7 +58,7 @@ class MemStats(C.Structure):
 
 
 class Tuning(C.Structure):
-    _fields_ = [(k, C.c_int32) for k in ("tile_bytes", "block_threads", "blocks_per_cu", "unroll", "flags")]
+    _fields_ = [(k, C.c_int32) for k in ("tile_bytes", "block_threads", "blocks_per_cu", "unroll", "flags", "transpose_rows", "transpose_cols")]
 
 
 class ReshardError(RuntimeError):
@@ -137,7 +137,7 @@ def version() -> str:
 
 
 def set_tuning(**kw) -> None:
-    """tile_bytes, block_threads, blocks_per_cu, unroll, flags; no argument = defaults."""
+    """tile_bytes, block_threads, blocks_per_cu, unroll, flags, transpose_rows, transpose_cols; no argument = defaults."""
     if not kw:
         _check(lib().reshard_set_tuning(None))
         return

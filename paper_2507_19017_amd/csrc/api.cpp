@@ -141,19 +141,23 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
             return fail(RESHARD_ERR_UNSUPPORTED, "source plus destination buffers exceed RESHARD_MAX_BUFFERS");
         }
         if (int rc = compile_descriptors(*spec, p->src, p->dst, p->descs)) { delete p; return rc; }
-        if (int rc = cut_tiles(p->descs, ns, current_tuning().tile_bytes, p->copy_tiles, p->transpose_tiles)) {
+        const Tuning tuning = current_tuning();
+        p->fast_rows = tuning.transpose_rows;
+        p->fast_cols = tuning.transpose_cols;
+        if (int rc = cut_tiles(p->descs, ns, tuning, p->copy_tiles, p->fast_transpose_tiles, p->transpose_tiles)) {
             delete p;
             return rc;
         }
-        if (p->copy_tiles.size() > 0xFFFFFFF0ull || p->transpose_tiles.size() > 0xFFFFFFF0ull) {
+        if (p->copy_tiles.size() > 0x7FFFFFF0ull || p->transpose_tiles.size() > 0x7FFFFFF0ull ||
+            p->fast_transpose_tiles.size() > 0x7FFFFFF0ull) {
             delete p;
             return fail(RESHARD_ERR_UNSUPPORTED, "too many tiles");
         }
         p->info.num_src_bufs = ns;
         p->info.num_dst_bufs = nd;
         p->info.num_descs = int64_t(p->descs.size());
-        p->info.num_tiles = int64_t(p->copy_tiles.size() + p->transpose_tiles.size());
-        p->info.num_transpose_tiles = int64_t(p->transpose_tiles.size());
+        p->info.num_transpose_tiles = int64_t(p->transpose_tiles.size() + p->fast_transpose_tiles.size());
+        p->info.num_tiles = int64_t(p->copy_tiles.size()) + p->info.num_transpose_tiles;
         int64_t moved = 0;
         for (const reshard_desc &d : p->descs) moved += d.rows * d.row_bytes;
         p->info.bytes_moved = moved;

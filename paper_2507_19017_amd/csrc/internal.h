@@ -65,6 +65,8 @@ struct Tuning {
     int blocks_per_cu = 0;        // 0: one tile per workgroup; > 0: persistent grid
     int unroll = 8;
     int flags = 7;                // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts
+    int transpose_rows = 256;     // register-transposed tiles of 2-byte elements: rows x cols of the source
+    int transpose_cols = 256;
 };
 Tuning current_tuning();
 
@@ -75,8 +77,9 @@ int fail(int code, const std::string &msg);
 int build_side(const reshard_model_spec &spec, const reshard_layout &lay, bool is_source, Side &out);
 int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
                         std::vector<reshard_desc> &descs);
-int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, int tile_bytes,
-              std::vector<Tile> &copy_tiles, std::vector<Tile> &transpose_tiles);
+int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
+              std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
+              std::vector<Tile> &transpose_tiles);
 
 }  // namespace reshard
 
@@ -84,12 +87,14 @@ struct reshard_plan {
     reshard_model_spec spec{};
     reshard::Side src, dst;
     std::vector<reshard_desc> descs;
-    std::vector<reshard::Tile> copy_tiles, transpose_tiles;
+    // copy tiles; full tiles of 2-byte transposes (register path); remaining transposing tiles
+    std::vector<reshard::Tile> copy_tiles, fast_transpose_tiles, transpose_tiles;
+    int fast_rows = 0, fast_cols = 0;  // tile shape the fast tiles were cut with
     reshard_plan_info info{};
 
     // device side (created lazily by the first execute)
     int device = -1;
-    void *d_tiles = nullptr;  // copy tiles followed by transposing tiles
+    void *d_tiles = nullptr;  // copy tiles, then fast transposing tiles, then generic transposing tiles
     int num_cus = 0;
 
     // bound pointers

@@ -389,9 +389,12 @@ int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
     return RESHARD_OK;
 }
 
-int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, int tile_bytes,
-              std::vector<Tile> &copy_tiles, std::vector<Tile> &transpose_tiles) {
+int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
+              std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
+              std::vector<Tile> &transpose_tiles) {
+    const int tile_bytes = tuning.tile_bytes;
     copy_tiles.clear();
+    fast_transpose_tiles.clear();
     transpose_tiles.clear();
     auto fits32 = [](int64_t v) { return v >= 0 && v <= 0xFFFFFFFFll; };
     for (const reshard_desc &d : descs) {
@@ -408,9 +411,28 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, int tile
             const int64_t cols = d.row_bytes / d.elem_bytes;
             t.kind = 1;
             t.vec_log2 = uint8_t(lg);
+            // the interior, in full tiles, goes to the register-transpose kernel when the
+            // elements are 2 bytes and every row start allows 16-byte accesses
+            int64_t fi = 0, fk = 0;
+            if (d.elem_bytes == 2 && (d.src_off | d.dst_off | d.src_stride | d.dst_stride) % 16 == 0) {
+                const int64_t TI = tuning.transpose_rows, TK = tuning.transpose_cols;
+                fi = d.rows / TI * TI;
+                fk = cols / TK * TK;
+                if (fi == 0 || fk == 0) fi = fk = 0;
+                for (int64_t i = 0; i < fi; i += TI)
+                    for (int64_t k = 0; k < fk; k += TK) {
+                        t.rows = uint32_t(TI);
+                        t.row_units = uint32_t(TK);
+                        t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
+                        t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
+                        fast_transpose_tiles.push_back(t);
+                    }
+            }
+            // the rest (edges, other element sizes, odd alignment): small generic tiles
             for (int64_t i = 0; i < d.rows; i += kTransposeDim)
-                for (int64_t k = 0; k < cols; k += kTransposeDim) {
-                    t.rows = uint32_t(std::min<int64_t>(kTransposeDim, d.rows - i));
+                for (int64_t k = (i < fi ? fk : 0); k < cols; k += kTransposeDim) {
+                    const int64_t i_end = i < fi ? std::min<int64_t>(fi, d.rows) : d.rows;
+                    t.rows = uint32_t(std::min<int64_t>(kTransposeDim, i_end - i));
                     t.row_units = uint32_t(std::min<int64_t>(kTransposeDim, cols - k));
                     t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
                     t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);

@@ -180,6 +180,59 @@ __global__ __launch_bounds__(256) void repack_transpose_kernel(const Tile *__res
     }
 }
 
+// Full TI x TK tiles of 2-byte elements, dst[k][i] = src[i][k].  Each lane loads an
+// 8 x 8 block (8 rows x 16 bytes, lanes adjacent along the source row), transposes it
+// in registers, and parks the 8 transposed 16-byte rows in LDS; after a barrier the
+// lanes read 16-byte chunks back along destination rows and store them.  Every
+// global and LDS access is 16 bytes wide.  LDS holds the tile as [k][i] with the
+// 16-byte chunks of a row XOR-swizzled by (k / 8) so that neither the writes (lanes
+// 8 rows apart) nor the reads (lanes along a row) pile onto one bank group.
+template <int TI, int TK>
+__global__ __launch_bounds__((TI * TK / 64) < 1024 ? (TI * TK / 64) : 1024)
+void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, PtrTable ptrs) {
+    constexpr int THREADS = (TI * TK / 64) < 1024 ? (TI * TK / 64) : 1024;
+    constexpr int BLOCKS = TI / 8 * (TK / 8);      // 8 x 8 blocks in a tile
+    constexpr int ROUNDS = BLOCKS / THREADS;
+    constexpr int KB = TK / 8, IC = TI / 8;        // blocks along k; 16-byte chunks per LDS row
+    static_assert(BLOCKS % THREADS == 0 && IC >= 8, "tile shape");
+    __shared__ u32x4 lds[TK * IC];
+    const Tile t = tiles[blockIdx.x];
+    const char *s = ptrs.p[t.src_buf] + t.src_off;
+    char *d = ptrs.p[t.dst_buf] + t.dst_off;
+    const uint32_t tid = threadIdx.x;
+    u32x4 r[ROUNDS][8];
+#pragma unroll
+    for (int q = 0; q < ROUNDS; ++q) {
+        const uint32_t b = tid + q * THREADS, kb = b % KB, ib = b / KB;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            r[q][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(s + uint64_t(ib * 8 + j) * t.src_stride + kb * 16));
+    }
+#pragma unroll
+    for (int q = 0; q < ROUNDS; ++q) {
+        const uint32_t b = tid + q * THREADS, kb = b % KB, ib = b / KB;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            // transposed row c of the block: elements (i0..i0+7, k0+c)
+            u32x4 o;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t x = r[q][2 * m][c >> 1], y = r[q][2 * m + 1][c >> 1];
+                o[m] = (c & 1) ? ((x >> 16) | (y & 0xFFFF0000u)) : ((x & 0xFFFFu) | (y << 16));
+            }
+            const uint32_t k = kb * 8 + c;
+            lds[k * IC + (ib ^ (kb & 7))] = o;     // (k >> 3) == kb
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < ROUNDS * 8; ++q) {
+        const uint32_t u = tid + q * THREADS, ic = u % IC, k = u / IC;
+        const u32x4 v = lds[k * IC + (ic ^ ((k >> 3) & 7))];
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d + uint64_t(k) * t.dst_stride + ic * 16));
+    }
+}
+
 template <int UNROLL, int NT>
 __global__ __launch_bounds__(1024) void plain_copy_kernel(const char *__restrict__ src,
                                                           char *__restrict__ dst, uint64_t units) {
@@ -281,20 +334,22 @@ int ensure_device_table(reshard_plan *plan) {
     int cus = 0;
     if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))
         return hip_fail(e, "hipDeviceGetAttribute");
-    const size_t nc = plan->copy_tiles.size(), nt = plan->transpose_tiles.size();
+    const std::vector<Tile> *lists[3] = {&plan->copy_tiles, &plan->fast_transpose_tiles, &plan->transpose_tiles};
+    size_t total = 0;
+    for (auto *l : lists) total += l->size();
     void *mem = nullptr;
-    if (hipError_t e = hipMalloc(&mem, (nc + nt) * sizeof(Tile))) {
+    if (hipError_t e = hipMalloc(&mem, total * sizeof(Tile))) {
         (void)hipGetLastError();
         return fail(RESHARD_ERR_OOM, std::string("hipMalloc of the tile table: ") + hipGetErrorString(e));
     }
-    hipError_t e = hipSuccess;
-    if (nc) e = hipMemcpy(mem, plan->copy_tiles.data(), nc * sizeof(Tile), hipMemcpyHostToDevice);
-    if (!e && nt)
-        e = hipMemcpy(static_cast<Tile *>(mem) + nc, plan->transpose_tiles.data(), nt * sizeof(Tile),
-                      hipMemcpyHostToDevice);
-    if (e) {
-        (void)hipFree(mem);
-        return hip_fail(e, "hipMemcpy of the tile table");
+    size_t at = 0;
+    for (auto *l : lists) {
+        if (l->empty()) continue;
+        if (hipError_t e = hipMemcpy(static_cast<Tile *>(mem) + at, l->data(), l->size() * sizeof(Tile), hipMemcpyHostToDevice)) {
+            (void)hipFree(mem);
+            return hip_fail(e, "hipMemcpy of the tile table");
+        }
+        at += l->size();
     }
     plan->d_tiles = mem;
     plan->device = dev;
@@ -310,7 +365,8 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     for (int i = 0; i < ns; ++i) pt.p[i] = const_cast<char *>(static_cast<const char *>(plan->src_ptrs[i]));
     for (int i = 0; i < nd; ++i) pt.p[ns + i] = static_cast<char *>(plan->dst_ptrs[i]);
     const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
-    const uint32_t nc = uint32_t(plan->copy_tiles.size()), nt = uint32_t(plan->transpose_tiles.size());
+    const uint32_t nc = uint32_t(plan->copy_tiles.size()), nf = uint32_t(plan->fast_transpose_tiles.size()),
+                   nt = uint32_t(plan->transpose_tiles.size());
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
     const uint32_t wanted = tn.blocks_per_cu ? uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu) : 0xFFFFFFFFu;
     if (nc) {
@@ -318,9 +374,26 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
         launch_copy(tn, grid, block, stream, tiles, nc, pt);
         if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
     }
+    if (nf) {
+        const Tile *ft = tiles + nc;
+        const int shape = plan->fast_rows * 1000 + plan->fast_cols;
+#define RESHARD_T16(TI, TK)                                                                                  \
+    case TI * 1000 + TK:                                                                                     \
+        hipLaunchKernelGGL((repack_transpose16_kernel<TI, TK>), dim3(nf),                                    \
+                           dim3((TI * TK / 64) < 1024 ? (TI * TK / 64) : 1024), 0, stream, ft, nf, pt);      \
+        break;
+        switch (shape) {
+            RESHARD_T16(64, 64) RESHARD_T16(64, 128) RESHARD_T16(64, 256)
+            RESHARD_T16(128, 64) RESHARD_T16(128, 128) RESHARD_T16(128, 256)
+            RESHARD_T16(256, 64) RESHARD_T16(256, 128) RESHARD_T16(256, 256)
+            default: return fail(RESHARD_ERR_INVALID_ARG, "unsupported transposing tile shape");
+        }
+#undef RESHARD_T16
+        if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the register-transpose kernel");
+    }
     if (nt) {
         dim3 grid(std::min(nt, wanted)), block(256);
-        const Tile *tt = tiles + nc;
+        const Tile *tt = tiles + nc + nf;
         switch (plan->spec.elem_bytes) {
             case 1: hipLaunchKernelGGL(repack_transpose_kernel<uint8_t>, grid, block, 0, stream, tt, nt, pt); break;
             case 2: hipLaunchKernelGGL(repack_transpose_kernel<uint16_t>, grid, block, 0, stream, tt, nt, pt); break;
@@ -360,6 +433,11 @@ extern "C" int reshard_set_tuning(const reshard_tuning *t) {
             if (u != 1 && u != 2 && u != 4 && u != 8 && u != 16) return fail(RESHARD_ERR_INVALID_ARG, "unroll must be 1, 2, 4, 8 or 16");
             n.unroll = u;
         }
+        for (int v : {t->transpose_rows, t->transpose_cols})
+            if (v != 0 && v != 64 && v != 128 && v != 256)
+                return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128 or 256");
+        if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
+        if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
         if (t->flags < -1 || t->flags > 7) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 7]");
         // 0 keeps the default like every other field; -1 asks for plain loads and stores, no barrier
         if (t->flags > 0) n.flags = t->flags;
@@ -378,6 +456,8 @@ extern "C" int reshard_get_tuning(reshard_tuning *out) {
     out->blocks_per_cu = t.blocks_per_cu;
     out->unroll = t.unroll;
     out->flags = t.flags;
+    out->transpose_rows = t.transpose_rows;
+    out->transpose_cols = t.transpose_cols;
     return RESHARD_OK;
 }
 

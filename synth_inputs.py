@@ -121,6 +121,13 @@ TINY = {
         make_layout(kind="train", tp=2, pp=2, ep=2, expert_layout="grouped"),
         make_layout(kind="gen", tp=1, ep=4),
         2002, "tiny MoE, grouped experts, TP2 PP2 EP2 -> TP1 EP4"),
+    # Grouped experts large enough for full register-transposed tiles plus ragged edges.
+    "mid_moe_grouped": _wl(
+        "mid_moe_grouped",
+        make_spec(family="moe_gqa", L=1, H=320, nq=4, nkv=2, d=16, V=64, E=4, Ie=200),
+        make_layout(kind="train", tp=1, pp=1, ep=2, expert_layout="grouped"),
+        make_layout(kind="gen", tp=2, ep=1),
+        2004, "mid-size MoE, grouped experts (transposing), EP2 -> TP2 EP1"),
     "tiny_mla": _wl(
         "tiny_mla",
         make_spec(family="moe_mla", L=2, H=40, nq=4, V=0, has_embeddings=0, E=8,

@@ -95,6 +95,26 @@ def test_every_launch_shape_gives_the_same_bits(tuning):
         set_tuning()
 
 
+@pytest.mark.parametrize("shape", [(64, 64), (64, 128), (64, 256), (128, 64), (128, 128), (128, 256),
+                                   (256, 64), (256, 128), (256, 256)])
+def test_register_transpose_tile_shapes(shape):
+    """Grouped (transposing) experts at a size with full tiles and ragged edges, every tile shape;
+    plus a shape whose expert dimensions are exact multiples of every tile shape."""
+    print("transpose shape", shape, flush=True)
+    exact = dict(TINY["mid_moe_grouped"])
+    exact["spec"] = dict(exact["spec"], H=512, Ie=256)
+    try:
+        set_tuning(transpose_rows=shape[0], transpose_cols=shape[1])
+        for wl in (TINY["mid_moe_grouped"], exact):
+            plan, _, _ = run_case(wl, "raw16")
+            # way back: generation [out][in] -> grouped [in][out] is a transpose as well
+            gen = dict(wl["dst"])
+            run_case(wl, "raw16", gen, wl["src"])
+        assert plan.info()["num_transpose_tiles"] > 0
+    finally:
+        set_tuning()
+
+
 def test_copy_baseline_matches_memcpy():
     n = 64 * 1024 * 1024 + 4096 + 16
     a = fill_buffer(n, 7, "cuda", "raw16")

@@ -41,13 +41,12 @@ def run_descs(descs, src, dst, counts=None):
                     counts[d["dst_buf"]][b:b + d["row_bytes"]] += 1
         else:
             cols = d["row_bytes"] // eb
-            for i in range(d["rows"]):
-                for k in range(cols):
-                    a = d["src_off"] + i * d["src_stride"] + k * eb
-                    b = d["dst_off"] + k * d["dst_stride"] + i * eb
-                    t[b:b + eb] = s[a:a + eb]
-                    if counts is not None:
-                        counts[d["dst_buf"]][b:b + eb] += 1
+            i, k, e = np.meshgrid(np.arange(d["rows"]), np.arange(cols), np.arange(eb), indexing="ij")
+            a = (d["src_off"] + i * d["src_stride"] + k * eb + e).ravel()
+            b = (d["dst_off"] + k * d["dst_stride"] + i * eb + e).ravel()
+            t[b] = s[a]
+            if counts is not None:
+                np.add.at(counts[d["dst_buf"]], b, 1)
 
 
 CASES = [(n, eb) for n in sorted(TINY) for eb in (1, 2, 4, 8)]
@@ -276,7 +275,8 @@ def test_state_machine_errors_without_a_device():
 def test_tuning_is_validated():
     set_tuning()
     base = get_tuning()
-    assert base == dict(tile_bytes=262144, block_threads=1024, blocks_per_cu=0, unroll=8, flags=7)
+    assert base == dict(tile_bytes=262144, block_threads=1024, blocks_per_cu=0, unroll=8, flags=7, transpose_rows=256,
+                        transpose_cols=256)
     set_tuning(tile_bytes=65536, unroll=8)
     assert get_tuning()["tile_bytes"] == 65536 and get_tuning()["unroll"] == 8
     w = WORKLOADS["C1"]
