@@ -237,6 +237,15 @@ int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshard_desc *out
 int reshard_execute(reshard_plan *plan, const void *const *src_ptrs, void *const *dst_ptrs,
                     void *stream);
 
+/*
+ * Optional: uploads the tile table to the current device now (hipMalloc + a
+ * synchronous copy) instead of inside the first reshard_execute.  After it, an
+ * execute is kernel launches only: no allocation, no copy, no synchronisation, so
+ * it may be recorded into a HIP graph (the pointer sets are baked into the
+ * recorded launches).  Errors: OOM, HIP.
+ */
+int reshard_plan_prepare(reshard_plan *plan);
+
 /* Bind (or re-bind, after the caller re-allocated) the source pointers without
  * running the repack.  Allowed in UNBOUND, RESIDENT, ON_HOST and RELEASED; from
  * RELEASED the state becomes ON_HOST again (a device home for swap-in exists). */

@@ -92,6 +92,7 @@ def lib():
             "reshard_plan_tensor": (C.c_int, [P, C.c_int, C.c_int64, C.POINTER(TensorInfo)]),
             "reshard_plan_get_info": (C.c_int, [P, C.POINTER(PlanInfo)]),
             "reshard_plan_desc": (C.c_int, [P, C.c_int64, C.POINTER(Desc)]),
+            "reshard_plan_prepare": (C.c_int, [P]),
             "reshard_execute": (C.c_int, [P, C.POINTER(P), C.POINTER(P), P]),
             "reshard_bind_src": (C.c_int, [P, C.POINTER(P)]),
             "reshard_swap_out": (C.c_int, [P, P]),
@@ -116,7 +117,7 @@ EXPORTS = (
     "reshard_last_error", "reshard_version", "reshard_set_tuning", "reshard_get_tuning",
     "reshard_plan_create", "reshard_plan_destroy", "reshard_plan_num_bufs", "reshard_plan_buf_bytes",
     "reshard_plan_buf_used", "reshard_plan_num_tensors", "reshard_plan_tensor", "reshard_plan_get_info",
-    "reshard_plan_desc", "reshard_execute", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
+    "reshard_plan_desc", "reshard_plan_prepare", "reshard_execute", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
     "reshard_swap_wait", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
 )
@@ -236,6 +237,9 @@ class Plan:
         return out
 
     # ---- the hot path ----------------------------------------------------
+    def prepare(self) -> None:
+        _check(lib().reshard_plan_prepare(self._h))
+
     def execute(self, src_ptrs, dst_ptrs, stream: int = 0) -> None:
         _check(lib().reshard_execute(self._h, _ptr_array(src_ptrs), _ptr_array(dst_ptrs), C.c_void_p(stream)))
 

@@ -229,6 +229,11 @@ extern "C" int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshar
     return RESHARD_OK;
 }
 
+extern "C" int reshard_plan_prepare(reshard_plan *p) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    return ensure_device_table(p);
+}
+
 extern "C" int reshard_bind_src(reshard_plan *p, const void *const *src_ptrs) {
     if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
     if (p->state == RESHARD_SRC_SWAPPING_OUT || p->state == RESHARD_SRC_SWAPPING_IN)

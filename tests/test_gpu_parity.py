@@ -132,6 +132,40 @@ def test_unused_source_buffers_may_be_null_and_are_never_read():
     assert src.count(None) == 4 and dst.count(None) == 1
 
 
+def test_execute_on_a_side_stream_and_inside_a_hip_graph():
+    """After prepare() an execute is launches only, so it can run on any stream and be
+    recorded into a graph; each replay is compared with an eager run on fresh inputs."""
+    wl = TINY["mid_moe_grouped"]
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    plan.prepare()
+    src = G.device_sources(plan, wl, "raw16")
+    dst = G.device_destinations(plan)
+    eager = G.device_destinations(plan)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.execute(G.ptrs(src), G.ptrs(eager), side.cuda_stream)
+    side.synchronize()
+    want = G.oracle_destinations(wl, G.to_host(src), 4)
+    G.assert_equal_buffers(eager, want, "side stream")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.execute(G.ptrs(src), G.ptrs(dst), torch.cuda.current_stream().cuda_stream)
+    for replay in range(3):
+        for i, s_ in enumerate(src):  # new contents in the same buffers
+            s_.copy_(fill_buffer(s_.numel() * 2, 77 + 10 * replay + i, "cuda", "raw16"))
+        for d_ in dst:
+            d_.fill_(G.SENT16)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        plan.execute(G.ptrs(src), G.ptrs(eager), G.stream_handle())
+        torch.cuda.synchronize()
+        for a, b in zip(dst, eager):
+            assert torch.equal(a, b), f"replay {replay}"
+        G.assert_equal_buffers(dst, G.oracle_destinations(wl, G.to_host(src), 4), f"replay {replay}")
+
+
 # ------------------------------------------------------------------ swap ----
 def test_swap_round_trip_ledger_and_rebinding():
     wl = WORKLOADS["C0"]
