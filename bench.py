@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="C1", help="C0, C1, C2, C3, C3P or C4")
+    ap.add_argument("--workload", default="C1", help="C0, C1, C1R, C2, C3, C3P or C4")
     ap.add_argument("--no-swap", action="store_true", help="time the repack alone (not a valid headline run)")
     ap.add_argument("--overlap", action="store_true",
                     help="queue the swap-out before the repack so the two overlap (under rocprofv3 the runtime "

@@ -43,9 +43,15 @@
  *     feed-forward, MoE families: router [E, H] (replicated); if n_shared > 0 the
  *       shared expert of width n_shared*Ie as fused gate_up and down, split like
  *       the dense feed-forward.
+ *     fewer KV heads than tensor ranks (T a multiple of nkv), both kinds: rank t
+ *       stores its nq/T query heads, then KV head t / (T/nkv): each KV head is
+ *       replicated on T/nkv ranks.
  *   Replicated ("common") tensors: ln1, ln2, final_ln, router, q_a, q_a_ln, kv_a,
  *     kv_a_ln.  They are READ from tensor rank 0 of the owning stage and WRITTEN
- *     to every destination tensor rank.
+ *     to every destination tensor rank.  Likewise a replicated KV head is read from
+ *     the lowest rank holding it, a tied embedding from the first stage.
+ *   Pipeline stages hold contiguous, equal blocks of layers unless the layout asks
+ *     for interleaved chunks (vpp) or an uneven first / last stage.
  *   Expert buffer (p, x) holds whole experts x*E/X .. (never tensor-split), per
  *   layer of the stage:
  *     TRAIN, RESHARD_PER_EXPERT: for each local expert fc1 = [gate; up] stored
@@ -70,7 +76,7 @@ typedef struct reshard_plan reshard_plan;
 enum {
     RESHARD_OK = 0,
     RESHARD_ERR_INVALID_ARG = -1, /* NULL/misaligned pointer, bad struct_size, bad index */
-    RESHARD_ERR_UNSUPPORTED = -2, /* shape not divisible by a degree, tp > nkv, too many buffers */
+    RESHARD_ERR_UNSUPPORTED = -2, /* shape not divisible by a degree, too many buffers */
     RESHARD_ERR_OOM = -3,         /* host or device allocation for the plan failed */
     RESHARD_ERR_HOST_OOM = -4,    /* pinned host memory for the swap could not be allocated */
     RESHARD_ERR_BAD_STATE = -5,   /* call not allowed in the plan's current swap state */
@@ -95,6 +101,8 @@ typedef struct reshard_model_spec {
     int32_t n_shared;       /* shared experts (0 = none); shared width = n_shared*Ie */
     int32_t q_lora, kv_lora, nope, rope, v_dim; /* MLA family */
     int32_t elem_bytes;     /* bytes per weight element: 1, 2, 4 or 8 */
+    int32_t tied_embeddings; /* 1: no lm_head; a TRAIN layout with pp > 1 keeps a copy of the
+                                embedding shard on its last stage (after final_ln) */
 } reshard_model_spec;
 
 /* One side of the resharding.  Set struct_size = sizeof. */
@@ -105,6 +113,10 @@ typedef struct reshard_layout {
     int32_t expert_layout;  /* TRAIN only: RESHARD_PER_EXPERT or RESHARD_GROUPED */
     int32_t tp_rank_filter; /* destination only: keep this tensor rank's dense buffers (-1 = all) */
     int32_t ep_rank_filter; /* destination only: keep this expert rank's buffers (-1 = all) */
+    int32_t vpp;            /* virtual pipeline size (0 or 1 = none): layers are cut into pp*vpp
+                               chunks, chunk c lives on stage c mod pp, stored in chunk order */
+    int32_t first_stage_layers; /* uneven pipeline split: layers on the first stage (0 = even) */
+    int32_t last_stage_layers;  /* ... and on the last; the stages between share the rest evenly */
 } reshard_layout;
 
 /* One stored tensor of a layout (for loading weights into / reading them out of the buffers). */
@@ -193,8 +205,8 @@ int reshard_get_tuning(reshard_tuning *out);
  * pair is allowed, so TRAIN -> GEN is the resharding, TRAIN -> TRAIN with equal
  * degrees is the identity and GEN -> TRAIN is the way back.  Rank filters must
  * be -1 on the source.  *out is owned by the library until reshard_plan_destroy.
- * Errors: INVALID_ARG (NULL, struct_size), UNSUPPORTED (divisibility, tp > nkv,
- * more than RESHARD_MAX_BUFFERS buffers, sizes beyond 32-bit strides), OOM.
+ * Errors: INVALID_ARG (NULL, struct_size), UNSUPPORTED (divisibility, more than
+ * RESHARD_MAX_BUFFERS buffers, sizes beyond 32-bit strides), OOM.
  */
 #define RESHARD_MAX_BUFFERS 384
 int reshard_plan_create(const reshard_model_spec *spec, const reshard_layout *src,

@@ -26,12 +26,14 @@ _EXPERT = {"per_expert": 0, "grouped": 1}
 class OrcSpec(C.Structure):
     _fields_ = [(k, C.c_int) for k in (
         "family", "L", "H", "nq", "nkv", "d", "I", "V", "qkv_bias", "has_embeddings",
-        "E", "Ie", "n_shared", "q_lora", "kv_lora", "nope", "rope", "v_dim", "elem_bytes")]
+        "E", "Ie", "n_shared", "q_lora", "kv_lora", "nope", "rope", "v_dim", "elem_bytes",
+        "tied_embeddings")]
 
 
 class OrcLayout(C.Structure):
     _fields_ = [(k, C.c_int) for k in (
-        "kind", "tp", "pp", "ep", "expert_layout", "tp_filter", "ep_filter")]
+        "kind", "tp", "pp", "ep", "expert_layout", "tp_filter", "ep_filter", "vpp",
+        "first_stage_layers", "last_stage_layers")]
 
 
 def build(force: bool = False) -> str:
@@ -64,7 +66,7 @@ def lib():
 def c_spec(spec: dict) -> OrcSpec:
     s = OrcSpec()
     for k, _ in OrcSpec._fields_:
-        setattr(s, k, _FAMILY[spec[k]] if k == "family" else int(spec[k]))
+        setattr(s, k, _FAMILY[spec[k]] if k == "family" else int(spec.get(k, 0)))
     return s
 
 
@@ -74,6 +76,9 @@ def c_layout(lay: dict) -> OrcLayout:
     l.tp, l.pp, l.ep = lay["tp"], lay["pp"], lay["ep"]
     l.expert_layout = _EXPERT[lay["expert_layout"]]
     l.tp_filter, l.ep_filter = lay["tp_filter"], lay["ep_filter"]
+    l.vpp = lay.get("vpp", 1)
+    l.first_stage_layers = lay.get("first_stage_layers", 0)
+    l.last_stage_layers = lay.get("last_stage_layers", 0)
     return l
 
 

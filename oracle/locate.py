@@ -109,7 +109,8 @@ def logical_tensors(spec: dict):
                 out.append(("ex_down", l, e, H, Ie))
     if spec["has_embeddings"]:
         out.append(("final_ln", -1, -1, 1, H))
-        out.append(("lm_head", -1, -1, spec["V"], H))
+        if not spec.get("tied_embeddings", 0):
+            out.append(("lm_head", -1, -1, spec["V"], H))
     return out
 
 
@@ -133,10 +134,10 @@ class Layout:
         assert T >= 1 and P >= 1 and X >= 1
         if self.kind == "gen":
             assert P == 1
-        assert spec["L"] % P == 0
         assert spec["nq"] % T == 0
         if spec["family"] != "moe_mla":
-            assert spec["nkv"] % T == 0, "KV-head replication (tp > nkv) unsupported"
+            # fewer KV heads than tensor ranks: every KV head is replicated on T/nkv ranks
+            assert spec["nkv"] % T == 0 or T % spec["nkv"] == 0
         if spec["family"] == "dense_gqa":
             assert spec["I"] % T == 0
             assert X == 1
@@ -148,8 +149,38 @@ class Layout:
         self.nd = P * T
         self.ne = P * X if self.moe else 0
         self.nbufs = self.nd + self.ne
-        self.Lp = spec["L"] // P
+        self.tied = bool(spec.get("tied_embeddings", 0)) and bool(spec["has_embeddings"])
+        self.stage_layers = self._assign_layers()
+        self.layer_stage = {l: p for p, ls in enumerate(self.stage_layers) for l in ls}
         self._walk()
+
+    def _assign_layers(self):
+        """Layers of every stage, in storage order.
+
+        Even split: contiguous blocks.  Virtual pipeline size v: the layers are cut
+        into P*v chunks; chunk c lives on stage c mod P, chunks of a stage stored in
+        chunk order.  Uneven split: the first / last stage hold the given numbers of
+        layers, the stages between share the rest evenly."""
+        L, P = self.spec["L"], self.P
+        v = self.lay.get("vpp", 1)
+        first, last = self.lay.get("first_stage_layers", 0), self.lay.get("last_stage_layers", 0)
+        if first or last:
+            assert v == 1 and P >= 2 and first > 0 and last > 0
+            mid = L - first - last
+            if P == 2:
+                assert mid == 0
+                counts = [first, last]
+            else:
+                assert mid > 0 and mid % (P - 2) == 0
+                counts = [first] + [mid // (P - 2)] * (P - 2) + [last]
+            out, at = [], 0
+            for n in counts:
+                out.append(list(range(at, at + n)))
+                at += n
+            return out
+        assert v >= 1 and L % (P * v) == 0
+        lc = L // (P * v)
+        return [[l for k in range(v) for l in range((k * P + p) * lc, (k * P + p + 1) * lc)] for p in range(P)]
 
     # ---- which buffers a filtered layout really holds -------------------
     def buffer_used(self, b: int) -> bool:
@@ -166,7 +197,7 @@ class Layout:
         seq = []
         if s["has_embeddings"] and p == 0:
             seq.append(("emb", -1, s["V"] // T * H))
-        for l in range(p * self.Lp, (p + 1) * self.Lp):
+        for l in self.stage_layers[p]:
             seq.append(("ln1", l, H))
             if fam == "moe_mla":
                 nql = s["nq"] // T
@@ -178,7 +209,7 @@ class Layout:
                 seq.append(("kv_b", l, nql * (s["nope"] + s["v_dim"]) * s["kv_lora"]))
                 seq.append(("wo", l, H * nql * s["v_dim"]))
             else:
-                rows = (s["nq"] + 2 * s["nkv"]) // T * s["d"]
+                rows = (s["nq"] // T + 2 * max(s["nkv"] // T, 1)) * s["d"]
                 seq.append(("qkv_w", l, rows * H))
                 if s["qkv_bias"]:
                     seq.append(("qkv_b", l, rows))
@@ -195,14 +226,18 @@ class Layout:
                     seq.append(("sh_fc2", l, H * Is // T))
         if s["has_embeddings"] and p == self.P - 1:
             seq.append(("final_ln", -1, H))
-            seq.append(("lm_head", -1, s["V"] // T * H))
+            if not self.tied:
+                seq.append(("lm_head", -1, s["V"] // T * H))
+            elif self.P > 1:
+                # tied output layer: the last stage keeps its own copy of the embedding shard
+                seq.append(("emb_tied", -1, s["V"] // T * H))
         return seq
 
     def _expert_sequence(self, p: int):
         s = self.spec
         H, Ie, El = s["H"], s["Ie"], s["E"] // self.X
         seq = []
-        for l in range(p * self.Lp, (p + 1) * self.Lp):
+        for l in self.stage_layers[p]:
             if self.kind == "gen":
                 seq.append(("w13", l, -1, El * 2 * Ie * H))
                 seq.append(("w2", l, -1, El * H * Ie))
@@ -246,8 +281,10 @@ class Layout:
     def place(self, name: str, layer: int, expert: int, r, c):
         """All homes of logical element (r, c) of a tensor: [(buffer, byte offset)].
 
-        One entry for split tensors, T entries (one per tensor rank, rank 0
-        first) for replicated ones.  r and c may be ints or equal-shape arrays.
+        One entry for split tensors, several for replicated ones (common weights:
+        one per tensor rank, rank 0 first; a KV head shared by T/nkv ranks: the
+        lowest rank first; a tied embedding: first stage first).  The first entry
+        is the copy a source is read from.  r and c may be ints or equal-shape arrays.
         """
         s, T, X = self.spec, self.T, self.X
         eb, H = s["elem_bytes"], s["H"]
@@ -258,7 +295,7 @@ class Layout:
         elif name in ("final_ln", "lm_head"):
             p = self.P - 1
         else:
-            p = layer // self.Lp
+            p = self.layer_stage[layer]
         dbase = p * T
 
         def dense(stored, t, elem):
@@ -270,7 +307,11 @@ class Layout:
 
         if name in ("emb", "lm_head"):
             n = s["V"] // T
-            return [dense(name, r // n, (r % n) * H + c)]
+            homes = [dense(name, r // n, (r % n) * H + c)]
+            if name == "emb" and self.tied and self.P > 1:
+                last = (self.P - 1) * T
+                homes.append((last + r // n, self.dense_off[self.P - 1][("emb_tied", -1)] + ((r % n) * H + c) * eb))
+            return homes
 
         if name in ("wq", "wk", "wv", "bq", "bk", "bv"):
             nq, nkv, d = s["nq"], s["nkv"], s["d"]
@@ -279,6 +320,15 @@ class Layout:
             bias = name[0] == "b"
             width = 1 if bias else H
             stored = "qkv_b" if bias else "qkv_w"
+            if T > nkv:
+                # every rank holds nq/T query heads and one (replicated) KV head, in both
+                # layout kinds: [its query rows, the key head, the value head]
+                rep, hq = T // nkv, nq // T
+                if which == "q":
+                    return [dense(stored, r // (hq * d), (r % (hq * d)) * width + c)]
+                head, w = r // d, r % d
+                row = hq * d + w + (0 if which == "k" else d)
+                return [dense(stored, head * rep + i, row * width + c) for i in range(rep)]
             if self.kind == "train":
                 # rank t holds nkv/T whole KV groups; inside a group: g query
                 # heads, then the key head, then the value head.

@@ -35,6 +35,7 @@ typedef struct {
     int family; /* 0 dense GQA, 1 MoE GQA, 2 MoE MLA */
     int L, H, nq, nkv, d, I, V, qkv_bias, has_embeddings;
     int E, Ie, n_shared, q_lora, kv_lora, nope, rope, v_dim, elem_bytes;
+    int tied_embeddings; /* 1: no lm_head; with pp > 1 the last training stage keeps an embedding copy */
 } orc_spec;
 
 typedef struct {
@@ -42,6 +43,9 @@ typedef struct {
     int tp, pp, ep;
     int expert_layout; /* 0 per-expert [out][in], 1 grouped [expert][in][out] */
     int tp_filter, ep_filter;
+    int vpp;                /* virtual pipeline size: layer chunks dealt round-robin to the stages */
+    int first_stage_layers; /* uneven split: layers on the first / last stage (0 = even) */
+    int last_stage_layers;
 } orc_layout;
 
 enum { FAM_DENSE = 0, FAM_MOE = 1, FAM_MLA = 2 };
@@ -63,11 +67,14 @@ enum {
 typedef struct {
     orc_spec s;
     orc_layout l;
-    int T, P, X, Lp, El, nd, ne, moe, grouped;
+    int T, P, X, El, nd, ne, moe, grouped, tied;
+    int *stage_of;   /* [L] stage holding a layer */
+    int *order;      /* [L] layers sorted by (stage, storage position) */
+    int *first;      /* [P+1] range of `order` belonging to a stage */
     int64_t eb;
     int64_t *doff;   /* [L][NSLOT] byte offset of a stored tensor in its stage's dense buffers */
     int64_t *eoff;   /* [L][El][2] byte offset in its stage's expert buffers (stacked: j = 0) */
-    int64_t emb_off, final_ln_off, lm_head_off;
+    int64_t emb_off, final_ln_off, lm_head_off, emb_tied_off;
     int64_t *dense_bytes, *expert_bytes; /* [P] */
 } ctx_t;
 
@@ -80,11 +87,16 @@ static int valid(const orc_spec *s, const orc_layout *l)
     if (s->elem_bytes != 1 && s->elem_bytes != 2 && s->elem_bytes != 4 && s->elem_bytes != 8) return 0;
     if (l->tp < 1 || l->pp < 1 || l->ep < 1) return 0;
     if (l->kind == K_GEN && l->pp != 1) return 0;
-    if (s->L % l->pp) return 0;
+    if (l->vpp < 1) return 0;
+    if (l->first_stage_layers || l->last_stage_layers) {
+        int mid = s->L - l->first_stage_layers - l->last_stage_layers;
+        if (l->vpp != 1 || l->pp < 2 || l->first_stage_layers <= 0 || l->last_stage_layers <= 0) return 0;
+        if (l->pp == 2 ? mid != 0 : (mid <= 0 || mid % (l->pp - 2))) return 0;
+    } else if (s->L % (l->pp * l->vpp)) return 0;
     if (s->nq % l->tp) return 0;
     if (s->family != FAM_MLA) {
         if (s->nkv <= 0 || s->d <= 0 || s->nq % s->nkv) return 0;
-        if (s->nkv % l->tp) return 0;
+        if (s->nkv % l->tp && l->tp % s->nkv) return 0;
     } else if (s->q_lora <= 0 || s->kv_lora <= 0 || s->nope <= 0 || s->rope <= 0 || s->v_dim <= 0)
         return 0;
     if (s->family == FAM_DENSE) {
@@ -100,6 +112,7 @@ static int valid(const orc_spec *s, const orc_layout *l)
 static void ctx_free(ctx_t *c)
 {
     free(c->doff); free(c->eoff); free(c->dense_bytes); free(c->expert_bytes);
+    free(c->stage_of); free(c->order); free(c->first);
 }
 
 /* Lay the stored tensors of every stage out in order, each on a 256-byte boundary. */
@@ -109,8 +122,35 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
     if (!valid(s, l)) return -1;
     c->s = *s; c->l = *l;
     c->T = l->tp; c->P = l->pp; c->X = l->ep;
-    c->Lp = s->L / c->P;
     c->moe = s->family != FAM_DENSE;
+    c->tied = s->tied_embeddings && s->has_embeddings;
+    /* which stage holds which layers, and in which order they are stored there */
+    c->stage_of = calloc(s->L, sizeof(int));
+    c->order = calloc(s->L, sizeof(int));
+    c->first = calloc(c->P + 1, sizeof(int));
+    {
+        int n = 0;
+        if (l->first_stage_layers || l->last_stage_layers) {
+            int mid = c->P > 2 ? (s->L - l->first_stage_layers - l->last_stage_layers) / (c->P - 2) : 0;
+            for (int p = 0; p < c->P; p++) {
+                int cnt = p == 0 ? l->first_stage_layers : p == c->P - 1 ? l->last_stage_layers : mid;
+                c->first[p] = n;
+                for (int i = 0; i < cnt; i++) { c->stage_of[n] = p; c->order[n] = n; n++; }
+            }
+        } else {
+            int lc = s->L / (c->P * l->vpp);
+            for (int p = 0; p < c->P; p++) {
+                c->first[p] = n;
+                for (int k = 0; k < l->vpp; k++)          /* chunk k*P + p */
+                    for (int i = 0; i < lc; i++) {
+                        int ly = (k * c->P + p) * lc + i;
+                        c->stage_of[ly] = p;
+                        c->order[n++] = ly;
+                    }
+            }
+        }
+        c->first[c->P] = n;
+    }
     c->El = c->moe ? s->E / c->X : 0;
     c->nd = c->P * c->T;
     c->ne = c->moe ? c->P * c->X : 0;
@@ -125,7 +165,8 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
         int64_t off = 0;
 #define PUT(dst, nelem) do { off = up256(off); (dst) = off; off += (int64_t)(nelem) * eb; } while (0)
         if (s->has_embeddings && p == 0) PUT(c->emb_off, s->V / T * H);
-        for (int ly = p * c->Lp; ly < (p + 1) * c->Lp; ly++) {
+        for (int at = c->first[p]; at < c->first[p + 1]; at++) {
+            int ly = c->order[at];
             int64_t *o = c->doff + (size_t)ly * NSLOT;
             PUT(o[S_LN1], H);
             if (s->family == FAM_MLA) {
@@ -138,7 +179,8 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
                 PUT(o[S_KVB], nql * (s->nope + s->v_dim) * s->kv_lora);
                 PUT(o[S_WO], H * nql * s->v_dim);
             } else {
-                int64_t rows = (int64_t)(s->nq + 2 * s->nkv) / T * s->d;
+                int64_t kvl = s->nkv / T > 0 ? s->nkv / T : 1; /* a replicated KV head when T > nkv */
+                int64_t rows = (s->nq / T + 2 * kvl) * s->d;
                 PUT(o[S_QKV_W], rows * H);
                 if (s->qkv_bias) PUT(o[S_QKV_B], rows);
                 PUT(o[S_WO], H * ((int64_t)s->nq * s->d / T));
@@ -158,13 +200,15 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
         }
         if (s->has_embeddings && p == c->P - 1) {
             PUT(c->final_ln_off, H);
-            PUT(c->lm_head_off, s->V / T * H);
+            if (!c->tied) PUT(c->lm_head_off, s->V / T * H);
+            else if (c->P > 1) PUT(c->emb_tied_off, s->V / T * H);
         }
         c->dense_bytes[p] = up256(off);
         if (c->moe) {
             off = 0;
             int64_t Ie = s->Ie, El = c->El;
-            for (int ly = p * c->Lp; ly < (p + 1) * c->Lp; ly++) {
+            for (int at = c->first[p]; at < c->first[p + 1]; at++) {
+                int ly = c->order[at];
                 int64_t *o = c->eoff + (size_t)ly * El * 2;
                 if (l->kind == K_GEN || c->grouped) {
                     PUT(o[0], El * 2 * Ie * H);
@@ -199,7 +243,7 @@ static void src_find(const ctx_t *c, int tid, int ly, int ex, int64_t r, int64_t
 {
     const orc_spec *s = &c->s;
     const int64_t H = s->H, T = c->T, eb = c->eb;
-    int p = tid == T_EMB ? 0 : (tid == T_FINAL_LN || tid == T_LM_HEAD) ? c->P - 1 : ly / c->Lp;
+    int p = tid == T_EMB ? 0 : (tid == T_FINAL_LN || tid == T_LM_HEAD) ? c->P - 1 : c->stage_of[ly];
     const int64_t *o = ly >= 0 ? c->doff + (size_t)ly * NSLOT : NULL;
     int64_t t = 0, e = 0, ncols = H;
     switch (tid) {
@@ -221,7 +265,12 @@ static void src_find(const ctx_t *c, int tid, int ly, int ex, int64_t r, int64_t
         int bias = tid == T_BQ || tid == T_BK || tid == T_BV;
         int isq = tid == T_WQ || tid == T_BQ, isk = tid == T_WK || tid == T_BK;
         int64_t g = s->nq / s->nkv, d = s->d, row;
-        if (c->l.kind == K_TRAIN) {
+        if (T > s->nkv) {
+            /* one replicated KV head per rank: read the copy on the lowest rank holding it */
+            int64_t rep = T / s->nkv, hq = s->nq / T;
+            if (isq) { t = r / (hq * d); row = r % (hq * d); }
+            else { t = (r / d) * rep; row = hq * d + r % d + (isk ? 0 : d); }
+        } else if (c->l.kind == K_TRAIN) {
             int64_t per = s->nkv / T, G, w;
             if (isq) { G = r / (g * d); w = r % (g * d); }
             else { G = r / d; w = r % d; w += isk ? g * d : (g + 1) * d; }
@@ -352,7 +401,8 @@ static void dst_pieces(const ctx_t *D, pieces_t *ps)
             int64_t n = s->V / T;
             add_piece(ps, T_EMB, -1, -1, t * n, n, 0, H, b, D->emb_off, H, 0);
         }
-        for (int ly = p * D->Lp; ly < (p + 1) * D->Lp; ly++) {
+        for (int at = D->first[p]; at < D->first[p + 1]; at++) {
+            int ly = D->order[at];
             const int64_t *o = D->doff + (size_t)ly * NSLOT;
             add_piece(ps, T_LN1, ly, -1, 0, 1, 0, H, b, o[S_LN1], H, 0);
             if (s->family == FAM_MLA) {
@@ -371,7 +421,13 @@ static void dst_pieces(const ctx_t *D, pieces_t *ps)
                 for (int bias = 0; bias <= (s->qkv_bias ? 1 : 0); bias++) {
                     int64_t w = bias ? 1 : H, base = o[bias ? S_QKV_B : S_QKV_W];
                     int tq = bias ? T_BQ : T_WQ, tk = bias ? T_BK : T_WK, tv = bias ? T_BV : T_WV;
-                    if (D->l.kind == K_TRAIN) {
+                    if (T > s->nkv) {
+                        /* this rank's query heads, then the KV head it shares with T/nkv - 1 others */
+                        int64_t rep = T / s->nkv, hq = s->nq / T, kvh = t / rep;
+                        add_piece(ps, tq, ly, -1, t * hq * d, hq * d, 0, w, b, base, w, 0);
+                        add_piece(ps, tk, ly, -1, kvh * d, d, 0, w, b, base + hq * d * w * eb, w, 0);
+                        add_piece(ps, tv, ly, -1, kvh * d, d, 0, w, b, base + (hq + 1) * d * w * eb, w, 0);
+                    } else if (D->l.kind == K_TRAIN) {
                         int64_t per = s->nkv / T;
                         for (int64_t j = 0; j < per; j++) {
                             int64_t G = t * per + j, row = j * (g + 2) * d;
@@ -408,14 +464,16 @@ static void dst_pieces(const ctx_t *D, pieces_t *ps)
         if (s->has_embeddings && p == D->P - 1) {
             int64_t n = s->V / T;
             add_piece(ps, T_FINAL_LN, -1, -1, 0, 1, 0, H, b, D->final_ln_off, H, 0);
-            add_piece(ps, T_LM_HEAD, -1, -1, t * n, n, 0, H, b, D->lm_head_off, H, 0);
+            if (!D->tied) add_piece(ps, T_LM_HEAD, -1, -1, t * n, n, 0, H, b, D->lm_head_off, H, 0);
+            else if (D->P > 1) add_piece(ps, T_EMB, -1, -1, t * n, n, 0, H, b, D->emb_tied_off, H, 0);
         }
     }
     for (int b = D->nd; b < D->nd + D->ne; b++) {
         if (!buf_used(D, b)) continue;
         int p = (b - D->nd) / D->X;
         int64_t x = (b - D->nd) % D->X, Ie = s->Ie, El = D->El;
-        for (int ly = p * D->Lp; ly < (p + 1) * D->Lp; ly++) {
+        for (int at = D->first[p]; at < D->first[p + 1]; at++) {
+            int ly = D->order[at];
             const int64_t *eo = D->eoff + (size_t)ly * El * 2;
             for (int64_t j = 0; j < El; j++) {
                 int ex = (int)(x * El + j);

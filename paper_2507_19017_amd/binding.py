@@ -25,12 +25,13 @@ _ERR_NAMES = {-1: "INVALID_ARG", -2: "UNSUPPORTED", -3: "OOM", -4: "HOST_OOM", -
 class ModelSpec(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(k, C.c_int32) for k in (
         "family", "L", "H", "nq", "nkv", "d", "I", "V", "qkv_bias", "has_embeddings", "E", "Ie",
-        "n_shared", "q_lora", "kv_lora", "nope", "rope", "v_dim", "elem_bytes")]
+        "n_shared", "q_lora", "kv_lora", "nope", "rope", "v_dim", "elem_bytes", "tied_embeddings")]
 
 
 class Layout(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(k, C.c_int32) for k in (
-        "kind", "tp", "pp", "ep", "expert_layout", "tp_rank_filter", "ep_rank_filter")]
+        "kind", "tp", "pp", "ep", "expert_layout", "tp_rank_filter", "ep_rank_filter", "vpp",
+        "first_stage_layers", "last_stage_layers")]
 
 
 class TensorInfo(C.Structure):
@@ -164,7 +165,7 @@ def make_spec(spec: dict) -> ModelSpec:
     s = ModelSpec()
     s.struct_size = C.sizeof(ModelSpec)
     for k, _ in ModelSpec._fields_[1:]:
-        setattr(s, k, FAMILY[spec[k]] if k == "family" else int(spec[k]))
+        setattr(s, k, FAMILY[spec[k]] if k == "family" else int(spec.get(k, 0)))
     return s
 
 
@@ -175,6 +176,9 @@ def make_layout(lay: dict) -> Layout:
     l.tp, l.pp, l.ep = int(lay["tp"]), int(lay["pp"]), int(lay["ep"])
     l.expert_layout = EXPERT_LAYOUT[lay["expert_layout"]]
     l.tp_rank_filter, l.ep_rank_filter = int(lay["tp_filter"]), int(lay["ep_filter"])
+    l.vpp = int(lay.get("vpp", 1))
+    l.first_stage_layers = int(lay.get("first_stage_layers", 0))
+    l.last_stage_layers = int(lay.get("last_stage_layers", 0))
     return l
 
 

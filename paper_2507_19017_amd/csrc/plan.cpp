@@ -41,8 +41,10 @@ bool is_replicated(int id) {
 // Lays stored tensors out in one buffer and records the fragments they hold.
 class BufferBuilder {
   public:
-    BufferBuilder(Side &side, int buf, int eb, bool record_frags, bool record_replicated)
-        : side_(side), buf_(buf), eb_(eb), frags_(record_frags), repl_(record_replicated) {}
+    // A destination records every copy of a tensor.  A source records only the copy that is
+    // read: common tensors on tensor rank 0 (`rank0`), other replicas where marked primary.
+    BufferBuilder(Side &side, int buf, int eb, bool record_frags, bool is_source, bool rank0)
+        : side_(side), buf_(buf), eb_(eb), frags_(record_frags), src_(is_source), rank0_(rank0) {}
 
     // Starts a stored tensor of `elems` elements; returns its byte offset.
     int64_t begin(const char *name, int layer, int expert, int64_t elems, bool replicated) {
@@ -63,18 +65,20 @@ class BufferBuilder {
 
     // Rows [r0,r1) x cols [c0,c1) of logical tensor `id` stored row-major (ld elements
     // per row) at byte offset `off`; transposed = stored column-major with that ld.
+    // `primary` = false marks a copy that a source never reads (another rank or stage holds
+    // the copy that is read); destinations record every copy.
     void frag(int id, int layer, int expert, int64_t r0, int64_t r1, int64_t c0, int64_t c1,
-              int64_t off, int64_t ld, bool transposed = false) {
+              int64_t off, int64_t ld, bool transposed = false, bool primary = true) {
         if (!frags_) return;
-        if (is_replicated(id) && !repl_) return;
+        if (src_ && (!primary || (is_replicated(id) && !rank0_))) return;
         side_.frags.push_back(Fragment{make_key(id, layer, expert), r0, r1, c0, c1, buf_, off, ld, transposed});
     }
 
     // A whole stored tensor that is one fragment.
     void whole(const char *name, int id, int layer, int64_t r0, int64_t rows, int64_t c0,
-               int64_t cols) {
-        int64_t at = begin(name, layer, -1, rows * cols, is_replicated(id));
-        frag(id, layer, -1, r0, r0 + rows, c0, c0 + cols, at, cols);
+               int64_t cols, bool primary = true) {
+        int64_t at = begin(name, layer, -1, rows * cols, is_replicated(id) || !primary);
+        frag(id, layer, -1, r0, r0 + rows, c0, c0 + cols, at, cols, false, primary);
     }
 
     int64_t finish() const { return (off_ + kAlign - 1) / kAlign * kAlign; }
@@ -82,7 +86,7 @@ class BufferBuilder {
   private:
     Side &side_;
     int buf_, eb_;
-    bool frags_, repl_;
+    bool frags_, src_, rank0_;
     int64_t off_ = 0;
 };
 
@@ -99,12 +103,24 @@ int check_shape(const reshard_model_spec &s, const reshard_layout &l) {
         return fail(RESHARD_ERR_INVALID_ARG, "elem_bytes must be 1, 2, 4 or 8");
     if (l.tp < 1 || l.pp < 1 || l.ep < 1) return fail(RESHARD_ERR_INVALID_ARG, "degrees must be >= 1");
     if (l.kind == RESHARD_GEN && l.pp != 1) return bad("a generation layout has one pipeline stage");
-    if (s.L % l.pp) return bad("layers not divisible by pp");
+    if (l.vpp < 0 || l.first_stage_layers < 0 || l.last_stage_layers < 0)
+        return fail(RESHARD_ERR_INVALID_ARG, "vpp and stage layer counts must be >= 0");
+    const int vpp = l.vpp > 0 ? l.vpp : 1;
+    if (l.first_stage_layers || l.last_stage_layers) {
+        const int mid = s.L - l.first_stage_layers - l.last_stage_layers;
+        if (vpp != 1) return bad("an uneven pipeline split cannot be combined with vpp");
+        if (l.pp < 2 || !l.first_stage_layers || !l.last_stage_layers)
+            return bad("an uneven pipeline split needs pp >= 2 and both first and last stage sizes");
+        if (l.pp == 2 ? mid != 0 : (mid <= 0 || mid % (l.pp - 2)))
+            return bad("layers between the first and last stage not divisible by pp - 2");
+    } else if (s.L % (l.pp * vpp)) {
+        return bad("layers not divisible by pp * vpp");
+    }
     if (s.nq % l.tp) return bad("query heads not divisible by tp");
     if (s.family != RESHARD_MOE_MLA) {
         if (s.nkv <= 0 || s.d <= 0) return fail(RESHARD_ERR_INVALID_ARG, "nkv, d must be positive");
         if (s.nq % s.nkv) return bad("query heads not divisible by KV heads");
-        if (s.nkv % l.tp) return bad("KV heads not divisible by tp (KV-head replication is unsupported)");
+        if (s.nkv % l.tp && l.tp % s.nkv) return bad("KV heads neither divide nor are divided by tp");
     } else if (s.q_lora <= 0 || s.kv_lora <= 0 || s.nope <= 0 || s.rope <= 0 || s.v_dim <= 0) {
         return fail(RESHARD_ERR_INVALID_ARG, "MLA dimensions must be positive");
     }
@@ -144,7 +160,22 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
     const bool moe = s.family != RESHARD_DENSE_GQA, mla = s.family == RESHARD_MOE_MLA;
     const bool gen = l.kind == RESHARD_GEN;
     const bool grouped = !gen && l.expert_layout == RESHARD_GROUPED;
-    const int64_t H = s.H, Lp = s.L / P;
+    const int64_t H = s.H;
+    const bool tied = s.tied_embeddings && s.has_embeddings;
+    // layers of every stage in storage order
+    std::vector<std::vector<int>> stage_layers(P);
+    if (l.first_stage_layers || l.last_stage_layers) {
+        const int mid = P > 2 ? (s.L - l.first_stage_layers - l.last_stage_layers) / (P - 2) : 0;
+        int next = 0;
+        for (int p = 0; p < P; ++p) {
+            const int n = p == 0 ? l.first_stage_layers : p == P - 1 ? l.last_stage_layers : mid;
+            for (int i = 0; i < n; ++i) stage_layers[p].push_back(next++);
+        }
+    } else {
+        const int v = l.vpp > 0 ? l.vpp : 1, chunk = s.L / (P * v);
+        for (int c = 0; c < P * v; ++c)  // chunk c -> stage c mod P, appended in chunk order
+            for (int i = 0; i < chunk; ++i) stage_layers[c % P].push_back(c * chunk + i);
+    }
     out = Side{};
     out.layout = l;
     out.nd = P * T;
@@ -158,14 +189,13 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
             const int b = p * T + t;
             const bool kept = is_source || l.tp_rank_filter < 0 || l.tp_rank_filter == t;
             // a source reads replicated tensors from tensor rank 0 only
-            BufferBuilder bb(out, b, eb, kept, !is_source || t == 0);
+            BufferBuilder bb(out, b, eb, kept, is_source, t == 0);
             if (!is_source) out.used[b] = kept;
             if (s.has_embeddings && p == 0) {
                 int64_t n = s.V / T;
                 bb.whole("emb", LT_EMB, -1, t * n, n, 0, H);
             }
-            for (int64_t ly = p * Lp; ly < (p + 1) * Lp; ++ly) {
-                const int L_ = int(ly);
+            for (const int L_ : stage_layers[p]) {
                 bb.whole("ln1", LT_LN1, L_, 0, 1, 0, H);
                 if (mla) {
                     const int64_t heads = s.nq / T;
@@ -179,14 +209,23 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
                     bb.whole("wo", LT_WO, L_, 0, H, t * heads * s.v_dim, heads * s.v_dim);
                 } else {
                     const int64_t d = s.d, g = s.nq / s.nkv;
-                    const int64_t groups = s.nkv / T;           // KV groups owned by this rank
-                    const int64_t qrows = groups * g * d, krows = groups * d;
+                    const bool kv_shared = T > s.nkv;           // each KV head replicated on T/nkv ranks
+                    const int64_t groups = kv_shared ? 1 : s.nkv / T;  // KV heads stored by this rank
+                    const int64_t qrows = int64_t(s.nq) / T * d, krows = groups * d;
                     for (int pass = 0; pass < (s.qkv_bias ? 2 : 1); ++pass) {
                         const bool bias = pass == 1;
                         const int64_t w = bias ? 1 : H;         // a bias is a one-column matrix
                         const int iq = bias ? LT_BQ : LT_WQ, ik = bias ? LT_BK : LT_WK, iv = bias ? LT_BV : LT_WV;
                         const int64_t at = bb.begin(bias ? "qkv_b" : "qkv_w", L_, -1, (qrows + 2 * krows) * w, false);
-                        if (gen) {
+                        if (kv_shared) {
+                            // both kinds: the rank's query rows, then the shared key and value head;
+                            // a source reads the head from the lowest rank holding it
+                            const int64_t rep = T / s.nkv, head = t / rep;
+                            const bool first_copy = t % rep == 0;
+                            bb.frag(iq, L_, -1, t * qrows, (t + 1) * qrows, 0, w, at, w);
+                            bb.frag(ik, L_, -1, head * d, (head + 1) * d, 0, w, at + qrows * w * eb, w, false, first_copy);
+                            bb.frag(iv, L_, -1, head * d, (head + 1) * d, 0, w, at + (qrows + d) * w * eb, w, false, first_copy);
+                        } else if (gen) {
                             // blocked: this rank's query rows, key rows, value rows
                             bb.frag(iq, L_, -1, t * qrows, (t + 1) * qrows, 0, w, at, w);
                             bb.frag(ik, L_, -1, t * krows, (t + 1) * krows, 0, w, at + qrows * w * eb, w);
@@ -224,7 +263,10 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
             if (s.has_embeddings && p == P - 1) {
                 int64_t n = s.V / T;
                 bb.whole("final_ln", LT_FINAL_LN, -1, 0, 1, 0, H);
-                bb.whole("lm_head", LT_LM_HEAD, -1, t * n, n, 0, H);
+                if (!tied)
+                    bb.whole("lm_head", LT_LM_HEAD, -1, t * n, n, 0, H);
+                else if (P > 1)  // the tied output layer's own copy; never the one a source reads
+                    bb.whole("emb_tied", LT_EMB, -1, t * n, n, 0, H, false);
             }
             out.buf_bytes[b] = bb.finish();
         }
@@ -233,10 +275,9 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
         for (int x = 0; x < X; ++x) {
             const int b = out.nd + p * X + x;
             const bool kept = is_source || l.ep_rank_filter < 0 || l.ep_rank_filter == x;
-            BufferBuilder bb(out, b, eb, kept, true);
+            BufferBuilder bb(out, b, eb, kept, is_source, true);
             if (!is_source) out.used[b] = kept;
-            for (int64_t ly = p * Lp; ly < (p + 1) * Lp; ++ly) {
-                const int L_ = int(ly);
+            for (const int L_ : stage_layers[p]) {
                 if (gen || grouped) {
                     const int64_t a1 = bb.begin(gen ? "w13" : "w1", L_, -1, El * 2 * Ie * H, false);
                     const int64_t a2 = bb.begin("w2", L_, -1, El * Ie * H, false);

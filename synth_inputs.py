@@ -20,12 +20,15 @@ import torch
 _SPEC_DEFAULTS = dict(
     family="dense_gqa", L=1, H=0, nq=0, nkv=0, d=0, I=0, V=0, qkv_bias=0,
     has_embeddings=1, E=0, Ie=0, n_shared=0, q_lora=0, kv_lora=0, nope=0,
-    rope=0, v_dim=0, elem_bytes=2,
+    rope=0, v_dim=0, elem_bytes=2, tied_embeddings=0,
 )
 # Keys of a layout.  `kind`: "train" or "gen"; `expert_layout`: "per_expert" or
 # "grouped"; the two filters select one rank of the layout (-1 = every rank).
+# `vpp`: virtual pipeline size (interleaved layer chunks); `first_stage_layers` /
+# `last_stage_layers`: uneven pipeline split (0 = even).
 _LAYOUT_DEFAULTS = dict(kind="train", tp=1, pp=1, ep=1,
-                        expert_layout="per_expert", tp_filter=-1, ep_filter=-1)
+                        expert_layout="per_expert", tp_filter=-1, ep_filter=-1,
+                        vpp=1, first_stage_layers=0, last_stage_layers=0)
 
 
 def make_spec(**kw) -> dict:
@@ -60,6 +63,16 @@ WORKLOADS = {
         make_layout(kind="train", tp=4, pp=2),
         make_layout(kind="gen", tp=2),
         1001, "Qwen2.5-7B-shaped, TP4 PP2 -> TP2"),
+    # The same 7B shape under a wider training layout: TP8 (each of the 4 KV heads shared by two
+    # ranks), PP2 with 2 interleaved chunks per stage -> generation TP2.  Not a task config; it
+    # exercises the layout options beyond them at full size.
+    "C1R": _wl(
+        "C1R",
+        make_spec(family="dense_gqa", L=28, H=3584, nq=28, nkv=4, d=128, I=18944,
+                  V=152064, qkv_bias=1),
+        make_layout(kind="train", tp=8, pp=2, vpp=2),
+        make_layout(kind="gen", tp=2),
+        1005, "Qwen2.5-7B-shaped, TP8 (KV heads replicated) PP2 VPP2 -> TP2"),
     # Qwen2.5-32B-shaped dense decoder, training TP8 PP4 -> generation TP4.
     "C2": _wl(
         "C2",
@@ -128,6 +141,22 @@ TINY = {
         make_layout(kind="train", tp=1, pp=1, ep=2, expert_layout="grouped"),
         make_layout(kind="gen", tp=2, ep=1),
         2004, "mid-size MoE, grouped experts (transposing), EP2 -> TP2 EP1"),
+    # KV-head replication: 2 KV heads on 4 tensor ranks (training) and 8 (the way back is
+    # exercised by the round-trip tests), interleaved pipeline chunks, tied embeddings.
+    "tiny_kvrep": _wl(
+        "tiny_kvrep",
+        make_spec(family="dense_gqa", L=8, H=48, nq=8, nkv=2, d=8, I=40, V=64,
+                  qkv_bias=1, tied_embeddings=1),
+        make_layout(kind="train", tp=4, pp=2, vpp=2),
+        make_layout(kind="gen", tp=8),
+        2005, "tiny dense, KV replication TP4 PP2 VPP2 -> TP8, tied embeddings"),
+    # Uneven pipeline stages (3 + 2 + 2 + 1 layers) and a destination with fewer ranks than KV heads.
+    "tiny_uneven": _wl(
+        "tiny_uneven",
+        make_spec(family="dense_gqa", L=8, H=32, nq=8, nkv=2, d=8, I=24, V=48),
+        make_layout(kind="train", tp=4, pp=4, first_stage_layers=3, last_stage_layers=1),
+        make_layout(kind="gen", tp=2),
+        2006, "tiny dense, uneven PP4 (3,2,2,1), TP4 (KV replicated) -> TP2"),
     "tiny_mla": _wl(
         "tiny_mla",
         make_spec(family="moe_mla", L=2, H=40, nq=4, V=0, has_embeddings=0, E=8,

@@ -31,8 +31,18 @@ def _layout_chunks(spec, lay, lg):
     gen = lay["kind"] == "gen"
     grouped = (not gen) and lay["expert_layout"] == "grouped"
     L, H = spec["L"], spec["H"]
-    Lp = L // P
     moe = fam != "dense_gqa"
+    tied = bool(spec.get("tied_embeddings", 0))
+    # layers of each stage in storage order
+    vpp = lay.get("vpp", 1)
+    first, last = lay.get("first_stage_layers", 0), lay.get("last_stage_layers", 0)
+    if first or last:
+        mid = (L - first - last) // (P - 2) if P > 2 else 0
+        stage_layers = np.split(np.arange(L), np.cumsum([first] + [mid] * (P - 2)))
+    else:
+        # chunks dealt round-robin: chunk c -> stage c mod P
+        chunks = np.arange(L).reshape(vpp, P, L // (P * vpp))
+        stage_layers = [chunks[:, p, :].reshape(-1) for p in range(P)]
     nd = P * T
     bufs = [[] for _ in range(nd + (P * X if moe else 0))]
 
@@ -47,7 +57,7 @@ def _layout_chunks(spec, lay, lg):
         if spec["has_embeddings"] and p == 0:
             for t, sh in enumerate(rows_split(lg[("emb", -1, -1)])):
                 dense[t].append(sh)
-        for l in range(p * Lp, (p + 1) * Lp):
+        for l in (int(x) for x in stage_layers[p]):
             for t in range(T):
                 dense[t].append(lg[("ln1", l, -1)])
             if fam == "moe_mla":
@@ -64,7 +74,13 @@ def _layout_chunks(spec, lay, lg):
                 for qn, kn, vn in names:
                     q, k, v = lg[(qn, l, -1)], lg[(kn, l, -1)], lg[(vn, l, -1)]
                     w = q.shape[1]
-                    if gen:
+                    if T > nkv:
+                        # each KV head is repeated for the T/nkv ranks that share it
+                        kr = np.repeat(k.reshape(nkv, d, w), T // nkv, axis=0)
+                        vr = np.repeat(v.reshape(nkv, d, w), T // nkv, axis=0)
+                        for t, a in enumerate(rows_split(q)):
+                            per_rank[t].append(np.concatenate([a, kr[t], vr[t]], axis=0))
+                    elif gen:
                         # per rank: its query rows, then key rows, then value rows
                         for t, (a, b, c) in enumerate(zip(rows_split(q), rows_split(k), rows_split(v))):
                             per_rank[t].append(np.concatenate([a, b, c], axis=0))
@@ -106,8 +122,16 @@ def _layout_chunks(spec, lay, lg):
                         for a, b in zip(fc1, fc2):
                             eb += [a, b]
         if spec["has_embeddings"] and p == P - 1:
-            for t, sh in enumerate(rows_split(lg[("lm_head", -1, -1)])):
-                dense[t] += [lg[("final_ln", -1, -1)], sh]
+            if not tied:
+                tail = rows_split(lg[("lm_head", -1, -1)])
+            elif P > 1:
+                tail = rows_split(lg[("emb", -1, -1)])  # the last stage's own copy of the tied embedding
+            else:
+                tail = [None] * T
+            for t in range(T):
+                dense[t].append(lg[("final_ln", -1, -1)])
+                if tail[t] is not None:
+                    dense[t].append(tail[t])
     return bufs
 
 

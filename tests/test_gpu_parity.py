@@ -286,6 +286,12 @@ def test_c1_qwen25_7b_shape_whole_output_against_the_oracle():
     pads_untouched(plan, dst)
 
 
+def test_c1r_kv_replication_and_interleaved_stages_at_full_size():
+    print("case C1R full", flush=True)
+    plan, src, dst = run_case(WORKLOADS["C1R"], "normal")
+    pads_untouched(plan, dst)
+
+
 def test_c2_qwen25_32b_shape_sampled_and_one_rank_whole():
     wl = WORKLOADS["C2"]
     print("case C2", flush=True)

@@ -378,9 +378,58 @@ def test_invalid_shapes_are_rejected():
     spec = dict(WORKLOADS["C0"]["spec"])
     with pytest.raises(ValueError):
         fast.buffer_sizes(spec, make_layout(kind="train", tp=3))
-    with pytest.raises(ValueError):  # tp > nkv
-        fast.buffer_sizes(spec, make_layout(kind="train", tp=4))
     with pytest.raises(ValueError):
         fast.buffer_sizes(spec, make_layout(kind="gen", tp=1, pp=2))
+    # KV heads neither divide nor are divided by the tensor ranks
+    odd = dict(spec, nq=12, nkv=4, H=768)
+    with pytest.raises(ValueError):
+        fast.buffer_sizes(odd, make_layout(kind="train", tp=6))
     with pytest.raises(AssertionError):
-        locate.Layout(spec, make_layout(kind="train", tp=4))
+        locate.Layout(odd, make_layout(kind="train", tp=6))
+    # pipeline shapes
+    for bad in (dict(pp=2, vpp=2, first_stage_layers=1, last_stage_layers=1), dict(pp=2, vpp=3),
+                dict(pp=2, first_stage_layers=1, last_stage_layers=2), dict(pp=1, first_stage_layers=1, last_stage_layers=1)):
+        with pytest.raises(ValueError):
+            fast.buffer_sizes(spec, make_layout(kind="train", tp=2, **bad))
+        with pytest.raises(AssertionError):
+            locate.Layout(spec, make_layout(kind="train", tp=2, **bad))
+
+
+def test_replicated_kv_heads_and_tied_embedding_are_read_from_their_first_copy():
+    """KV heads shared by T/nkv ranks are read from the lowest such rank; a tied embedding
+    from the first stage.  Source buffers hold their own index, so the origin shows."""
+    w = TINY["tiny_kvrep"]
+    spec = with_eb(w["spec"], 2)
+    gen1 = make_layout(kind="gen", tp=1)
+    S, D = locate.Layout(spec, w["src"]), locate.Layout(spec, gen1)
+    src = [np.full(n // 2, 100 + b, dtype=np.uint16) for b, n in enumerate(S.buf_bytes)]
+    for maker in ("definition", "loop"):
+        dst = sentinel_bufs(D.buf_bytes, [True], 2)
+        if maker == "definition":
+            locate.reshard_definition(spec, w["src"], gen1, src, dst)
+        else:
+            fast.reshard(spec, w["src"], gen1, src, dst)
+        H, nq, nkv, d = spec["H"], spec["nq"], spec["nkv"], spec["d"]
+        for l in range(spec["L"]):
+            p = S.layer_stage[l]
+            off = D.dense_off[0][("qkv_w", l)] // 2
+            blk = dst[0][off:off + (nq + 2 * nkv) * d * H].reshape(-1, H)
+            k, v = blk[nq * d:(nq + nkv) * d], blk[(nq + nkv) * d:]
+            for head in range(nkv):  # 4 ranks, 2 KV heads: head h is read from rank 2h of its stage
+                assert np.all(k[head * d:(head + 1) * d] == 100 + p * 4 + 2 * head)
+                assert np.all(v[head * d:(head + 1) * d] == 100 + p * 4 + 2 * head)
+        off = D.dense_off[0][("emb", -1)] // 2
+        emb = dst[0][off:off + spec["V"] * H].reshape(4, -1)
+        assert [int(x[0]) for x in emb] == [100, 101, 102, 103] and all(np.all(x == x[0]) for x in emb)
+
+
+def test_virtual_pipeline_and_uneven_stage_assignment():
+    """Interleaved chunks: with 8 layers, 2 stages, 2 chunks per stage, stage 0 stores layers
+    0, 1, 4, 5.  Uneven: 3 + 2 + 2 + 1."""
+    a = locate.Layout(TINY["tiny_kvrep"]["spec"], TINY["tiny_kvrep"]["src"])
+    assert a.stage_layers == [[0, 1, 4, 5], [2, 3, 6, 7]]
+    b = locate.Layout(TINY["tiny_uneven"]["spec"], TINY["tiny_uneven"]["src"])
+    assert b.stage_layers == [[0, 1, 2], [3, 4], [5, 6], [7]]
+    # storage order inside a stage follows that list
+    names = [(n, l) for (n, l, j, off, nb) in a.stored[0] if n == "ln1"]
+    assert names == [("ln1", 0), ("ln1", 1), ("ln1", 4), ("ln1", 5)]

@@ -117,11 +117,11 @@ def test_tensor_table_matches_the_oracle_layout():
             want = [(b, n, l, off, nb) for b in range(L.nbufs) for (n, l, j, off, nb) in L.stored[b]]
             assert got == want
             for t in plan.tensors(side):
-                assert t["replicated"] == (t["name"] in locate.REPLICATED)
+                assert t["replicated"] == (t["name"] in locate.REPLICATED or t["name"] == "emb_tied")
                 assert t["offset"] % 256 == 0
 
 
-@pytest.mark.parametrize("name", ["C0", "C1", "C2", "C3", "C3P", "C4"])
+@pytest.mark.parametrize("name", ["C0", "C1", "C1R", "C2", "C3", "C3P", "C4"])
 def test_full_size_plans_cover_every_destination_byte_once(name):
     """Interval analysis at the benchmark shapes: the destination intervals of all
     descriptor rows are pairwise disjoint and their union is exactly the stored
@@ -219,7 +219,12 @@ def test_invalid_requests_return_error_codes():
     gen = make_layout(kind="gen", tp=1)
     cases = [
         (spec, make_layout(kind="train", tp=3), gen, binding.ERR_UNSUPPORTED),   # heads % tp
-        (spec, make_layout(kind="train", tp=4), gen, binding.ERR_UNSUPPORTED),   # tp > nkv
+        (dict(spec, nq=12, nkv=4, H=768), make_layout(kind="train", tp=6), gen, binding.ERR_UNSUPPORTED),  # 6 vs 4 KV heads
+        (spec, make_layout(kind="train", tp=2, pp=2, vpp=2, first_stage_layers=1, last_stage_layers=1), gen, binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2, pp=2, vpp=3), gen, binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2, pp=2, first_stage_layers=1, last_stage_layers=2), gen, binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2, pp=1, first_stage_layers=1, last_stage_layers=1), gen, binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2, vpp=-1), gen, binding.ERR_INVALID_ARG),
         (spec, make_layout(kind="train", tp=2, pp=3), gen, binding.ERR_UNSUPPORTED),
         (spec, make_layout(kind="train", tp=2), make_layout(kind="gen", tp=1, pp=2), binding.ERR_UNSUPPORTED),
         (spec, make_layout(kind="train", tp=2, ep=2), gen, binding.ERR_UNSUPPORTED),
