@@ -63,16 +63,16 @@ WORKLOADS = {
         make_layout(kind="train", tp=4, pp=2),
         make_layout(kind="gen", tp=2),
         1001, "Qwen2.5-7B-shaped, TP4 PP2 -> TP2"),
-    # The same 7B shape under a wider training layout: TP8 (each of the 4 KV heads shared by two
-    # ranks), PP2 with 2 interleaved chunks per stage -> generation TP2.  Not a task config; it
-    # exercises the layout options beyond them at full size.
+    # Not a task config: an 8B-class GQA shape (32 query / 8 KV heads) under a wide training
+    # layout, TP16 (every KV head shared by two ranks), PP2 with 2 interleaved chunks per
+    # stage -> generation TP4.  It exercises the layout options beyond the task's at full size.
     "C1R": _wl(
         "C1R",
-        make_spec(family="dense_gqa", L=28, H=3584, nq=28, nkv=4, d=128, I=18944,
-                  V=152064, qkv_bias=1),
-        make_layout(kind="train", tp=8, pp=2, vpp=2),
-        make_layout(kind="gen", tp=2),
-        1005, "Qwen2.5-7B-shaped, TP8 (KV heads replicated) PP2 VPP2 -> TP2"),
+        make_spec(family="dense_gqa", L=32, H=4096, nq=32, nkv=8, d=128, I=14336,
+                  V=128256),
+        make_layout(kind="train", tp=16, pp=2, vpp=2),
+        make_layout(kind="gen", tp=4),
+        1005, "8B-class GQA shape, TP16 (KV heads replicated) PP2 VPP2 -> TP4"),
     # Qwen2.5-32B-shaped dense decoder, training TP8 PP4 -> generation TP4.
     "C2": _wl(
         "C2",
