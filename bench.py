@@ -36,6 +36,7 @@ def parse():
                     help="queue the swap-out before the repack so the two overlap (under rocprofv3 the runtime "
                          "copies with shader kernels instead of the DMA engines, which starves the repack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verbose", action="store_true", help="per-step timings on stderr")
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--tuning", default="", help="e.g. tile_bytes=65536,unroll=8")
     return ap.parse_args()
@@ -165,6 +166,9 @@ def main():
                 out_s.append(t1 - t0)
                 in_s.append(t3 - t2)
                 freed.append(before - after)
+                if a.verbose:
+                    print("step: kernel %.3f ms, swap-out %.1f GB/s, swap-in %.1f GB/s" % (
+                        kernel_ms[-1], src_bytes / (t1 - t0) / 1e9, src_bytes / (t3 - t2) / 1e9), file=sys.stderr)
 
     for _ in range(a.warmup):
         step(False)

@@ -369,14 +369,24 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
                    nt = uint32_t(plan->transpose_tiles.size());
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
     const uint32_t wanted = tn.blocks_per_cu ? uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu) : 0xFFFFFFFFu;
-    if (nc) {
+    if (nc && tn.blocks_per_cu) {
         dim3 grid(std::min(nc, wanted)), block(tn.block_threads);
         launch_copy(tn, grid, block, stream, tiles, nc, pt);
         if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
+    } else if (nc) {
+        // one tile per workgroup; a launch may not exceed 2^32 - 1 lanes in x, so very long
+        // tables go out in slices
+        const uint32_t per_launch = 0xFFFFFFFFu / uint32_t(tn.block_threads);
+        for (uint32_t first = 0; first < nc; first += per_launch) {
+            const uint32_t n = std::min(per_launch, nc - first);
+            launch_copy(tn, dim3(n), dim3(tn.block_threads), stream, tiles + first, n, pt);
+            if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
+        }
     }
     if (nf) {
         const Tile *ft = tiles + nc;
         const int shape = plan->fast_rows * 1000 + plan->fast_cols;
+        if (uint64_t(nf) * 1024 > 0xFFFFFFFFull) return fail(RESHARD_ERR_UNSUPPORTED, "too many transposing tiles for one launch");
 #define RESHARD_T16(TI, TK)                                                                                  \
     case TI * 1000 + TK:                                                                                     \
         hipLaunchKernelGGL((repack_transpose16_kernel<TI, TK>), dim3(nf),                                    \

@@ -6,6 +6,9 @@ totals (which for the dense shapes are the public parameter counts of the models
 the paper trains), invariants (identity, round trip) and planted mistakes.
 """
 
+import json
+import os
+
 import numpy as np
 import pytest
 
@@ -270,15 +273,32 @@ def logical_bytes(spec):
     return sum(R * C for *_, R, C in locate.logical_tensors(spec)) * spec["elem_bytes"]
 
 
+GOLDEN = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.json")))
+
+
 def test_byte_totals_match_public_parameter_counts():
     """bf16 bytes of the Qwen2.5-7B / 32B shapes are twice the models' public
-    parameter counts (7,615,616,512 and 32,763,876,352)."""
-    assert logical_bytes(WORKLOADS["C1"]["spec"]) == 2 * 7_615_616_512 == 15_231_233_024
-    assert logical_bytes(WORKLOADS["C2"]["spec"]) == 2 * 32_763_876_352 == 65_527_752_704
+    parameter counts (tests/golden/paper_values.json)."""
+    params = GOLDEN["public_parameter_counts"]
+    assert logical_bytes(WORKLOADS["C1"]["spec"]) == 2 * params["Qwen2.5-7B"] == 15_231_233_024
+    assert logical_bytes(WORKLOADS["C2"]["spec"]) == 2 * params["Qwen2.5-32B"] == 65_527_752_704
     assert logical_bytes(WORKLOADS["C0"]["spec"]) == 3_951_104
-    # Qwen3-30B-A3B: 30,532,122,624 parameters minus the per-layer q/k norm
-    # vectors (2 x 128 per layer x 48 layers) that this shape leaves out.
-    assert logical_bytes(WORKLOADS["C3"]["spec"]) == 2 * (30_532_122_624 - 48 * 256) == 61_064_220_672
+    # Qwen3-30B-A3B: its parameters minus the per-layer q/k norm vectors
+    # (2 x 128 per layer x 48 layers) that this shape leaves out.
+    assert logical_bytes(WORKLOADS["C3"]["spec"]) == 2 * (params["Qwen3-30B-A3B"] - 48 * 256) == 61_064_220_672
+
+
+def test_redundant_memory_formula_gives_the_papers_order_of_magnitude():
+    """Eq. (3): R = GDP * (TW / UTP + EW / GEP).  With the Qwen3-MoE-30B shape split into
+    TP weights (everything but the routed experts) and EP weights (the routed experts),
+    any setting with GDP == GEP and GDP >= UTP gives more than the paper's 60 GB."""
+    spec = WORKLOADS["C3"]["spec"]
+    ew = sum(R * C for n, *_, R, C in locate.logical_tensors(spec) if n.startswith("ex_")) * 2 / 1e9
+    tw = logical_bytes(spec) / 1e9 - ew
+    assert abs(ew - 57.98) < 0.01 and abs(tw - 3.08) < 0.01
+    low = GOLDEN["redundant_memory_qwen3_moe_30b_lower_bound_gb"]["value"]
+    for utp, gdp in ((1, 1), (2, 2), (2, 4), (4, 4), (4, 8)):
+        assert gdp * (tw / utp + ew / gdp) > low
 
 
 def test_per_device_share_of_the_32b_model_is_about_8_gb():
@@ -287,6 +307,8 @@ def test_per_device_share_of_the_32b_model_is_about_8_gb():
     w = WORKLOADS["C2"]
     S = locate.Layout(w["spec"], w["src"])
     per_tp_rank = [sum(S.buf_bytes[p * 8 + t] for p in range(4)) for t in range(8)]
+    printed = GOLDEN["released_gb_per_device_qwen25_32b_tp8_to_tp4"]["value"]
+    assert all(round(n / 1e9) == printed for n in per_tp_rank)
     assert all(7.9e9 < n < 8.4e9 for n in per_tp_rank)
     assert abs(sum(per_tp_rank) - 65_527_752_704) < 16e6  # replicated norms + padding only
 
