@@ -176,13 +176,13 @@ typedef struct reshard_mem_stats_t {
 
 /* Knobs of the repack kernel; zero fields keep the built-in default. */
 typedef struct reshard_tuning {
-    int32_t tile_bytes;     /* bytes of work per tile (power of two, 4 KiB .. 512 KiB; default 256 KiB) */
+    int32_t tile_bytes;     /* bytes of work per tile (power of two, 4 KiB .. 512 KiB; default 64 KiB) */
     int32_t block_threads;  /* 64, 128, 256, 512 or 1024 (default 1024) */
     int32_t blocks_per_cu;  /* 0 (default): one tile per workgroup; n > 0: persistent grid of n per CU */
     int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4, 8 or 16 (default 8) */
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
-                               barrier between a tile's load burst and its store burst (default 7);
-                               -1 = none of them */
+                               barrier between a tile's load burst and its store burst, bit 3: each XCD
+                               walks a contiguous eighth of the tile table (default 15); -1 = none */
     int32_t transpose_rows; /* shape of a register-transposed tile of 2-byte elements: source rows */
     int32_t transpose_cols; /* ... and source columns; each 64, 128 or 256 (default 256 x 256) */
 } reshard_tuning;

@@ -60,11 +60,12 @@ constexpr int kMaxTileUnits = 32768;  // keeps the multiply-high row split exact
 constexpr int kTransposeDim = 64;     // transposing tiles are at most 64 x 64 elements
 
 struct Tuning {
-    int tile_bytes = 256 * 1024;  // two rounds of block_threads * unroll * 16 bytes
+    int tile_bytes = 64 * 1024;   // one half-filled round of block_threads * unroll * 16 bytes
     int block_threads = 1024;
     int blocks_per_cu = 0;        // 0: one tile per workgroup; > 0: persistent grid
     int unroll = 8;
-    int flags = 7;                // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts
+    int flags = 15;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
+                                  // bit 3: each XCD walks a contiguous eighth of the tile table
     int transpose_rows = 256;     // register-transposed tiles of 2-byte elements: rows x cols of the source
     int transpose_cols = 256;
 };

@@ -80,6 +80,8 @@ TUNINGS = [
     dict(tile_bytes=524288, block_threads=1024, unroll=4, blocks_per_cu=1),
     dict(tile_bytes=65536, block_threads=256, unroll=8, blocks_per_cu=16, flags=7),
     dict(tile_bytes=131072, block_threads=1024, unroll=16, flags=7),
+    dict(tile_bytes=262144, block_threads=1024, unroll=8, flags=11),
+    dict(tile_bytes=4096, block_threads=256, unroll=2, flags=8),
 ]
 
 
