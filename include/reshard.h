@@ -119,14 +119,20 @@ typedef struct reshard_layout {
     int32_t last_stage_layers;  /* ... and on the last; the stages between share the rest evenly */
 } reshard_layout;
 
+/* Weight classes of the paper's redundant-memory example (Problem Statement): tensor-parallel
+ * weights T, expert-parallel weights E, common (replicated) weights C. */
+enum { RESHARD_CLASS_TP = 0, RESHARD_CLASS_EP = 1, RESHARD_CLASS_COMMON = 2 };
+
 /* One stored tensor of a layout (for loading weights into / reading them out of the buffers). */
 typedef struct reshard_tensor_info {
     char name[24];          /* "ln1", "qkv_w", "qkv_b", "wo", "gate_up", "down", "fc1", "w13", ... */
     int32_t layer;          /* -1 for embedding / final norm / lm_head */
     int32_t expert;         /* global expert index of a per-expert tensor, else -1 */
     int32_t buffer;         /* index into src_ptrs / dst_ptrs */
-    int32_t replicated;     /* 1 for a common (replicated) tensor */
+    int32_t replicated;     /* 1 for a common (replicated) tensor or a never-read copy */
     int64_t offset, bytes;  /* placement inside the buffer */
+    int32_t weight_class;   /* RESHARD_CLASS_TP / EP / COMMON */
+    int32_t reserved_;
 } reshard_tensor_info;
 
 /*
@@ -227,6 +233,20 @@ int reshard_plan_buf_used(const reshard_plan *plan, int side, int index);
 /* Stored-tensor table of one side, in (buffer, offset) order. */
 int64_t reshard_plan_num_tensors(const reshard_plan *plan, int side);
 int reshard_plan_tensor(const reshard_plan *plan, int side, int64_t index, reshard_tensor_info *out);
+
+/* Bytes one side stores per weight class, over all its buffers (every copy counted):
+ * out[RESHARD_CLASS_TP], out[RESHARD_CLASS_EP], out[RESHARD_CLASS_COMMON]. */
+int reshard_plan_class_bytes(const reshard_plan *plan, int side, int64_t out[3]);
+
+/*
+ * Redundant memory of a resharding WITHOUT the swap (paper Eq. 3, Problem Statement):
+ *   R = GDP * (TW / UTP + EW / GEP)
+ * with GDP / GEP the generation-side DP and EP sizes, UTP the update-side TP size, TW / EW
+ * the total bytes of the tensor-parallel and expert-parallel weights.  Pure arithmetic;
+ * returns -1 for a non-positive degree.
+ */
+double reshard_redundant_memory_bytes(int gen_dp, double tp_weight_bytes, int update_tp,
+                                      double ep_weight_bytes, int gen_ep);
 
 /* Plan statistics and the descriptor table (copied into caller memory). */
 int reshard_plan_get_info(const reshard_plan *plan, reshard_plan_info *out);

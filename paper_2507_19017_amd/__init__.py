@@ -6,6 +6,7 @@ from .binding import (  # noqa: F401
     copy_baseline,
     get_tuning,
     last_error,
+    redundant_memory_bytes,
     lib,
     set_host_limit,
     set_tuning,

@@ -37,7 +37,7 @@ class Layout(C.Structure):
 class TensorInfo(C.Structure):
     _fields_ = [("name", C.c_char * 24), ("layer", C.c_int32), ("expert", C.c_int32),
                 ("buffer", C.c_int32), ("replicated", C.c_int32), ("offset", C.c_int64),
-                ("bytes", C.c_int64)]
+                ("bytes", C.c_int64), ("weight_class", C.c_int32), ("reserved_", C.c_int32)]
 
 
 class Desc(C.Structure):
@@ -92,6 +92,8 @@ def lib():
             "reshard_plan_num_tensors": (C.c_int64, [P, C.c_int]),
             "reshard_plan_tensor": (C.c_int, [P, C.c_int, C.c_int64, C.POINTER(TensorInfo)]),
             "reshard_plan_get_info": (C.c_int, [P, C.POINTER(PlanInfo)]),
+            "reshard_plan_class_bytes": (C.c_int, [P, C.c_int, C.POINTER(C.c_int64)]),
+            "reshard_redundant_memory_bytes": (C.c_double, [C.c_int, C.c_double, C.c_int, C.c_double, C.c_int]),
             "reshard_plan_desc": (C.c_int, [P, C.c_int64, C.POINTER(Desc)]),
             "reshard_plan_prepare": (C.c_int, [P]),
             "reshard_execute": (C.c_int, [P, C.POINTER(P), C.POINTER(P), P]),
@@ -118,6 +120,7 @@ EXPORTS = (
     "reshard_last_error", "reshard_version", "reshard_set_tuning", "reshard_get_tuning",
     "reshard_plan_create", "reshard_plan_destroy", "reshard_plan_num_bufs", "reshard_plan_buf_bytes",
     "reshard_plan_buf_used", "reshard_plan_num_tensors", "reshard_plan_tensor", "reshard_plan_get_info",
+    "reshard_plan_class_bytes", "reshard_redundant_memory_bytes",
     "reshard_plan_desc", "reshard_plan_prepare", "reshard_execute", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
     "reshard_swap_wait", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
@@ -159,6 +162,10 @@ def set_host_limit(limit: int) -> None:
 
 def copy_baseline(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
     _check(lib().reshard_copy_baseline(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), int(nbytes), C.c_void_p(stream)))
+
+
+def redundant_memory_bytes(gen_dp: int, tp_weight_bytes: float, update_tp: int, ep_weight_bytes: float, gen_ep: int) -> float:
+    return lib().reshard_redundant_memory_bytes(gen_dp, tp_weight_bytes, update_tp, ep_weight_bytes, gen_ep)
 
 
 def make_spec(spec: dict) -> ModelSpec:
@@ -224,8 +231,14 @@ class Plan:
         for i in range(n):
             _check(lib().reshard_plan_tensor(self._h, side, i, C.byref(ti)))
             out.append(dict(name=ti.name.decode(), layer=ti.layer, expert=ti.expert, buffer=ti.buffer,
-                            replicated=bool(ti.replicated), offset=ti.offset, bytes=ti.bytes))
+                            replicated=bool(ti.replicated), offset=ti.offset, bytes=ti.bytes,
+                            weight_class="TEC"[ti.weight_class]))
         return out
+
+    def class_bytes(self, side: int) -> dict:
+        out = (C.c_int64 * 3)()
+        _check(lib().reshard_plan_class_bytes(self._h, side, out))
+        return {"T": out[0], "E": out[1], "C": out[2]}
 
     def info(self) -> dict:
         pi = PlanInfo()

@@ -217,6 +217,20 @@ extern "C" int reshard_plan_tensor(const reshard_plan *plan, int side, int64_t i
     return RESHARD_OK;
 }
 
+extern "C" int reshard_plan_class_bytes(const reshard_plan *plan, int side, int64_t out[3]) {
+    const Side *s = side_of(plan, side);
+    if (!s || !out) return fail(RESHARD_ERR_INVALID_ARG, "bad plan, side or out");
+    out[0] = out[1] = out[2] = 0;
+    for (const reshard_tensor_info &t : s->tensors) out[t.weight_class] += t.bytes;
+    return RESHARD_OK;
+}
+
+extern "C" double reshard_redundant_memory_bytes(int gen_dp, double tp_weight_bytes, int update_tp,
+                                                 double ep_weight_bytes, int gen_ep) {
+    if (gen_dp <= 0 || update_tp <= 0 || gen_ep <= 0) return -1.0;
+    return gen_dp * (tp_weight_bytes / update_tp + ep_weight_bytes / gen_ep);
+}
+
 extern "C" int reshard_plan_get_info(const reshard_plan *plan, reshard_plan_info *out) {
     if (!plan || !out) return fail(RESHARD_ERR_INVALID_ARG, "NULL argument");
     *out = plan->info;
@@ -270,6 +284,11 @@ extern "C" int reshard_execute(reshard_plan *p, const void *const *src_ptrs, voi
         }
     }
     if (int rc = ensure_device_table(p)) return rc;
+    {
+        int dev = -1;
+        if (hipError_t e = hipGetDevice(&dev)) return hip_fail(e, "hipGetDevice");
+        if (dev != p->device) return fail(RESHARD_ERR_INVALID_ARG, "the plan's tile table lives on another device than the current one");
+    }
     for (size_t i = 0; i < p->src_ptrs.size(); ++i) p->src_ptrs[i] = p->src.used[i] ? src_ptrs[i] : nullptr;
     for (size_t j = 0; j < p->dst_ptrs.size(); ++j) p->dst_ptrs[j] = p->dst.used[j] ? dst_ptrs[j] : nullptr;
     if (int rc = launch_repack(p, static_cast<hipStream_t>(stream))) return rc;

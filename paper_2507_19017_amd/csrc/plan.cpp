@@ -43,8 +43,10 @@ class BufferBuilder {
   public:
     // A destination records every copy of a tensor.  A source records only the copy that is
     // read: common tensors on tensor rank 0 (`rank0`), other replicas where marked primary.
-    BufferBuilder(Side &side, int buf, int eb, bool record_frags, bool is_source, bool rank0)
-        : side_(side), buf_(buf), eb_(eb), frags_(record_frags), src_(is_source), rank0_(rank0) {}
+    BufferBuilder(Side &side, int buf, int eb, bool record_frags, bool is_source, bool rank0,
+                  bool expert_buffer = false)
+        : side_(side), buf_(buf), eb_(eb), frags_(record_frags), src_(is_source), rank0_(rank0),
+          expert_buffer_(expert_buffer) {}
 
     // Starts a stored tensor of `elems` elements; returns its byte offset.
     int64_t begin(const char *name, int layer, int expert, int64_t elems, bool replicated) {
@@ -55,6 +57,7 @@ class BufferBuilder {
         ti.expert = expert;
         ti.buffer = buf_;
         ti.replicated = replicated ? 1 : 0;
+        ti.weight_class = expert_buffer_ ? RESHARD_CLASS_EP : replicated ? RESHARD_CLASS_COMMON : RESHARD_CLASS_TP;
         ti.offset = off_;
         ti.bytes = elems * eb_;
         side_.tensors.push_back(ti);
@@ -78,6 +81,7 @@ class BufferBuilder {
     void whole(const char *name, int id, int layer, int64_t r0, int64_t rows, int64_t c0,
                int64_t cols, bool primary = true) {
         int64_t at = begin(name, layer, -1, rows * cols, is_replicated(id) || !primary);
+        if (!is_replicated(id)) side_.tensors.back().weight_class = RESHARD_CLASS_TP;  // a never-read copy of a shard
         frag(id, layer, -1, r0, r0 + rows, c0, c0 + cols, at, cols, false, primary);
     }
 
@@ -86,7 +90,7 @@ class BufferBuilder {
   private:
     Side &side_;
     int buf_, eb_;
-    bool frags_, src_, rank0_;
+    bool frags_, src_, rank0_, expert_buffer_;
     int64_t off_ = 0;
 };
 
@@ -275,7 +279,7 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
         for (int x = 0; x < X; ++x) {
             const int b = out.nd + p * X + x;
             const bool kept = is_source || l.ep_rank_filter < 0 || l.ep_rank_filter == x;
-            BufferBuilder bb(out, b, eb, kept, is_source, true);
+            BufferBuilder bb(out, b, eb, kept, is_source, true, true);
             if (!is_source) out.used[b] = kept;
             for (const int L_ : stage_layers[p]) {
                 if (gen || grouped) {

@@ -214,6 +214,28 @@ def test_sampled_descriptor_rows_agree_with_the_definition_oracle_at_full_size()
             assert hit == (int(a), int(ao)), (name, int(b), int(bo))
 
 
+def test_weight_classes_and_the_redundant_memory_formula():
+    """Classes T / E / C of the paper's redundant-memory example, and Eq. (3) on them."""
+    from paper_2507_19017_amd import redundant_memory_bytes
+    w = WORKLOADS["C3"]
+    plan = Plan(w["spec"], w["src"], w["dst"])
+    src = plan.class_bytes(0)
+    # source TP1: experts 57.98 GB, replicated norms + routers, the rest tensor-parallel class
+    assert src["E"] == 57_982_058_496
+    assert src["T"] + src["C"] + src["E"] == 61_064_220_672
+    common = sum(R * C for n, *_, R, C in locate.logical_tensors(w["spec"]) if n in locate.REPLICATED) * 2
+    assert src["C"] == common
+    dst = plan.class_bytes(1)
+    assert dst["E"] == src["E"] and dst["T"] == src["T"] and dst["C"] == 2 * common  # TP2: two copies
+    for t in plan.tensors(0):
+        assert t["weight_class"] == ("E" if t["buffer"] >= 2 else "C" if t["name"] in locate.REPLICATED else "T")
+    # Eq. (3) with TW = T + C bytes and EW = E bytes: the paper's "more than 60 GB"
+    tw, ew = src["T"] + src["C"], src["E"]
+    r = redundant_memory_bytes(4, tw, 4, ew, 4)
+    assert r == 4 * (tw / 4 + ew / 4) and r / 1e9 > 60
+    assert redundant_memory_bytes(0, tw, 4, ew, 4) == -1.0
+
+
 def test_invalid_requests_return_error_codes():
     spec = dict(WORKLOADS["C0"]["spec"])
     gen = make_layout(kind="gen", tp=1)
