@@ -219,10 +219,12 @@ def main():
     torch.cuda.synchronize()
     plain_gbps = 2 * cp_n / (min(x.elapsed_time(y) for x, y in evs[1:]) / 1e3) / 1e9
 
-    traffic = None
+    traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "repack_hbm_traffic.json")  # from rocprofv3 --pmc runs
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(a.workload)
+        traffic_detail = json.load(open(tpath)).get(a.workload)
+        if traffic_detail:
+            traffic = traffic_detail["total_bytes"]  # HBM bytes per execute, fetch + write, counter-based
 
     link = None if a.no_link_probe or a.no_swap else link_probe()
     out = {
@@ -239,6 +241,7 @@ def main():
                    "swap_overlaps_repack": bool(a.overlap and not a.no_swap)},
         "roofline": {"bound": "hbm", "achieved": round(repack_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(repack_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "algorithmic_bytes": 2 * moved, "traffic_detail": traffic_detail,
                      "kernel_ms_avg": round(k_avg * 1e3, 4), "kernel_ms_min": round(min(kernel_ms), 4),
                      "plain_copy_GBps": round(plain_gbps, 1)},
         "pct_hbm_peak": round(100 * repack_gbps / HBM_PEAK_GBPS, 2),

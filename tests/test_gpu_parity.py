@@ -8,7 +8,7 @@ import torch
 import gpu_util as G
 from oracle import fast, locate
 from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, get_tuning, set_tuning
-from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout
+from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout, make_spec
 
 pytestmark = pytest.mark.gpu
 
@@ -115,6 +115,36 @@ def test_register_transpose_tile_shapes(shape):
         assert plan.info()["num_transpose_tiles"] > 0
     finally:
         set_tuning()
+
+
+DEGENERATE = [
+    # the smallest model the shape rules allow: one head, one layer, 16-byte rows, nothing to split
+    ("one_head", make_spec(family="dense_gqa", L=1, H=8, nq=1, nkv=1, d=8, I=8, V=8),
+     make_layout(kind="train"), make_layout(kind="gen")),
+    # no embeddings at all and a single stage on both sides: only the fused-QKV permutation moves data
+    ("qkv_only_moves", make_spec(family="dense_gqa", L=3, H=64, nq=8, nkv=4, d=8, I=32, V=0, has_embeddings=0),
+     make_layout(kind="train", tp=1), make_layout(kind="gen", tp=1)),
+    # generation -> generation with equal degrees: a pure copy, pads skipped
+    ("gen_identity", make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=2, d=8, V=48, E=4, Ie=24, n_shared=1),
+     make_layout(kind="gen", tp=2, ep=2), make_layout(kind="gen", tp=2, ep=2)),
+    # a destination filter that keeps one dense rank and one expert rank of many
+    ("one_rank_of_each", make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=4, d=8, V=64, E=8, Ie=16),
+     make_layout(kind="train", tp=2, pp=2, ep=4), make_layout(kind="gen", tp=4, ep=8, tp_filter=3, ep_filter=5)),
+    # odd byte counts: 1-byte elements and widths that are not multiples of anything
+    ("odd_bytes", make_spec(family="dense_gqa", L=2, H=7, nq=3, nkv=3, d=5, I=9, V=6, qkv_bias=1, elem_bytes=1),
+     make_layout(kind="train", tp=3), make_layout(kind="gen", tp=1)),
+]
+
+
+@pytest.mark.parametrize("case", DEGENERATE, ids=[c[0] for c in DEGENERATE])
+def test_degenerate_and_ragged_shapes(case):
+    """Edge shapes: nothing to split, a pure copy, single-rank filters, 1-byte ragged rows.
+    (An empty plan does not exist: every valid model has at least one layer.)"""
+    name, spec, src, dst = case
+    print("degenerate", name, flush=True)
+    wl = dict(name=name, spec=spec, src=src, dst=dst, seed=4000)
+    plan, s, d = run_case(wl, "raw16")
+    assert plan.info()["bytes_moved"] > 0
 
 
 def test_copy_baseline_matches_memcpy():

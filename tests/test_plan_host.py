@@ -85,6 +85,34 @@ def test_descriptors_reproduce_the_oracle_on_tiny_models(name, eb):
     assert {i for i, u in enumerate(plan.buf_used(0)) if u} == read
 
 
+def test_degenerate_shapes_through_the_descriptor_interpreter():
+    cases = [
+        (make_spec(family="dense_gqa", L=1, H=8, nq=1, nkv=1, d=8, I=8, V=8), make_layout(kind="train"), make_layout(kind="gen")),
+        (make_spec(family="dense_gqa", L=3, H=64, nq=8, nkv=4, d=8, I=32, V=0, has_embeddings=0),
+         make_layout(kind="train", tp=1), make_layout(kind="gen", tp=1)),
+        (make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=2, d=8, V=48, E=4, Ie=24, n_shared=1),
+         make_layout(kind="gen", tp=2, ep=2), make_layout(kind="gen", tp=2, ep=2)),
+        (make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=4, d=8, V=64, E=8, Ie=16),
+         make_layout(kind="train", tp=2, pp=2, ep=4), make_layout(kind="gen", tp=4, ep=8, tp_filter=3, ep_filter=5)),
+        (make_spec(family="dense_gqa", L=2, H=7, nq=3, nkv=3, d=5, I=9, V=6, qkv_bias=1, elem_bytes=1),
+         make_layout(kind="train", tp=3), make_layout(kind="gen", tp=1)),
+    ]
+    for spec, a, b in cases:
+        eb = spec["elem_bytes"]
+        plan = Plan(spec, a, b)
+        A, B = locate.Layout(spec, a), locate.Layout(spec, b)
+        assert plan.buf_bytes(0) == A.buf_bytes and plan.buf_bytes(1) == B.buf_bytes
+        rng = np.random.default_rng(5)
+        src = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in A.buf_bytes]
+        dst = [np.full(n, SENT, dtype=np.uint8) for n in B.buf_bytes]
+        run_descs(plan.descs(), src, dst)
+        dt = {1: np.uint8, 2: np.uint16}[eb]
+        want = [np.full(n, SENT, dtype=np.uint8) if B.buffer_used(i) else None for i, n in enumerate(B.buf_bytes)]
+        fast.reshard(spec, a, b, [x.view(dt) for x in src], [x.view(dt) if x is not None else None for x in want])
+        for i, wnt in enumerate(want):
+            assert np.array_equal(dst[i], wnt if wnt is not None else np.full(B.buf_bytes[i], SENT, dtype=np.uint8))
+
+
 @pytest.mark.parametrize("pair", ["identity", "back"])
 @pytest.mark.parametrize("name", sorted(TINY))
 def test_identity_and_way_back_plans(name, pair):
