@@ -151,6 +151,23 @@ typedef struct reshard_desc {
     int64_t src_stride, dst_stride;
 } reshard_desc;
 
+/*
+ * One device work item (host-side view of the tile table, for inspection and tests).
+ * kind 0: `rows` rows of `row_units` vectors of `vec_bytes` bytes each, row pitches as given.
+ * kind 1: transposing tile of `rows` source rows x `row_units` elements of `vec_bytes` bytes:
+ *     dst[dst_off + k*dst_stride + i*vec_bytes] = src[src_off + i*src_stride + k*vec_bytes]
+ * tile_class: 0 copy kernel, 1 register-transpose kernel (tuned shape), 2 register-transpose
+ * kernel (64 x 64), 3 generic transpose kernel.
+ */
+typedef struct reshard_tile {
+    int32_t src_buf, dst_buf;
+    int32_t kind, tile_class;
+    int64_t src_off, dst_off;
+    int64_t rows, row_units;
+    int64_t src_stride, dst_stride;
+    int32_t vec_bytes, reserved_;
+} reshard_tile;
+
 typedef struct reshard_plan_info {
     int32_t num_src_bufs, num_dst_bufs;
     int64_t num_descs;      /* copy descriptors after merging */
@@ -251,6 +268,8 @@ double reshard_redundant_memory_bytes(int gen_dp, double tp_weight_bytes, int up
 /* Plan statistics and the descriptor table (copied into caller memory). */
 int reshard_plan_get_info(const reshard_plan *plan, reshard_plan_info *out);
 int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshard_desc *out);
+/* Tile `index` in launch order (0 <= index < num_tiles). */
+int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshard_tile *out);
 
 /*
  * Step "select and copy", run time: one asynchronous kernel launch on `stream`

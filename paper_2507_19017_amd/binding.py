@@ -47,6 +47,13 @@ class Desc(C.Structure):
                 ("dst_stride", C.c_int64)]
 
 
+class TileView(C.Structure):
+    _fields_ = [("src_buf", C.c_int32), ("dst_buf", C.c_int32), ("kind", C.c_int32), ("tile_class", C.c_int32),
+                ("src_off", C.c_int64), ("dst_off", C.c_int64), ("rows", C.c_int64), ("row_units", C.c_int64),
+                ("src_stride", C.c_int64), ("dst_stride", C.c_int64), ("vec_bytes", C.c_int32),
+                ("reserved_", C.c_int32)]
+
+
 class PlanInfo(C.Structure):
     _fields_ = [("num_src_bufs", C.c_int32), ("num_dst_bufs", C.c_int32), ("num_descs", C.c_int64),
                 ("num_tiles", C.c_int64), ("num_transpose_tiles", C.c_int64),
@@ -95,6 +102,7 @@ def lib():
             "reshard_plan_class_bytes": (C.c_int, [P, C.c_int, C.POINTER(C.c_int64)]),
             "reshard_redundant_memory_bytes": (C.c_double, [C.c_int, C.c_double, C.c_int, C.c_double, C.c_int]),
             "reshard_plan_desc": (C.c_int, [P, C.c_int64, C.POINTER(Desc)]),
+            "reshard_plan_tile": (C.c_int, [P, C.c_int64, C.POINTER(TileView)]),
             "reshard_plan_prepare": (C.c_int, [P]),
             "reshard_execute": (C.c_int, [P, C.POINTER(P), C.POINTER(P), P]),
             "reshard_bind_src": (C.c_int, [P, C.POINTER(P)]),
@@ -121,7 +129,7 @@ EXPORTS = (
     "reshard_plan_create", "reshard_plan_destroy", "reshard_plan_num_bufs", "reshard_plan_buf_bytes",
     "reshard_plan_buf_used", "reshard_plan_num_tensors", "reshard_plan_tensor", "reshard_plan_get_info",
     "reshard_plan_class_bytes", "reshard_redundant_memory_bytes",
-    "reshard_plan_desc", "reshard_plan_prepare", "reshard_execute", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
+    "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
     "reshard_swap_wait", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
 )
@@ -251,6 +259,14 @@ class Plan:
         for i in range(n):
             _check(lib().reshard_plan_desc(self._h, i, C.byref(d)))
             out.append({k: getattr(d, k) for k, _ in Desc._fields_})
+        return out
+
+    def tiles(self):
+        n = self.info()["num_tiles"]
+        out, t = [], TileView()
+        for i in range(n):
+            _check(lib().reshard_plan_tile(self._h, i, C.byref(t)))
+            out.append({k: getattr(t, k) for k, _ in TileView._fields_ if k != "reserved_"})
         return out
 
     # ---- the hot path ----------------------------------------------------

@@ -144,19 +144,21 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
         const Tuning tuning = current_tuning();
         p->fast_rows = tuning.transpose_rows;
         p->fast_cols = tuning.transpose_cols;
-        if (int rc = cut_tiles(p->descs, ns, tuning, p->copy_tiles, p->fast_transpose_tiles, p->transpose_tiles)) {
+        if (int rc = cut_tiles(p->descs, ns, tuning, p->copy_tiles, p->fast_transpose_tiles, p->edge_transpose_tiles,
+                               p->transpose_tiles)) {
             delete p;
             return rc;
         }
         if (p->copy_tiles.size() > 0x7FFFFFF0ull || p->transpose_tiles.size() > 0x7FFFFFF0ull ||
-            p->fast_transpose_tiles.size() > 0x7FFFFFF0ull) {
+            p->fast_transpose_tiles.size() > 0x7FFFFFF0ull || p->edge_transpose_tiles.size() > 0x7FFFFFF0ull) {
             delete p;
             return fail(RESHARD_ERR_UNSUPPORTED, "too many tiles");
         }
         p->info.num_src_bufs = ns;
         p->info.num_dst_bufs = nd;
         p->info.num_descs = int64_t(p->descs.size());
-        p->info.num_transpose_tiles = int64_t(p->transpose_tiles.size() + p->fast_transpose_tiles.size());
+        p->info.num_transpose_tiles = int64_t(p->transpose_tiles.size() + p->fast_transpose_tiles.size() +
+                                              p->edge_transpose_tiles.size());
         p->info.num_tiles = int64_t(p->copy_tiles.size()) + p->info.num_transpose_tiles;
         int64_t moved = 0;
         for (const reshard_desc &d : p->descs) moved += d.rows * d.row_bytes;
@@ -240,6 +242,29 @@ extern "C" int reshard_plan_get_info(const reshard_plan *plan, reshard_plan_info
 extern "C" int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshard_desc *out) {
     if (!plan || !out || index < 0 || index >= int64_t(plan->descs.size())) return fail(RESHARD_ERR_INVALID_ARG, "bad plan, index or out");
     *out = plan->descs[size_t(index)];
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshard_tile *out) {
+    if (!plan || !out || index < 0 || index >= plan->info.num_tiles) return fail(RESHARD_ERR_INVALID_ARG, "bad plan, index or out");
+    const std::vector<Tile> *lists[4] = {&plan->copy_tiles, &plan->fast_transpose_tiles, &plan->edge_transpose_tiles,
+                                         &plan->transpose_tiles};
+    int cls = 0;
+    size_t at = size_t(index);
+    while (at >= lists[cls]->size()) at -= lists[cls++]->size();
+    const Tile &t = (*lists[cls])[at];
+    out->src_buf = t.src_buf;
+    out->dst_buf = int32_t(t.dst_buf) - plan->info.num_src_bufs;
+    out->kind = t.kind;
+    out->tile_class = cls;
+    out->src_off = int64_t(t.src_off);
+    out->dst_off = int64_t(t.dst_off);
+    out->rows = t.rows;
+    out->row_units = t.row_units;
+    out->src_stride = t.src_stride;
+    out->dst_stride = t.dst_stride;
+    out->vec_bytes = 1 << t.vec_log2;
+    out->reserved_ = 0;
     return RESHARD_OK;
 }
 

@@ -80,7 +80,7 @@ int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
                         std::vector<reshard_desc> &descs);
 int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
               std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
-              std::vector<Tile> &transpose_tiles);
+              std::vector<Tile> &edge_transpose_tiles, std::vector<Tile> &transpose_tiles);
 
 }  // namespace reshard
 
@@ -89,13 +89,15 @@ struct reshard_plan {
     reshard::Side src, dst;
     std::vector<reshard_desc> descs;
     // copy tiles; full tiles of 2-byte transposes (register path); remaining transposing tiles
-    std::vector<reshard::Tile> copy_tiles, fast_transpose_tiles, transpose_tiles;
+    // (the register path takes the interior in fast_rows x fast_cols tiles and the strips
+    // left over in 64 x 64 tiles; what is still left goes to the generic kernel)
+    std::vector<reshard::Tile> copy_tiles, fast_transpose_tiles, edge_transpose_tiles, transpose_tiles;
     int fast_rows = 0, fast_cols = 0;  // tile shape the fast tiles were cut with
     reshard_plan_info info{};
 
     // device side (created lazily by the first execute)
     int device = -1;
-    void *d_tiles = nullptr;  // copy tiles, then fast transposing tiles, then generic transposing tiles
+    void *d_tiles = nullptr;  // copy, fast transposing, 64 x 64 transposing, generic transposing tiles
     int num_cus = 0;
 
     // bound pointers

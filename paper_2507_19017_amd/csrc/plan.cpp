@@ -436,10 +436,11 @@ int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
 
 int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
               std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
-              std::vector<Tile> &transpose_tiles) {
+              std::vector<Tile> &edge_transpose_tiles, std::vector<Tile> &transpose_tiles) {
     const int tile_bytes = tuning.tile_bytes;
     copy_tiles.clear();
     fast_transpose_tiles.clear();
+    edge_transpose_tiles.clear();
     transpose_tiles.clear();
     auto fits32 = [](int64_t v) { return v >= 0 && v <= 0xFFFFFFFFll; };
     for (const reshard_desc &d : descs) {
@@ -456,33 +457,51 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
             const int64_t cols = d.row_bytes / d.elem_bytes;
             t.kind = 1;
             t.vec_log2 = uint8_t(lg);
-            // the interior, in full tiles, goes to the register-transpose kernel when the
-            // elements are 2 bytes and every row start allows 16-byte accesses
-            int64_t fi = 0, fk = 0;
-            if (d.elem_bytes == 2 && (d.src_off | d.dst_off | d.src_stride | d.dst_stride) % 16 == 0) {
-                const int64_t TI = tuning.transpose_rows, TK = tuning.transpose_cols;
-                fi = d.rows / TI * TI;
-                fk = cols / TK * TK;
-                if (fi == 0 || fk == 0) fi = fk = 0;
-                for (int64_t i = 0; i < fi; i += TI)
-                    for (int64_t k = 0; k < fk; k += TK) {
-                        t.rows = uint32_t(TI);
-                        t.row_units = uint32_t(TK);
+            // Tiles the rectangle [i0,i1) x [k0,k1) of the source matrix with full ti x tk tiles
+            // starting at its corner; returns the extent covered (a multiple of the tile shape).
+            auto tile_rect = [&](int64_t i0, int64_t i1, int64_t k0, int64_t k1, int64_t ti, int64_t tk,
+                                 std::vector<Tile> &out, int64_t &ci, int64_t &ck) {
+                ci = (i1 - i0) / ti * ti;
+                ck = (k1 - k0) / tk * tk;
+                if (ci == 0 || ck == 0) { ci = ck = 0; return; }
+                for (int64_t i = i0; i < i0 + ci; i += ti)
+                    for (int64_t k = k0; k < k0 + ck; k += tk) {
+                        t.rows = uint32_t(std::min(ti, i1 - i));
+                        t.row_units = uint32_t(std::min(tk, k1 - k));
                         t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
                         t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
-                        fast_transpose_tiles.push_back(t);
+                        out.push_back(t);
                     }
+            };
+            // generic tiles: any extent, cut at kTransposeDim
+            auto generic_rect = [&](int64_t i0, int64_t i1, int64_t k0, int64_t k1) {
+                for (int64_t i = i0; i < i1; i += kTransposeDim)
+                    for (int64_t k = k0; k < k1; k += kTransposeDim) {
+                        t.rows = uint32_t(std::min<int64_t>(kTransposeDim, i1 - i));
+                        t.row_units = uint32_t(std::min<int64_t>(kTransposeDim, k1 - k));
+                        t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
+                        t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
+                        transpose_tiles.push_back(t);
+                    }
+            };
+            const bool reg_path = d.elem_bytes == 2 && (d.src_off | d.dst_off | d.src_stride | d.dst_stride) % 16 == 0;
+            if (!reg_path) {
+                generic_rect(0, d.rows, 0, cols);
+                continue;
             }
-            // the rest (edges, other element sizes, odd alignment): small generic tiles
-            for (int64_t i = 0; i < d.rows; i += kTransposeDim)
-                for (int64_t k = (i < fi ? fk : 0); k < cols; k += kTransposeDim) {
-                    const int64_t i_end = i < fi ? std::min<int64_t>(fi, d.rows) : d.rows;
-                    t.rows = uint32_t(std::min<int64_t>(kTransposeDim, i_end - i));
-                    t.row_units = uint32_t(std::min<int64_t>(kTransposeDim, cols - k));
-                    t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
-                    t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
-                    transpose_tiles.push_back(t);
-                }
+            // interior in big register-transposed tiles; the right and bottom strips in 64 x 64
+            // register-transposed tiles; what is left of those (under 64 wide or high) generic
+            int64_t fi, fk;
+            tile_rect(0, d.rows, 0, cols, tuning.transpose_rows, tuning.transpose_cols, fast_transpose_tiles, fi, fk);
+            struct Rect { int64_t i0, i1, k0, k1; };
+            const Rect strips[2] = {{0, fi, fk, cols}, {fi, d.rows, 0, cols}};  // right of the interior; below it
+            for (const Rect &r : strips) {
+                if (r.i0 >= r.i1 || r.k0 >= r.k1) continue;
+                int64_t ei, ek;
+                tile_rect(r.i0, r.i1, r.k0, r.k1, 64, 64, edge_transpose_tiles, ei, ek);
+                generic_rect(r.i0, r.i0 + ei, r.k0 + ek, r.k1);  // right of the 64 x 64 part
+                generic_rect(r.i0 + ei, r.i1, r.k0, r.k1);       // below it
+            }
             continue;
         }
         // widest vector that every row start and the row length allow

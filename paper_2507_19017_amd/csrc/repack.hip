@@ -359,7 +359,8 @@ int ensure_device_table(reshard_plan *plan) {
     int cus = 0;
     if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))
         return hip_fail(e, "hipDeviceGetAttribute");
-    const std::vector<Tile> *lists[3] = {&plan->copy_tiles, &plan->fast_transpose_tiles, &plan->transpose_tiles};
+    const std::vector<Tile> *lists[4] = {&plan->copy_tiles, &plan->fast_transpose_tiles,
+                                         &plan->edge_transpose_tiles, &plan->transpose_tiles};
     size_t total = 0;
     for (auto *l : lists) total += l->size();
     void *mem = nullptr;
@@ -391,7 +392,7 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     for (int i = 0; i < nd; ++i) pt.p[ns + i] = static_cast<char *>(plan->dst_ptrs[i]);
     const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
     const uint32_t nc = uint32_t(plan->copy_tiles.size()), nf = uint32_t(plan->fast_transpose_tiles.size()),
-                   nt = uint32_t(plan->transpose_tiles.size());
+                   ne = uint32_t(plan->edge_transpose_tiles.size()), nt = uint32_t(plan->transpose_tiles.size());
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
     const uint32_t wanted = tn.blocks_per_cu ? uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu) : 0xFFFFFFFFu;
     if (nc && tn.blocks_per_cu) {
@@ -408,14 +409,18 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
             if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
         }
     }
-    if (nf) {
-        const int shape = plan->fast_rows * 1000 + plan->fast_cols;
+    // register-transposed tiles: the interior in the tuned shape, the strips in 64 x 64
+    struct FastClass { uint32_t first, count; int rows, cols; };
+    const FastClass classes[2] = {{nc, nf, plan->fast_rows, plan->fast_cols}, {nc + nf, ne, 64, 64}};
+    for (const FastClass &fc : classes) {
+        if (!fc.count) continue;
+        const int shape = fc.rows * 1000 + fc.cols;
         const int by_xcd = (tn.flags & 8) ? 1 : 0;
-        const uint32_t threads = uint32_t(std::min(plan->fast_rows * plan->fast_cols / 64, 1024));
+        const uint32_t threads = uint32_t(std::min(fc.rows * fc.cols / 64, 1024));
         const uint32_t per_launch = (0xFFFFFFFFu / threads) & ~7u;  // at most 2^32 - 1 lanes per launch
-        for (uint32_t first = 0; first < nf; first += per_launch) {
-            const Tile *ft = tiles + nc + first;
-            const uint32_t n = std::min(per_launch, nf - first);
+        for (uint32_t first = 0; first < fc.count; first += per_launch) {
+            const Tile *ft = tiles + fc.first + first;
+            const uint32_t n = std::min(per_launch, fc.count - first);
             const dim3 grid(by_xcd ? (n + 7) / 8 * 8 : n), block(threads);
 #define RESHARD_T16(TI, TK)                                                                                  \
     case TI * 1000 + TK:                                                                                     \
@@ -433,7 +438,7 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     }
     if (nt) {
         dim3 grid(std::min(nt, wanted)), block(256);
-        const Tile *tt = tiles + nc + nf;
+        const Tile *tt = tiles + nc + nf + ne;
         switch (plan->spec.elem_bytes) {
             case 1: hipLaunchKernelGGL(repack_transpose_kernel<uint8_t>, grid, block, 0, stream, tt, nt, pt); break;
             case 2: hipLaunchKernelGGL(repack_transpose_kernel<uint16_t>, grid, block, 0, stream, tt, nt, pt); break;

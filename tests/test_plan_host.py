@@ -49,6 +49,74 @@ def run_descs(descs, src, dst, counts=None):
                 np.add.at(counts[d["dst_buf"]], b, 1)
 
 
+def run_tiles(tiles, src, dst, counts):
+    """Interpret the device tile table on byte arrays, as reshard.h words it."""
+    for t in tiles:
+        s, d = src[t["src_buf"]], dst[t["dst_buf"]]
+        v = t["vec_bytes"]
+        if t["kind"] == 0:
+            i, u, e = np.meshgrid(np.arange(t["rows"]), np.arange(t["row_units"]), np.arange(v), indexing="ij")
+            a = (t["src_off"] + i * t["src_stride"] + u * v + e).ravel()
+            b = (t["dst_off"] + i * t["dst_stride"] + u * v + e).ravel()
+        else:
+            i, k, e = np.meshgrid(np.arange(t["rows"]), np.arange(t["row_units"]), np.arange(v), indexing="ij")
+            a = (t["src_off"] + i * t["src_stride"] + k * v + e).ravel()
+            b = (t["dst_off"] + k * t["dst_stride"] + i * v + e).ravel()
+        d[b] = s[a]
+        np.add.at(counts[t["dst_buf"]], b, 1)
+
+
+TILE_TUNINGS = [dict(), dict(tile_bytes=4096, transpose_rows=64, transpose_cols=128),
+                dict(tile_bytes=8192, transpose_rows=128, transpose_cols=64), dict(transpose_rows=64, transpose_cols=64)]
+
+
+@pytest.mark.parametrize("tuning", TILE_TUNINGS)
+@pytest.mark.parametrize("name", ["tiny_dense", "tiny_moe_grouped", "mid_moe_grouped", "tiny_kvrep", "C0"])
+def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, tuning):
+    """The cut into device tiles (rows per tile, runs of long rows, vector width, the three
+    levels of transposing tiles) moves exactly what the descriptors say."""
+    w = {**TINY, **WORKLOADS}[name]
+    spec = w["spec"]
+    try:
+        set_tuning(**tuning)
+        plan = Plan(spec, w["src"], w["dst"])
+    finally:
+        set_tuning()
+    S, D = locate.Layout(spec, w["src"]), locate.Layout(spec, w["dst"])
+    rng = np.random.default_rng(17)
+    src = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in S.buf_bytes]
+    dst = [np.full(n, SENT, dtype=np.uint8) for n in D.buf_bytes]
+    cnt = [np.zeros(n, dtype=np.int32) for n in D.buf_bytes]
+    tiles = plan.tiles()
+    assert len(tiles) == plan.info()["num_tiles"]
+    run_tiles(tiles, src, dst, cnt)
+    want = [np.full(n, SENT, dtype=np.uint8) for n in D.buf_bytes]
+    fast.reshard(spec, w["src"], w["dst"], [x.view(np.uint16) for x in src], [x.view(np.uint16) for x in want])
+    for b in range(D.nbufs):
+        assert np.array_equal(dst[b], want[b]), f"buffer {b}"
+        owned = np.zeros(D.buf_bytes[b], dtype=bool)
+        for _, _, _, off, nb in D.stored[b]:
+            owned[off:off + nb] = True
+        assert np.all(cnt[b][owned] == 1) and np.all(cnt[b][~owned] == 0)
+    for t in tiles:
+        units = t["rows"] * t["row_units"]
+        assert 1 <= units <= 32768 and t["vec_bytes"] in (1, 2, 4, 8, 16)
+        if t["kind"] == 0:
+            assert t["tile_class"] == 0
+            assert (t["src_off"] | t["dst_off"]) % t["vec_bytes"] == 0
+            if t["rows"] > 1:
+                assert (t["src_stride"] | t["dst_stride"]) % t["vec_bytes"] == 0
+        else:
+            assert t["tile_class"] in (1, 2, 3)
+            if t["tile_class"] in (1, 2):  # register path: full tiles, 16-byte accesses
+                assert (t["src_off"] | t["dst_off"] | t["src_stride"] | t["dst_stride"]) % 16 == 0
+                assert t["rows"] % 64 == 0 and t["row_units"] % 64 == 0
+    if name == "mid_moe_grouped":  # every level of the transposing cut is exercised
+        shape = (tuning.get("transpose_rows", 256), tuning.get("transpose_cols", 256))
+        want_classes = {(256, 256): {0, 2, 3}, (64, 64): {0, 1, 3}}.get(shape, {0, 1, 2, 3})
+        assert {t["tile_class"] for t in tiles} == want_classes
+
+
 CASES = [(n, eb) for n in sorted(TINY) for eb in (1, 2, 4, 8)]
 
 
