@@ -234,7 +234,10 @@ def test_swap_round_trip_ledger_and_rebinding():
     plan.mark_src_released()
     st = plan.mem_stats()
     assert (st["src_live"], st["released"], st["state"], st["peak_device"]) == (0, nsrc, "released", nsrc + ndst)
+    # the allocator agrees with the ledger: dropping the training copy frees exactly those bytes
+    before = torch.cuda.memory_allocated()
     del src
+    assert before - torch.cuda.memory_allocated() == st["released"]
     with pytest.raises(ReshardError) as e:
         plan.swap_in(h)  # no device home yet
     assert e.value.code == binding.ERR_BAD_STATE
@@ -257,6 +260,32 @@ def test_swap_round_trip_ledger_and_rebinding():
     assert torch.equal(dst[0], dst2[0])
     plan.release_host()
     assert plan.mem_stats()["host_pinned"] == 0
+
+
+def test_swap_in_overlaps_other_work_on_the_callers_stream():
+    """The host-to-device copies run on the plan's side stream: kernels already queued on
+    the caller's stream proceed meanwhile, and work queued after swap_in sees the weights."""
+    wl = WORKLOADS["C0"]
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    src = G.device_sources(plan, wl, "raw16")
+    keep = [s.clone() for s in src]
+    h = G.stream_handle()
+    plan.bind_src(G.ptrs(src))
+    plan.swap_out(h)
+    plan.swap_wait()
+    for s in src:
+        s.zero_()
+    busy = torch.ones(1 << 24, device="cuda")
+    for _ in range(20):  # unrelated work in flight on the caller's stream
+        busy = busy * 1.0001
+    plan.swap_in(h)
+    after = [s.clone() for s in src]  # queued after swap_in on the same stream: must see the weights
+    torch.cuda.synchronize()
+    for a, k in zip(after, keep):
+        assert torch.equal(a, k)
+    assert abs(float(busy[0]) - 1.0001 ** 20) < 1e-3
+    plan.swap_wait()
+    assert plan.mem_stats()["state"] == "resident"
 
 
 def test_pinned_allocation_failure_leaves_the_ledger_unchanged():
