@@ -1,0 +1,99 @@
+// Host-only driver for the plan builder, built by tests/test_plan_sanitizers.py with
+// AddressSanitizer and UndefinedBehaviorSanitizer (g++, no GPU code involved).  It builds the
+// fragment lists, descriptors and tiles of a set of shapes, valid and invalid, and checks a few
+// invariants; the sanitizers abort on any out-of-bounds access, overflow or leak.
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "internal.h"
+
+using namespace reshard;
+
+static reshard_model_spec spec(int family, int L, int H, int nq, int nkv, int d, int I, int V, int bias, int emb,
+                               int E, int Ie, int shared, int eb, int tied = 0) {
+    reshard_model_spec s{};
+    s.struct_size = sizeof s;
+    s.family = family; s.L = L; s.H = H; s.nq = nq; s.nkv = nkv; s.d = d; s.I = I; s.V = V;
+    s.qkv_bias = bias; s.has_embeddings = emb; s.E = E; s.Ie = Ie; s.n_shared = shared; s.elem_bytes = eb;
+    s.tied_embeddings = tied;
+    return s;
+}
+static reshard_layout lay(int kind, int tp, int pp, int ep, int grouped = 0, int tf = -1, int ef = -1, int vpp = 1,
+                          int first = 0, int last = 0) {
+    reshard_layout l{};
+    l.struct_size = sizeof l;
+    l.kind = kind; l.tp = tp; l.pp = pp; l.ep = ep; l.expert_layout = grouped;
+    l.tp_rank_filter = tf; l.ep_rank_filter = ef; l.vpp = vpp; l.first_stage_layers = first; l.last_stage_layers = last;
+    return l;
+}
+
+static int run(const reshard_model_spec &s, const reshard_layout &a, const reshard_layout &b, const Tuning &tn,
+               bool expect_ok) {
+    Side S, D;
+    std::vector<reshard_desc> descs;
+    std::vector<Tile> c, f, e, g;
+    int rc = build_side(s, a, true, S);
+    if (!rc) rc = build_side(s, b, false, D);
+    if (!rc) rc = compile_descriptors(s, S, D, descs);
+    if (!rc) rc = cut_tiles(descs, int(S.buf_bytes.size()), tn, c, f, e, g);
+    if ((rc == 0) != expect_ok) {
+        std::printf("unexpected result %d (expected %s)\n", rc, expect_ok ? "ok" : "an error");
+        return 1;
+    }
+    if (rc) return 0;
+    // bytes of the tiles equal bytes of the descriptors; every access stays inside its buffer
+    long long dbytes = 0, tbytes = 0;
+    for (const reshard_desc &d : descs) dbytes += d.rows * d.row_bytes;
+    auto check = [&](const std::vector<Tile> &v) {
+        for (const Tile &t : v) {
+            const long long unit = 1ll << t.vec_log2;
+            tbytes += (long long)t.rows * t.row_units * unit;
+            const long long sb = S.buf_bytes[t.src_buf], db = D.buf_bytes[t.dst_buf - S.buf_bytes.size()];
+            long long s_end, d_end;
+            if (t.kind == 0) {
+                s_end = (long long)t.src_off + (long long)(t.rows - 1) * t.src_stride + t.row_units * unit;
+                d_end = (long long)t.dst_off + (long long)(t.rows - 1) * t.dst_stride + t.row_units * unit;
+            } else {
+                s_end = (long long)t.src_off + (long long)(t.rows - 1) * t.src_stride + t.row_units * unit;
+                d_end = (long long)t.dst_off + (long long)(t.row_units - 1) * t.dst_stride + t.rows * unit;
+            }
+            if (s_end > sb || d_end > db) { std::printf("tile leaves its buffer\n"); std::exit(1); }
+        }
+    };
+    check(c); check(f); check(e); check(g);
+    if (dbytes != tbytes) { std::printf("tile bytes %lld != descriptor bytes %lld\n", tbytes, dbytes); return 1; }
+    return 0;
+}
+
+int main() {
+    Tuning def;
+    Tuning small; small.tile_bytes = 4096; small.transpose_rows = 64; small.transpose_cols = 128;
+    int bad = 0;
+    const int TR = RESHARD_TRAIN, GEN = RESHARD_GEN;
+    for (const Tuning &tn : {def, small}) {
+        // the task's shapes
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, true);
+        bad += run(spec(0, 28, 3584, 28, 4, 128, 18944, 152064, 1, 1, 0, 0, 0, 2), lay(TR, 4, 2, 1), lay(GEN, 2, 1, 1), tn, true);
+        bad += run(spec(0, 64, 5120, 40, 8, 128, 27648, 152064, 1, 1, 0, 0, 0, 2), lay(TR, 8, 4, 1), lay(GEN, 4, 1, 1), tn, true);
+        bad += run(spec(1, 48, 2048, 32, 4, 128, 0, 151936, 0, 1, 128, 768, 0, 2), lay(TR, 1, 2, 8, 1), lay(GEN, 2, 1, 4), tn, true);
+        // ragged and odd shapes, every element size, filters, the way back, the layout options
+        for (int eb : {1, 2, 4, 8}) {
+            bad += run(spec(0, 4, 48, 8, 4, 8, 40, 64, 1, 1, 0, 0, 0, eb), lay(TR, 4, 2, 1), lay(GEN, 2, 1, 1), tn, true);
+            bad += run(spec(1, 2, 320, 4, 2, 16, 0, 64, 0, 1, 4, 200, 1, eb), lay(TR, 1, 1, 2, 1), lay(GEN, 2, 1, 1), tn, true);
+            bad += run(spec(1, 2, 320, 4, 2, 16, 0, 64, 0, 1, 4, 200, 1, eb), lay(GEN, 2, 1, 1), lay(TR, 1, 1, 2, 1), tn, true);
+            bad += run(spec(0, 8, 48, 8, 2, 8, 40, 64, 1, 1, 0, 0, 0, eb, 1), lay(TR, 4, 2, 1, 0, -1, -1, 2), lay(GEN, 8, 1, 1), tn, true);
+            bad += run(spec(0, 8, 32, 8, 2, 8, 24, 48, 0, 1, 0, 0, 0, eb), lay(TR, 4, 4, 1, 0, -1, -1, 1, 3, 1), lay(GEN, 2, 1, 1, 0, 1), tn, true);
+            bad += run(spec(0, 2, 7, 3, 3, 5, 9, 6, 1, 1, 0, 0, 0, 1), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, true);
+        }
+        // invalid requests must be refused, not crash
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, false);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 3), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, false);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 2, 1), tn, false);
+        bad += run(spec(1, 4, 64, 4, 4, 8, 0, 64, 0, 1, 512, 8, 0, 2), lay(TR, 1, 1, 512), lay(GEN, 1, 1, 1), tn, false);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, 0), lay(GEN, 1, 1, 1), tn, false);
+    }
+    std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
+    return bad ? 1 : 0;
+}
