@@ -117,6 +117,10 @@ typedef struct reshard_layout {
                                chunks, chunk c lives on stage c mod pp, stored in chunk order */
     int32_t first_stage_layers; /* uneven pipeline split: layers on the first stage (0 = even) */
     int32_t last_stage_layers;  /* ... and on the last; the stages between share the rest evenly */
+    int32_t vocab_padded;   /* rows the embedding / lm_head are padded to before the tensor-parallel
+                               split (0 = V; else >= V and divisible by tp).  Rank t stores
+                               vocab_padded/tp rows; rows at or beyond V are padding: never read, never
+                               written */
 } reshard_layout;
 
 /* Weight classes of the paper's redundant-memory example (Problem Statement): tensor-parallel

@@ -144,8 +144,10 @@ class Layout:
         else:
             assert spec["E"] % X == 0
             assert (spec["n_shared"] * spec["Ie"]) % T == 0
+        # rows of the embedding / lm_head before the tensor-parallel split: V, or V padded up
+        self.Vp = lay.get("vocab_padded", 0) or spec["V"]
         if spec["has_embeddings"]:
-            assert spec["V"] % T == 0
+            assert self.Vp >= spec["V"] and self.Vp % T == 0
         self.nd = P * T
         self.ne = P * X if self.moe else 0
         self.nbufs = self.nd + self.ne
@@ -196,7 +198,7 @@ class Layout:
         H, fam = s["H"], s["family"]
         seq = []
         if s["has_embeddings"] and p == 0:
-            seq.append(("emb", -1, s["V"] // T * H))
+            seq.append(("emb", -1, self.Vp // T * H))
         for l in self.stage_layers[p]:
             seq.append(("ln1", l, H))
             if fam == "moe_mla":
@@ -227,10 +229,10 @@ class Layout:
         if s["has_embeddings"] and p == self.P - 1:
             seq.append(("final_ln", -1, H))
             if not self.tied:
-                seq.append(("lm_head", -1, s["V"] // T * H))
+                seq.append(("lm_head", -1, self.Vp // T * H))
             elif self.P > 1:
                 # tied output layer: the last stage keeps its own copy of the embedding shard
-                seq.append(("emb_tied", -1, s["V"] // T * H))
+                seq.append(("emb_tied", -1, self.Vp // T * H))
         return seq
 
     def _expert_sequence(self, p: int):
@@ -277,6 +279,20 @@ class Layout:
                 for x in range(self.X):
                     self.buf_bytes[self.nd + p * self.X + x] = _align(off)
 
+    def owned(self, b: int):
+        """(offset, bytes) of the parts of buffer b that hold logical weights: the stored
+        tensors minus vocabulary padding rows."""
+        s, T = self.spec, self.T
+        out = []
+        for name, layer, j, off, nbytes in self.stored[b]:
+            if name in ("emb", "lm_head", "emb_tied"):
+                n, t = self.Vp // T, b % T
+                real = max(0, min(n, s["V"] - t * n))
+                nbytes = real * s["H"] * s["elem_bytes"]
+            if nbytes:
+                out.append((off, nbytes))
+        return out
+
     # ---- the layout function -------------------------------------------------
     def place(self, name: str, layer: int, expert: int, r, c):
         """All homes of logical element (r, c) of a tensor: [(buffer, byte offset)].
@@ -306,7 +322,7 @@ class Layout:
             return [dense(name, np.zeros_like(r) + t, r * cols + c) for t in range(T)]
 
         if name in ("emb", "lm_head"):
-            n = s["V"] // T
+            n = self.Vp // T  # rows per rank, padding rows included; only rows below V are logical
             homes = [dense(name, r // n, (r % n) * H + c)]
             if name == "emb" and self.tied and self.P > 1:
                 last = (self.P - 1) * T

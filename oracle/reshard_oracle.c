@@ -46,6 +46,7 @@ typedef struct {
     int vpp;                /* virtual pipeline size: layer chunks dealt round-robin to the stages */
     int first_stage_layers; /* uneven split: layers on the first / last stage (0 = even) */
     int last_stage_layers;
+    int vocab_padded;       /* rows the embedding / lm_head are padded to before the split (0 = V) */
 } orc_layout;
 
 enum { FAM_DENSE = 0, FAM_MOE = 1, FAM_MLA = 2 };
@@ -68,6 +69,7 @@ typedef struct {
     orc_spec s;
     orc_layout l;
     int T, P, X, El, nd, ne, moe, grouped, tied;
+    int64_t Vp;      /* vocabulary rows including padding */
     int *stage_of;   /* [L] stage holding a layer */
     int *order;      /* [L] layers sorted by (stage, storage position) */
     int *first;      /* [P+1] range of `order` belonging to a stage */
@@ -105,7 +107,10 @@ static int valid(const orc_spec *s, const orc_layout *l)
         if (s->E <= 0 || s->Ie <= 0 || s->E % l->ep) return 0;
         if ((s->n_shared * s->Ie) % l->tp) return 0;
     }
-    if (s->has_embeddings && (s->V <= 0 || s->V % l->tp)) return 0;
+    if (s->has_embeddings) {
+        int vp = l->vocab_padded ? l->vocab_padded : s->V;
+        if (s->V <= 0 || vp < s->V || vp % l->tp) return 0;
+    }
     return 1;
 }
 
@@ -124,6 +129,7 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
     c->T = l->tp; c->P = l->pp; c->X = l->ep;
     c->moe = s->family != FAM_DENSE;
     c->tied = s->tied_embeddings && s->has_embeddings;
+    c->Vp = l->vocab_padded ? l->vocab_padded : s->V;
     /* which stage holds which layers, and in which order they are stored there */
     c->stage_of = calloc(s->L, sizeof(int));
     c->order = calloc(s->L, sizeof(int));
@@ -164,7 +170,7 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
     for (int p = 0; p < c->P; p++) {
         int64_t off = 0;
 #define PUT(dst, nelem) do { off = up256(off); (dst) = off; off += (int64_t)(nelem) * eb; } while (0)
-        if (s->has_embeddings && p == 0) PUT(c->emb_off, s->V / T * H);
+        if (s->has_embeddings && p == 0) PUT(c->emb_off, c->Vp / T * H);
         for (int at = c->first[p]; at < c->first[p + 1]; at++) {
             int ly = c->order[at];
             int64_t *o = c->doff + (size_t)ly * NSLOT;
@@ -200,8 +206,8 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
         }
         if (s->has_embeddings && p == c->P - 1) {
             PUT(c->final_ln_off, H);
-            if (!c->tied) PUT(c->lm_head_off, s->V / T * H);
-            else if (c->P > 1) PUT(c->emb_tied_off, s->V / T * H);
+            if (!c->tied) PUT(c->lm_head_off, c->Vp / T * H);
+            else if (c->P > 1) PUT(c->emb_tied_off, c->Vp / T * H);
         }
         c->dense_bytes[p] = up256(off);
         if (c->moe) {
@@ -248,7 +254,7 @@ static void src_find(const ctx_t *c, int tid, int ly, int ex, int64_t r, int64_t
     int64_t t = 0, e = 0, ncols = H;
     switch (tid) {
     case T_EMB: case T_LM_HEAD: {
-        int64_t n = s->V / T;
+        int64_t n = c->Vp / T; /* rows per rank, padding rows included */
         t = r / n;
         e = (tid == T_EMB ? c->emb_off : c->lm_head_off) / eb + (r % n) * H + col;
         break;
@@ -397,10 +403,10 @@ static void dst_pieces(const ctx_t *D, pieces_t *ps)
         if (!buf_used(D, b)) continue;
         int p = b / D->T;
         int64_t t = b % D->T;
-        if (s->has_embeddings && p == 0) {
-            int64_t n = s->V / T;
-            add_piece(ps, T_EMB, -1, -1, t * n, n, 0, H, b, D->emb_off, H, 0);
-        }
+        /* real vocabulary rows of this rank: the shard minus padding rows (possibly none) */
+        int64_t vn = D->Vp / T, vreal = s->V - t * vn < vn ? s->V - t * vn : vn;
+        if (s->has_embeddings && p == 0 && vreal > 0)
+            add_piece(ps, T_EMB, -1, -1, t * vn, vreal, 0, H, b, D->emb_off, H, 0);
         for (int at = D->first[p]; at < D->first[p + 1]; at++) {
             int ly = D->order[at];
             const int64_t *o = D->doff + (size_t)ly * NSLOT;
@@ -462,10 +468,11 @@ static void dst_pieces(const ctx_t *D, pieces_t *ps)
             }
         }
         if (s->has_embeddings && p == D->P - 1) {
-            int64_t n = s->V / T;
             add_piece(ps, T_FINAL_LN, -1, -1, 0, 1, 0, H, b, D->final_ln_off, H, 0);
-            if (!D->tied) add_piece(ps, T_LM_HEAD, -1, -1, t * n, n, 0, H, b, D->lm_head_off, H, 0);
-            else if (D->P > 1) add_piece(ps, T_EMB, -1, -1, t * n, n, 0, H, b, D->emb_tied_off, H, 0);
+            if (vreal > 0) {
+                if (!D->tied) add_piece(ps, T_LM_HEAD, -1, -1, t * vn, vreal, 0, H, b, D->lm_head_off, H, 0);
+                else if (D->P > 1) add_piece(ps, T_EMB, -1, -1, t * vn, vreal, 0, H, b, D->emb_tied_off, H, 0);
+            }
         }
     }
     for (int b = D->nd; b < D->nd + D->ne; b++) {

@@ -31,7 +31,7 @@ class ModelSpec(C.Structure):
 class Layout(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(k, C.c_int32) for k in (
         "kind", "tp", "pp", "ep", "expert_layout", "tp_rank_filter", "ep_rank_filter", "vpp",
-        "first_stage_layers", "last_stage_layers")]
+        "first_stage_layers", "last_stage_layers", "vocab_padded")]
 
 
 class TensorInfo(C.Structure):
@@ -194,6 +194,7 @@ def make_layout(lay: dict) -> Layout:
     l.vpp = int(lay.get("vpp", 1))
     l.first_stage_layers = int(lay.get("first_stage_layers", 0))
     l.last_stage_layers = int(lay.get("last_stage_layers", 0))
+    l.vocab_padded = int(lay.get("vocab_padded", 0))
     return l
 
 

@@ -77,6 +77,15 @@ class BufferBuilder {
         side_.frags.push_back(Fragment{make_key(id, layer, expert), r0, r1, c0, c1, buf_, off, ld, transposed});
     }
 
+    // A vocabulary shard: `rows` stored rows of which only those below `vocab` are logical.
+    void vocab_shard(const char *name, int id, int64_t r0, int64_t rows, int64_t vocab, int64_t cols,
+                     bool primary = true) {
+        int64_t at = begin(name, -1, -1, rows * cols, !primary);
+        side_.tensors.back().weight_class = RESHARD_CLASS_TP;
+        const int64_t r1 = std::min(r0 + rows, vocab);
+        if (r1 > r0) frag(id, -1, -1, r0, r1, 0, cols, at, cols, false, primary);
+    }
+
     // A whole stored tensor that is one fragment.
     void whole(const char *name, int id, int layer, int64_t r0, int64_t rows, int64_t c0,
                int64_t cols, bool primary = true) {
@@ -140,7 +149,9 @@ int check_shape(const reshard_model_spec &s, const reshard_layout &l) {
     }
     if (s.has_embeddings) {
         if (s.V <= 0) return fail(RESHARD_ERR_INVALID_ARG, "V must be positive");
-        if (s.V % l.tp) return bad("vocabulary not divisible by tp (padded vocabularies are unsupported)");
+        if (l.vocab_padded < 0 || (l.vocab_padded && l.vocab_padded < s.V))
+            return fail(RESHARD_ERR_INVALID_ARG, "vocab_padded must be 0 or at least V");
+        if ((l.vocab_padded ? l.vocab_padded : s.V) % l.tp) return bad("(padded) vocabulary not divisible by tp");
     }
     return RESHARD_OK;
 }
@@ -195,10 +206,8 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
             // a source reads replicated tensors from tensor rank 0 only
             BufferBuilder bb(out, b, eb, kept, is_source, t == 0);
             if (!is_source) out.used[b] = kept;
-            if (s.has_embeddings && p == 0) {
-                int64_t n = s.V / T;
-                bb.whole("emb", LT_EMB, -1, t * n, n, 0, H);
-            }
+            const int64_t vrows = (l.vocab_padded ? l.vocab_padded : s.V) / T;  // per rank, padding included
+            if (s.has_embeddings && p == 0) bb.vocab_shard("emb", LT_EMB, t * vrows, vrows, s.V, H);
             for (const int L_ : stage_layers[p]) {
                 bb.whole("ln1", LT_LN1, L_, 0, 1, 0, H);
                 if (mla) {
@@ -265,12 +274,11 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
                 }
             }
             if (s.has_embeddings && p == P - 1) {
-                int64_t n = s.V / T;
                 bb.whole("final_ln", LT_FINAL_LN, -1, 0, 1, 0, H);
                 if (!tied)
-                    bb.whole("lm_head", LT_LM_HEAD, -1, t * n, n, 0, H);
+                    bb.vocab_shard("lm_head", LT_LM_HEAD, t * vrows, vrows, s.V, H);
                 else if (P > 1)  // the tied output layer's own copy; never the one a source reads
-                    bb.whole("emb_tied", LT_EMB, -1, t * n, n, 0, H, false);
+                    bb.vocab_shard("emb_tied", LT_EMB, t * vrows, vrows, s.V, H, false);
             }
             out.buf_bytes[b] = bb.finish();
         }

@@ -25,10 +25,11 @@ _SPEC_DEFAULTS = dict(
 # Keys of a layout.  `kind`: "train" or "gen"; `expert_layout`: "per_expert" or
 # "grouped"; the two filters select one rank of the layout (-1 = every rank).
 # `vpp`: virtual pipeline size (interleaved layer chunks); `first_stage_layers` /
-# `last_stage_layers`: uneven pipeline split (0 = even).
+# `last_stage_layers`: uneven pipeline split (0 = even); `vocab_padded`: rows the
+# embedding / lm_head are padded to before the tensor-parallel split (0 = V).
 _LAYOUT_DEFAULTS = dict(kind="train", tp=1, pp=1, ep=1,
                         expert_layout="per_expert", tp_filter=-1, ep_filter=-1,
-                        vpp=1, first_stage_layers=0, last_stage_layers=0)
+                        vpp=1, first_stage_layers=0, last_stage_layers=0, vocab_padded=0)
 
 
 def make_spec(**kw) -> dict:
@@ -157,6 +158,14 @@ TINY = {
         make_layout(kind="train", tp=4, pp=4, first_stage_layers=3, last_stage_layers=1),
         make_layout(kind="gen", tp=2),
         2006, "tiny dense, uneven PP4 (3,2,2,1), TP4 (KV replicated) -> TP2"),
+    # Vocabulary padded differently on the two sides: 50 real rows, padded to 64 for TP4
+    # (the last rank holds 2 real rows and 14 padding rows) and to 54 for TP2.
+    "tiny_vocabpad": _wl(
+        "tiny_vocabpad",
+        make_spec(family="dense_gqa", L=2, H=24, nq=4, nkv=4, d=8, I=24, V=50),
+        make_layout(kind="train", tp=4, pp=2, vocab_padded=64),
+        make_layout(kind="gen", tp=2, vocab_padded=54),
+        2007, "tiny dense, vocabulary 50 padded to 64 (TP4 PP2) -> padded to 54 (TP2)"),
     "tiny_mla": _wl(
         "tiny_mla",
         make_spec(family="moe_mla", L=2, H=40, nq=4, V=0, has_embeddings=0, E=8,

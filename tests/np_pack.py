@@ -24,7 +24,7 @@ def make_logical(spec, tensors, rng, dtype):
     return out
 
 
-def _layout_chunks(spec, lay, lg):
+def _layout_chunks(spec, lay, lg, fill=0):
     """Per buffer, the ordered list of shard arrays (any shape; stored flattened)."""
     fam = spec["family"]
     T, P, X = lay["tp"], lay["pp"], lay["ep"]
@@ -45,6 +45,11 @@ def _layout_chunks(spec, lay, lg):
         stage_layers = [chunks[:, p, :].reshape(-1) for p in range(P)]
     nd = P * T
     bufs = [[] for _ in range(nd + (P * X if moe else 0))]
+    Vp = lay.get("vocab_padded", 0) or spec["V"]
+
+    def vocab_padded(a):  # padding rows appended before the split; they hold the gap value
+        return np.concatenate([a, np.full((Vp - a.shape[0], a.shape[1]), fill, dtype=a.dtype)], axis=0)
+
 
     def rows_split(a):  # column-parallel: split the output rows over ranks
         return np.split(a, T, axis=0)
@@ -55,7 +60,7 @@ def _layout_chunks(spec, lay, lg):
     for p in range(P):
         dense = [bufs[p * T + t] for t in range(T)]
         if spec["has_embeddings"] and p == 0:
-            for t, sh in enumerate(rows_split(lg[("emb", -1, -1)])):
+            for t, sh in enumerate(rows_split(vocab_padded(lg[("emb", -1, -1)]))):
                 dense[t].append(sh)
         for l in (int(x) for x in stage_layers[p]):
             for t in range(T):
@@ -123,9 +128,9 @@ def _layout_chunks(spec, lay, lg):
                             eb += [a, b]
         if spec["has_embeddings"] and p == P - 1:
             if not tied:
-                tail = rows_split(lg[("lm_head", -1, -1)])
+                tail = rows_split(vocab_padded(lg[("lm_head", -1, -1)]))
             elif P > 1:
-                tail = rows_split(lg[("emb", -1, -1)])  # the last stage's own copy of the tied embedding
+                tail = rows_split(vocab_padded(lg[("emb", -1, -1)]))  # the last stage's own copy of the tied embedding
             else:
                 tail = [None] * T
             for t in range(T):
@@ -139,7 +144,7 @@ def pack(spec, lay, lg, dtype, fill):
     """Flat buffers (1-D arrays of `dtype`) of a layout; gaps hold `fill`."""
     eb = np.dtype(dtype).itemsize
     out = []
-    for chunks in _layout_chunks(spec, lay, lg):
+    for chunks in _layout_chunks(spec, lay, lg, fill):
         parts, off = [], 0
         for a in chunks:
             pad = (-off) % 256

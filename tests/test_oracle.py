@@ -331,7 +331,7 @@ def test_destination_bytes_closed_form(name):
             want += n if dl["ep_filter"] in (-1, x) else 0
         else:
             want += n if dl["tp_filter"] < 0 else n // dl["tp"]
-    got = sum(nb for b in range(D.nbufs) if D.buffer_used(b) for *_, nb in D.stored[b])
+    got = sum(nb for b in range(D.nbufs) if D.buffer_used(b) for _, nb in D.owned(b))
     assert got == want
     if name == "C4":
         assert got == 26_276_528_128

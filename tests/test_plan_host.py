@@ -71,7 +71,7 @@ TILE_TUNINGS = [dict(), dict(tile_bytes=4096, transpose_rows=64, transpose_cols=
 
 
 @pytest.mark.parametrize("tuning", TILE_TUNINGS)
-@pytest.mark.parametrize("name", ["tiny_dense", "tiny_moe_grouped", "mid_moe_grouped", "tiny_kvrep", "C0"])
+@pytest.mark.parametrize("name", ["tiny_dense", "tiny_moe_grouped", "mid_moe_grouped", "tiny_kvrep", "tiny_vocabpad", "C0"])
 def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, tuning):
     """The cut into device tiles (rows per tile, runs of long rows, vector width, the three
     levels of transposing tiles) moves exactly what the descriptors say."""
@@ -95,7 +95,7 @@ def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, tunin
     for b in range(D.nbufs):
         assert np.array_equal(dst[b], want[b]), f"buffer {b}"
         owned = np.zeros(D.buf_bytes[b], dtype=bool)
-        for _, _, _, off, nb in D.stored[b]:
+        for off, nb in D.owned(b):
             owned[off:off + nb] = True
         assert np.all(cnt[b][owned] == 1) and np.all(cnt[b][~owned] == 0)
     for t in tiles:
@@ -145,7 +145,7 @@ def test_descriptors_reproduce_the_oracle_on_tiny_models(name, eb):
             continue
         assert np.array_equal(dst[b], want[b]), f"buffer {b}"
         owned = np.zeros(D.buf_bytes[b], dtype=bool)
-        for _, _, _, off, nb in D.stored[b]:
+        for off, nb in D.owned(b):
             owned[off:off + nb] = True
         assert np.all(cnt[b][owned] == 1) and np.all(cnt[b][~owned] == 0)  # exactly once, pads never
         total += int(owned.sum())
@@ -261,8 +261,8 @@ def test_full_size_plans_cover_every_destination_byte_once(name):
         ua = np.concatenate([a[:1], a[brk + 1]])
         ue = np.concatenate([e[brk], e[-1:]])
         # union of the stored tensors, merged where they touch
-        ta = np.array([off for *_, off, nb in D.stored[b]], dtype=np.int64)
-        te = ta + np.array([nb for *_, off, nb in D.stored[b]], dtype=np.int64)
+        ta = np.array([off for off, nb in D.owned(b)], dtype=np.int64)
+        te = ta + np.array([nb for off, nb in D.owned(b)], dtype=np.int64)
         tb = np.flatnonzero(ta[1:] != te[:-1])
         wa = np.concatenate([ta[:1], ta[tb + 1]])
         we = np.concatenate([te[tb], te[-1:]])
@@ -350,6 +350,8 @@ def test_invalid_requests_return_error_codes():
         (spec, make_layout(kind="train", tp=2), make_layout(kind="gen", tp=1, tp_filter=1), binding.ERR_INVALID_ARG),
         (dict(spec, elem_bytes=3), make_layout(kind="train", tp=2), gen, binding.ERR_INVALID_ARG),
         (dict(spec, V=1023), make_layout(kind="train", tp=2), gen, binding.ERR_UNSUPPORTED),
+        (spec, make_layout(kind="train", tp=2, vocab_padded=1000), gen, binding.ERR_INVALID_ARG),   # below V
+        (spec, make_layout(kind="train", tp=2, vocab_padded=1025), gen, binding.ERR_UNSUPPORTED),   # not divisible
         (dict(spec, L=0), make_layout(kind="train", tp=2), gen, binding.ERR_INVALID_ARG),
     ]
     for s, a, b, code in cases:
