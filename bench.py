@@ -133,7 +133,8 @@ def main():
     plan.bind_src(ptrs(src))
     torch.cuda.reset_peak_memory_stats()
 
-    kernel_ms, out_s, in_s, freed = [], [], [], []
+    kernel_ms, out_s, in_s, first_s, freed = [], [], [], [], []
+    first_used = used_s.index(True)
 
     def step(record):
         nonlocal src
@@ -157,6 +158,8 @@ def main():
             plan.bind_src(ptrs(src))
             t2 = time.perf_counter()
             plan.swap_in(h)
+            plan.swap_wait_buffer(first_used)   # the first stage's weights are usable from here on
+            t2b = time.perf_counter()
             plan.swap_wait()
             t3 = time.perf_counter()
         torch.cuda.synchronize()
@@ -165,6 +168,7 @@ def main():
             if not a.no_swap:
                 out_s.append(t1 - t0)
                 in_s.append(t3 - t2)
+                first_s.append(t2b - t2)
                 freed.append(before - after)
                 if a.verbose:
                     print("step: kernel %.3f ms, swap-out %.1f GB/s, swap-in %.1f GB/s" % (
@@ -253,6 +257,7 @@ def main():
         so, si = sum(out_s) / len(out_s), sum(in_s) / len(in_s)
         out["swap"] = {"bytes_each_way": src_bytes, "out_GBps": round(src_bytes / so / 1e9, 2),
                        "in_GBps": round(src_bytes / si / 1e9, 2),
+                       "in_first_buffer_ms": round(sum(first_s) / len(first_s) * 1e3, 2), "in_all_buffers_ms": round(si * 1e3, 2),
                        "link_probe_GBps": None if link is None else {k: round(v, 2) for k, v in link.items()}}
         if link:
             out["swap"]["out_frac_of_link"] = round(src_bytes / so / 1e9 / link["d2h"], 3)

@@ -328,6 +328,16 @@ int reshard_swap_out(reshard_plan *plan, void *stream);
  */
 int reshard_swap_in(reshard_plan *plan, void *stream);
 
+/*
+ * Finer-grained wait: the copy of source buffer `index` alone (the copies of one swap run in
+ * buffer order).  With host_wait != 0 the host blocks until that buffer's copy of the swap in
+ * flight (or the last finished one) is done; otherwise `stream` is made to wait for it, so a
+ * consumer can start on the first pipeline stage's weights while later buffers still stream
+ * in.  The plan's state is not changed (reshard_swap_wait still completes the swap).
+ * Errors: INVALID_ARG (index, unused buffer), BAD_STATE (no swap was ever started), HIP.
+ */
+int reshard_swap_wait_buffer(reshard_plan *plan, int index, void *stream, int host_wait);
+
 /* Blocks the host until the swap copies in flight are done and completes the
  * state change (SWAPPING_OUT -> ON_HOST, SWAPPING_IN -> RESIDENT).  A no-op in
  * any other state. */

@@ -109,6 +109,7 @@ def lib():
             "reshard_swap_out": (C.c_int, [P, P]),
             "reshard_swap_in": (C.c_int, [P, P]),
             "reshard_swap_wait": (C.c_int, [P]),
+            "reshard_swap_wait_buffer": (C.c_int, [P, C.c_int, P, C.c_int]),
             "reshard_mark_src_released": (C.c_int, [P]),
             "reshard_mark_dst_released": (C.c_int, [P]),
             "reshard_release_host": (C.c_int, [P]),
@@ -130,7 +131,7 @@ EXPORTS = (
     "reshard_plan_buf_used", "reshard_plan_num_tensors", "reshard_plan_tensor", "reshard_plan_get_info",
     "reshard_plan_class_bytes", "reshard_redundant_memory_bytes",
     "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
-    "reshard_swap_wait", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_release_host",
+    "reshard_swap_wait", "reshard_swap_wait_buffer", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
 )
 
@@ -288,6 +289,9 @@ class Plan:
 
     def swap_wait(self) -> None:
         _check(lib().reshard_swap_wait(self._h))
+
+    def swap_wait_buffer(self, index: int, stream: int = 0, host_wait: bool = True) -> None:
+        _check(lib().reshard_swap_wait_buffer(self._h, index, C.c_void_p(stream), 1 if host_wait else 0))
 
     def mark_src_released(self) -> None:
         _check(lib().reshard_mark_src_released(self._h))

@@ -66,6 +66,13 @@ int ensure_swap_objects(reshard_plan *p) {
         if (hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) return hip_fail(e, "hipEventCreate");
         p->ev_done = ev;
     }
+    if (p->ev_buf.empty()) p->ev_buf.assign(p->src.buf_bytes.size(), nullptr);
+    for (size_t i = 0; i < p->ev_buf.size(); ++i) {
+        if (!p->src.used[i] || p->ev_buf[i]) continue;
+        hipEvent_t ev;
+        if (hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) return hip_fail(e, "hipEventCreate");
+        p->ev_buf[i] = ev;
+    }
     return RESHARD_OK;
 }
 
@@ -183,6 +190,8 @@ extern "C" int reshard_plan_destroy(reshard_plan *p) {
     if (p->side_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(p->side_stream));
     if (p->ev_ready) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev_ready));
     if (p->ev_done) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev_done));
+    for (void *ev : p->ev_buf)
+        if (ev) (void)hipEventDestroy(static_cast<hipEvent_t>(ev));
     if (p->d_tiles) (void)hipFree(p->d_tiles);
     delete p;
     return RESHARD_OK;
@@ -338,7 +347,9 @@ extern "C" int reshard_swap_out(reshard_plan *p, void *stream) {
         if (!p->src.used[i]) continue;
         if (hipError_t e = hipMemcpyAsync(p->host_copy[i], p->src_ptrs[i], size_t(p->src.buf_bytes[i]), hipMemcpyDeviceToHost, side))
             return hip_fail(e, "hipMemcpyAsync device-to-host");
+        if (hipError_t e = hipEventRecord(static_cast<hipEvent_t>(p->ev_buf[i]), side)) return hip_fail(e, "hipEventRecord");
     }
+    p->swapped_once = true;
     if (hipError_t e = hipEventRecord(done, side)) return hip_fail(e, "hipEventRecord");
     p->state = RESHARD_SRC_SWAPPING_OUT;
     return RESHARD_OK;
@@ -358,10 +369,26 @@ extern "C" int reshard_swap_in(reshard_plan *p, void *stream) {
         if (!p->src.used[i]) continue;
         if (hipError_t e = hipMemcpyAsync(const_cast<void *>(p->src_ptrs[i]), p->host_copy[i], size_t(p->src.buf_bytes[i]), hipMemcpyHostToDevice, side))
             return hip_fail(e, "hipMemcpyAsync host-to-device");
+        if (hipError_t e = hipEventRecord(static_cast<hipEvent_t>(p->ev_buf[i]), side)) return hip_fail(e, "hipEventRecord");
     }
     if (hipError_t e = hipEventRecord(done, side)) return hip_fail(e, "hipEventRecord");
     if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), done, 0)) return hip_fail(e, "hipStreamWaitEvent");
     p->state = RESHARD_SRC_SWAPPING_IN;
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_swap_wait_buffer(reshard_plan *p, int index, void *stream, int host_wait) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    if (index < 0 || index >= int(p->src.buf_bytes.size()) || !p->src.used[size_t(index)])
+        return fail(RESHARD_ERR_INVALID_ARG, "index does not name a used source buffer");
+    if (!p->swapped_once || p->ev_buf.empty() || !p->ev_buf[size_t(index)])
+        return fail(RESHARD_ERR_BAD_STATE, "no swap has been started on this plan");
+    hipEvent_t ev = static_cast<hipEvent_t>(p->ev_buf[size_t(index)]);
+    if (host_wait) {
+        if (hipError_t e = hipEventSynchronize(ev)) return hip_fail(e, "hipEventSynchronize");
+    } else if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), ev, 0)) {
+        return hip_fail(e, "hipStreamWaitEvent");
+    }
     return RESHARD_OK;
 }
 

@@ -112,6 +112,8 @@ struct reshard_plan {
     void *side_stream = nullptr;
     void *ev_ready = nullptr;  // recorded on the caller's stream
     void *ev_done = nullptr;   // recorded on the side stream
+    std::vector<void *> ev_buf; // per source buffer: recorded after that buffer's copy (lazy)
+    bool swapped_once = false;
 
     // ledger
     int64_t src_live = 0, dst_live = 0, peak_device = 0, released = 0;

@@ -288,6 +288,34 @@ def test_swap_in_overlaps_other_work_on_the_callers_stream():
     assert plan.mem_stats()["state"] == "resident"
 
 
+def test_buffers_of_a_swap_in_can_be_consumed_one_by_one():
+    """Per-buffer waits: a consumer stream that waits for buffer i alone sees buffer i."""
+    wl = TINY["tiny_dense"]  # 8 source buffers
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    src = G.device_sources(plan, wl, "raw16")
+    keep = [s.clone() for s in src]
+    h = G.stream_handle()
+    plan.bind_src(G.ptrs(src))
+    plan.swap_out(h)
+    plan.swap_wait_buffer(0)           # host wait for the first buffer's copy
+    plan.swap_wait()
+    for s in src:
+        s.zero_()
+    torch.cuda.synchronize()
+    plan.swap_in(h)
+    consumer = torch.cuda.Stream()
+    seen = []
+    for i in range(len(src)):
+        plan.swap_wait_buffer(i, consumer.cuda_stream, host_wait=False)
+        with torch.cuda.stream(consumer):
+            seen.append(src[i].clone())
+    consumer.synchronize()
+    for a, k in zip(seen, keep):
+        assert torch.equal(a, k)
+    plan.swap_wait()
+    assert plan.mem_stats()["state"] == "resident"
+
+
 def test_pinned_allocation_failure_leaves_the_ledger_unchanged():
     wl = WORKLOADS["C0"]
     plan = Plan(wl["spec"], wl["src"], wl["dst"])

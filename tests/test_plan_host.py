@@ -393,6 +393,12 @@ def test_state_machine_errors_without_a_device():
         plan.execute([1 << 20, 1 << 30], [(1 << 20) + 256])
     assert e.value.code == binding.ERR_INVALID_ARG  # overlap
     plan.swap_wait()  # no-op
+    with pytest.raises(ReshardError) as e:
+        plan.swap_wait_buffer(0)
+    assert e.value.code == binding.ERR_BAD_STATE
+    with pytest.raises(ReshardError) as e:
+        plan.swap_wait_buffer(7)
+    assert e.value.code == binding.ERR_INVALID_ARG
     plan.release_host()
     assert plan.host_copy(0) == 0
 
