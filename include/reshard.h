@@ -52,8 +52,9 @@
  *     the lowest rank holding it, a tied embedding from the first stage.
  *   Pipeline stages hold contiguous, equal blocks of layers unless the layout asks
  *     for interleaved chunks (vpp) or an uneven first / last stage.
- *   Expert buffer (p, x) holds whole experts x*E/X .. (never tensor-split), per
- *   layer of the stage:
+ *   Expert buffer (p, x) holds whole experts x*E/X .. (unless etp > 1, see reshard_layout:
+ *   then buffer (p, x, y) holds gate/up rows and down columns y*Ie/etp.. of each of them, and
+ *   Ie below reads Ie/etp), per layer of the stage:
  *     TRAIN, RESHARD_PER_EXPERT: for each local expert fc1 = [gate; up] stored
  *       [2*Ie, H], then fc2 = down stored [H, Ie].
  *     TRAIN, RESHARD_GROUPED (grouped-matmul orientation): w1[E/X][H][2*Ie] with
@@ -121,6 +122,10 @@ typedef struct reshard_layout {
                                split (0 = V; else >= V and divisible by tp).  Rank t stores
                                vocab_padded/tp rows; rows at or beyond V are padding: never read, never
                                written */
+    int32_t etp;            /* expert tensor parallelism: 0 or 1 = whole experts; tp = every expert is
+                               split over the tensor ranks like a dense feed-forward.  Expert buffers
+                               are then indexed P*T + (p*X + x)*etp + y, and tp_rank_filter also
+                               selects y */
 } reshard_layout;
 
 /* Weight classes of the paper's redundant-memory example (Problem Statement): tensor-parallel

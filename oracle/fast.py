@@ -33,7 +33,7 @@ class OrcSpec(C.Structure):
 class OrcLayout(C.Structure):
     _fields_ = [(k, C.c_int) for k in (
         "kind", "tp", "pp", "ep", "expert_layout", "tp_filter", "ep_filter", "vpp",
-        "first_stage_layers", "last_stage_layers", "vocab_padded")]
+        "first_stage_layers", "last_stage_layers", "vocab_padded", "etp")]
 
 
 def build(force: bool = False) -> str:
@@ -80,6 +80,7 @@ def c_layout(lay: dict) -> OrcLayout:
     l.first_stage_layers = lay.get("first_stage_layers", 0)
     l.last_stage_layers = lay.get("last_stage_layers", 0)
     l.vocab_padded = lay.get("vocab_padded", 0)
+    l.etp = lay.get("etp", 1)
     return l
 
 

@@ -148,8 +148,14 @@ class Layout:
         self.Vp = lay.get("vocab_padded", 0) or spec["V"]
         if spec["has_embeddings"]:
             assert self.Vp >= spec["V"] and self.Vp % T == 0
+        # expert tensor parallelism: 1 = whole experts, T = every expert split over the tensor
+        # ranks like a dense feed-forward (gate/up by rows, down by columns)
+        self.Y = lay.get("etp", 1) if self.moe else 1
+        assert self.Y in (1, T)
+        if self.moe:
+            assert spec["Ie"] % self.Y == 0
         self.nd = P * T
-        self.ne = P * X if self.moe else 0
+        self.ne = P * X * self.Y if self.moe else 0
         self.nbufs = self.nd + self.ne
         self.tied = bool(spec.get("tied_embeddings", 0)) and bool(spec["has_embeddings"])
         self.stage_layers = self._assign_layers()
@@ -189,7 +195,9 @@ class Layout:
         tf, ef = self.lay["tp_filter"], self.lay["ep_filter"]
         if b < self.nd:
             return tf < 0 or b % self.T == tf
-        return ef < 0 or (b - self.nd) % self.X == ef
+        # expert buffer (stage, expert rank x, expert-tensor rank y): index nd + (p*X + x)*Y + y
+        x, y = (b - self.nd) // self.Y % self.X, (b - self.nd) % self.Y
+        return (ef < 0 or x == ef) and (self.Y == 1 or tf < 0 or y == tf)
 
     # ---- in-buffer order and offsets --------------------------------------
     def _dense_sequence(self, p: int):
@@ -237,7 +245,7 @@ class Layout:
 
     def _expert_sequence(self, p: int):
         s = self.spec
-        H, Ie, El = s["H"], s["Ie"], s["E"] // self.X
+        H, Ie, El = s["H"], s["Ie"] // self.Y, s["E"] // self.X  # Ie: width held by one buffer
         seq = []
         for l in self.stage_layers[p]:
             if self.kind == "gen":
@@ -273,11 +281,11 @@ class Layout:
                 for name, l, j, n in self._expert_sequence(p):
                     off = _align(off)
                     self.expert_off[p][(name, l, j)] = off
-                    for x in range(self.X):
-                        self.stored[self.nd + p * self.X + x].append((name, l, j, off, n * eb))
+                    for xy in range(self.X * self.Y):
+                        self.stored[self.nd + p * self.X * self.Y + xy].append((name, l, j, off, n * eb))
                     off += n * eb
-                for x in range(self.X):
-                    self.buf_bytes[self.nd + p * self.X + x] = _align(off)
+                for xy in range(self.X * self.Y):
+                    self.buf_bytes[self.nd + p * self.X * self.Y + xy] = _align(off)
 
     def owned(self, b: int):
         """(offset, bytes) of the parts of buffer b that hold logical weights: the stored
@@ -393,28 +401,33 @@ class Layout:
             return [dense(name, r // n, (r % n) * cols + c)]
 
         if name in ("ex_gate", "ex_up", "ex_down"):
-            Ie, El = s["Ie"], s["E"] // X
+            Y, El = self.Y, s["E"] // X
+            n = s["Ie"] // Y                      # expert width held by one buffer
             x, j = expert // El, expert % El
-            buf = np.zeros_like(r) + (self.nd + p * X + x)
+            if name == "ex_down":                 # [H, Ie]: columns split over the expert-tensor ranks
+                y, rl, cl = c // n, r, c % n
+            else:                                 # [Ie, H]: rows split
+                y, rl, cl = r // n, r % n, c
+            buf = self.nd + (p * X + x) * Y + y
             eo = self.expert_off[p]
-            up = Ie if name == "ex_up" else 0
+            up = n if name == "ex_up" else 0
             if self.kind == "gen":
                 if name == "ex_down":
-                    off = eo[("w2", layer, -1)] + ((j * H + r) * Ie + c) * eb
+                    off = eo[("w2", layer, -1)] + ((j * H + rl) * n + cl) * eb
                 else:
-                    off = eo[("w13", layer, -1)] + ((j * 2 * Ie + up + r) * H + c) * eb
+                    off = eo[("w13", layer, -1)] + ((j * 2 * n + up + rl) * H + cl) * eb
             elif self.grouped:
                 # grouped-matmul orientation: [expert][in][out]
                 if name == "ex_down":
-                    off = eo[("w2", layer, -1)] + ((j * Ie + c) * H + r) * eb
+                    off = eo[("w2", layer, -1)] + ((j * n + cl) * H + rl) * eb
                 else:
-                    off = eo[("w1", layer, -1)] + ((j * H + c) * 2 * Ie + up + r) * eb
+                    off = eo[("w1", layer, -1)] + ((j * H + cl) * 2 * n + up + rl) * eb
             else:
                 if name == "ex_down":
-                    off = eo[("fc2", layer, j)] + (r * Ie + c) * eb
+                    off = eo[("fc2", layer, j)] + (rl * n + cl) * eb
                 else:
-                    off = eo[("fc1", layer, j)] + ((up + r) * H + c) * eb
-            return [(buf, off)]
+                    off = eo[("fc1", layer, j)] + ((up + rl) * H + cl) * eb
+            return [(buf + np.zeros_like(r), off)]
 
         raise KeyError(name)
 

@@ -47,6 +47,7 @@ typedef struct {
     int first_stage_layers; /* uneven split: layers on the first / last stage (0 = even) */
     int last_stage_layers;
     int vocab_padded;       /* rows the embedding / lm_head are padded to before the split (0 = V) */
+    int etp;                /* expert tensor parallelism: 1 (whole experts) or tp */
 } orc_layout;
 
 enum { FAM_DENSE = 0, FAM_MOE = 1, FAM_MLA = 2 };
@@ -68,7 +69,7 @@ enum {
 typedef struct {
     orc_spec s;
     orc_layout l;
-    int T, P, X, El, nd, ne, moe, grouped, tied;
+    int T, P, X, Y, El, nd, ne, moe, grouped, tied; /* Y: expert-tensor ranks per expert rank */
     int64_t Vp;      /* vocabulary rows including padding */
     int *stage_of;   /* [L] stage holding a layer */
     int *order;      /* [L] layers sorted by (stage, storage position) */
@@ -105,6 +106,8 @@ static int valid(const orc_spec *s, const orc_layout *l)
         if (s->I <= 0 || s->I % l->tp || l->ep != 1) return 0;
     } else {
         if (s->E <= 0 || s->Ie <= 0 || s->E % l->ep) return 0;
+        if (l->etp != 1 && l->etp != l->tp) return 0;
+        if (s->Ie % l->etp) return 0;
         if ((s->n_shared * s->Ie) % l->tp) return 0;
     }
     if (s->has_embeddings) {
@@ -158,8 +161,9 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
         c->first[c->P] = n;
     }
     c->El = c->moe ? s->E / c->X : 0;
+    c->Y = c->moe ? l->etp : 1;
     c->nd = c->P * c->T;
-    c->ne = c->moe ? c->P * c->X : 0;
+    c->ne = c->moe ? c->P * c->X * c->Y : 0; /* expert buffer (p, x, y): nd + (p*X + x)*Y + y */
     c->grouped = l->kind == K_TRAIN && l->expert_layout == 1;
     c->eb = s->elem_bytes;
     c->doff = calloc((size_t)s->L * NSLOT, sizeof(int64_t));
@@ -212,7 +216,7 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
         c->dense_bytes[p] = up256(off);
         if (c->moe) {
             off = 0;
-            int64_t Ie = s->Ie, El = c->El;
+            int64_t Ie = s->Ie / c->Y, El = c->El; /* Ie: the expert width one buffer holds */
             for (int at = c->first[p]; at < c->first[p + 1]; at++) {
                 int ly = c->order[at];
                 int64_t *o = c->eoff + (size_t)ly * El * 2;
@@ -236,7 +240,8 @@ static int ctx_init(ctx_t *c, const orc_spec *s, const orc_layout *l)
 static int buf_used(const ctx_t *c, int b)
 {
     if (b < c->nd) return c->l.tp_filter < 0 || b % c->T == c->l.tp_filter;
-    return c->l.ep_filter < 0 || (b - c->nd) % c->X == c->l.ep_filter;
+    int x = (b - c->nd) / c->Y % c->X, y = (b - c->nd) % c->Y;
+    return (c->l.ep_filter < 0 || x == c->l.ep_filter) && (c->Y == 1 || c->l.tp_filter < 0 || y == c->l.tp_filter);
 }
 
 /*
@@ -323,20 +328,22 @@ static void src_find(const ctx_t *c, int tid, int ly, int ex, int64_t r, int64_t
         break;
     }
     case T_EX_GATE: case T_EX_UP: case T_EX_DOWN: {
-        int64_t Ie = s->Ie, El = c->El, x = ex / El, j = ex % El;
+        /* n: the expert width one buffer holds; gate/up rows and down columns are split over Y ranks */
+        int64_t n = s->Ie / c->Y, El = c->El, x = ex / El, j = ex % El, y, rl = r, cl = col;
         const int64_t *eo = c->eoff + (size_t)ly * El * 2;
-        int64_t upo = tid == T_EX_UP ? Ie : 0;
-        *buf = c->nd + p * c->X + (int)x;
+        if (tid == T_EX_DOWN) { y = col / n; cl = col % n; } else { y = r / n; rl = r % n; }
+        int64_t upo = tid == T_EX_UP ? n : 0;
+        *buf = c->nd + (p * c->X + (int)x) * c->Y + (int)y;
         if (c->l.kind == K_GEN) {
-            if (tid == T_EX_DOWN) { *off = eo[1] + ((j * H + r) * Ie + col) * eb; *run = Ie - col; }
-            else { *off = eo[0] + ((j * 2 * Ie + upo + r) * H + col) * eb; *run = H - col; }
+            if (tid == T_EX_DOWN) { *off = eo[1] + ((j * H + rl) * n + cl) * eb; *run = n - cl; }
+            else { *off = eo[0] + ((j * 2 * n + upo + rl) * H + cl) * eb; *run = H - cl; }
         } else if (c->grouped) {
-            if (tid == T_EX_DOWN) *off = eo[1] + ((j * Ie + col) * H + r) * eb;
-            else *off = eo[0] + ((j * H + col) * 2 * Ie + upo + r) * eb;
+            if (tid == T_EX_DOWN) *off = eo[1] + ((j * n + cl) * H + rl) * eb;
+            else *off = eo[0] + ((j * H + cl) * 2 * n + upo + rl) * eb;
             *run = 1;
         } else {
-            if (tid == T_EX_DOWN) { *off = eo[2 * j + 1] + (r * Ie + col) * eb; *run = Ie - col; }
-            else { *off = eo[2 * j] + ((upo + r) * H + col) * eb; *run = H - col; }
+            if (tid == T_EX_DOWN) { *off = eo[2 * j + 1] + (rl * n + cl) * eb; *run = n - cl; }
+            else { *off = eo[2 * j] + ((upo + rl) * H + cl) * eb; *run = H - cl; }
         }
         return;
     }
@@ -477,27 +484,28 @@ static void dst_pieces(const ctx_t *D, pieces_t *ps)
     }
     for (int b = D->nd; b < D->nd + D->ne; b++) {
         if (!buf_used(D, b)) continue;
-        int p = (b - D->nd) / D->X;
-        int64_t x = (b - D->nd) % D->X, Ie = s->Ie, El = D->El;
+        int p = (b - D->nd) / (D->X * D->Y);
+        int64_t x = (b - D->nd) / D->Y % D->X, y = (b - D->nd) % D->Y;
+        int64_t n = s->Ie / D->Y, El = D->El; /* this buffer holds rows / columns y*n .. of every local expert */
         for (int at = D->first[p]; at < D->first[p + 1]; at++) {
             int ly = D->order[at];
             const int64_t *eo = D->eoff + (size_t)ly * El * 2;
             for (int64_t j = 0; j < El; j++) {
                 int ex = (int)(x * El + j);
                 if (D->l.kind == K_GEN) {
-                    int64_t b13 = eo[0] + j * 2 * Ie * H * eb;
-                    add_piece(ps, T_EX_GATE, ly, ex, 0, Ie, 0, H, b, b13, H, 0);
-                    add_piece(ps, T_EX_UP, ly, ex, 0, Ie, 0, H, b, b13 + Ie * H * eb, H, 0);
-                    add_piece(ps, T_EX_DOWN, ly, ex, 0, H, 0, Ie, b, eo[1] + j * H * Ie * eb, Ie, 0);
+                    int64_t b13 = eo[0] + j * 2 * n * H * eb;
+                    add_piece(ps, T_EX_GATE, ly, ex, y * n, n, 0, H, b, b13, H, 0);
+                    add_piece(ps, T_EX_UP, ly, ex, y * n, n, 0, H, b, b13 + n * H * eb, H, 0);
+                    add_piece(ps, T_EX_DOWN, ly, ex, 0, H, y * n, n, b, eo[1] + j * H * n * eb, n, 0);
                 } else if (D->grouped) {
-                    int64_t b1 = eo[0] + j * H * 2 * Ie * eb;
-                    add_piece(ps, T_EX_GATE, ly, ex, 0, Ie, 0, H, b, b1, 2 * Ie, 1);
-                    add_piece(ps, T_EX_UP, ly, ex, 0, Ie, 0, H, b, b1 + Ie * eb, 2 * Ie, 1);
-                    add_piece(ps, T_EX_DOWN, ly, ex, 0, H, 0, Ie, b, eo[1] + j * Ie * H * eb, H, 1);
+                    int64_t b1 = eo[0] + j * H * 2 * n * eb;
+                    add_piece(ps, T_EX_GATE, ly, ex, y * n, n, 0, H, b, b1, 2 * n, 1);
+                    add_piece(ps, T_EX_UP, ly, ex, y * n, n, 0, H, b, b1 + n * eb, 2 * n, 1);
+                    add_piece(ps, T_EX_DOWN, ly, ex, 0, H, y * n, n, b, eo[1] + j * n * H * eb, H, 1);
                 } else {
-                    add_piece(ps, T_EX_GATE, ly, ex, 0, Ie, 0, H, b, eo[2 * j], H, 0);
-                    add_piece(ps, T_EX_UP, ly, ex, 0, Ie, 0, H, b, eo[2 * j] + Ie * H * eb, H, 0);
-                    add_piece(ps, T_EX_DOWN, ly, ex, 0, H, 0, Ie, b, eo[2 * j + 1], Ie, 0);
+                    add_piece(ps, T_EX_GATE, ly, ex, y * n, n, 0, H, b, eo[2 * j], H, 0);
+                    add_piece(ps, T_EX_UP, ly, ex, y * n, n, 0, H, b, eo[2 * j] + n * H * eb, H, 0);
+                    add_piece(ps, T_EX_DOWN, ly, ex, 0, H, y * n, n, b, eo[2 * j + 1], n, 0);
                 }
             }
         }
@@ -521,7 +529,7 @@ int64_t orc_buf_bytes(const orc_spec *s, const orc_layout *l, int i)
     if (ctx_init(&c, s, l)) return -1;
     int64_t n = -1;
     if (i >= 0 && i < c.nd) n = c.dense_bytes[i / c.T];
-    else if (i >= c.nd && i < c.nd + c.ne) n = c.expert_bytes[(i - c.nd) / c.X];
+    else if (i >= c.nd && i < c.nd + c.ne) n = c.expert_bytes[(i - c.nd) / (c.X * c.Y)];
     ctx_free(&c);
     return n;
 }

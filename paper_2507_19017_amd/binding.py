@@ -31,7 +31,7 @@ class ModelSpec(C.Structure):
 class Layout(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(k, C.c_int32) for k in (
         "kind", "tp", "pp", "ep", "expert_layout", "tp_rank_filter", "ep_rank_filter", "vpp",
-        "first_stage_layers", "last_stage_layers", "vocab_padded")]
+        "first_stage_layers", "last_stage_layers", "vocab_padded", "etp")]
 
 
 class TensorInfo(C.Structure):
@@ -196,6 +196,7 @@ def make_layout(lay: dict) -> Layout:
     l.first_stage_layers = int(lay.get("first_stage_layers", 0))
     l.last_stage_layers = int(lay.get("last_stage_layers", 0))
     l.vocab_padded = int(lay.get("vocab_padded", 0))
+    l.etp = int(lay.get("etp", 1))
     return l
 
 

@@ -146,6 +146,9 @@ int check_shape(const reshard_model_spec &s, const reshard_layout &l) {
         if (s.E % l.ep) return bad("experts not divisible by ep");
         if (s.n_shared < 0) return fail(RESHARD_ERR_INVALID_ARG, "n_shared must be >= 0");
         if ((int64_t(s.n_shared) * s.Ie) % l.tp) return bad("shared-expert width not divisible by tp");
+        if (l.etp < 0) return fail(RESHARD_ERR_INVALID_ARG, "etp must be >= 0");
+        if (l.etp > 1 && l.etp != l.tp) return bad("expert tensor parallelism must be 1 or equal to tp");
+        if (l.etp > 1 && s.Ie % l.etp) return bad("expert width not divisible by etp");
     }
     if (s.has_embeddings) {
         if (s.V <= 0) return fail(RESHARD_ERR_INVALID_ARG, "V must be positive");
@@ -194,7 +197,8 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
     out = Side{};
     out.layout = l;
     out.nd = P * T;
-    out.ne = moe ? P * X : 0;
+    const int Y = moe && l.etp > 0 ? l.etp : 1;  // expert-tensor ranks per expert rank
+    out.ne = moe ? P * X * Y : 0;
     if (out.nd + out.ne > RESHARD_MAX_BUFFERS) return fail(RESHARD_ERR_UNSUPPORTED, "too many buffers in one layout");
     out.buf_bytes.assign(out.nd + out.ne, 0);
     out.used.assign(out.nd + out.ne, 0);
@@ -283,44 +287,49 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
             out.buf_bytes[b] = bb.finish();
         }
         if (!moe) continue;
-        const int64_t Ie = s.Ie, El = s.E / X;
-        for (int x = 0; x < X; ++x) {
-            const int b = out.nd + p * X + x;
-            const bool kept = is_source || l.ep_rank_filter < 0 || l.ep_rank_filter == x;
-            BufferBuilder bb(out, b, eb, kept, is_source, true, true);
-            if (!is_source) out.used[b] = kept;
-            for (const int L_ : stage_layers[p]) {
-                if (gen || grouped) {
-                    const int64_t a1 = bb.begin(gen ? "w13" : "w1", L_, -1, El * 2 * Ie * H, false);
-                    const int64_t a2 = bb.begin("w2", L_, -1, El * Ie * H, false);
-                    for (int64_t j = 0; j < El; ++j) {
-                        const int e = int(x * El + j);
-                        if (gen) {
-                            const int64_t base = a1 + j * 2 * Ie * H * eb;
-                            bb.frag(LT_EX_GATE, L_, e, 0, Ie, 0, H, base, H);
-                            bb.frag(LT_EX_UP, L_, e, 0, Ie, 0, H, base + Ie * H * eb, H);
-                            bb.frag(LT_EX_DOWN, L_, e, 0, H, 0, Ie, a2 + j * H * Ie * eb, Ie);
-                        } else {
-                            // [expert][in][out]: logical (out r, in c) sits at column-major position
-                            const int64_t base = a1 + j * H * 2 * Ie * eb;
-                            bb.frag(LT_EX_GATE, L_, e, 0, Ie, 0, H, base, 2 * Ie, true);
-                            bb.frag(LT_EX_UP, L_, e, 0, Ie, 0, H, base + Ie * eb, 2 * Ie, true);
-                            bb.frag(LT_EX_DOWN, L_, e, 0, H, 0, Ie, a2 + j * Ie * H * eb, H, true);
+        // Expert buffer (p, x, y): whole experts x*E/X .. when Y == 1; with expert tensor parallelism
+        // (Y == T) expert-tensor rank y holds rows y*n.. of gate and up and columns y*n.. of down.
+        const int64_t n = s.Ie / Y, El = s.E / X;
+        for (int x = 0; x < X; ++x)
+            for (int y = 0; y < Y; ++y) {
+                const int b = out.nd + (p * X + x) * Y + y;
+                const bool kept = is_source || ((l.ep_rank_filter < 0 || l.ep_rank_filter == x) &&
+                                                (Y == 1 || l.tp_rank_filter < 0 || l.tp_rank_filter == y));
+                BufferBuilder bb(out, b, eb, kept, is_source, true, true);
+                if (!is_source) out.used[b] = kept;
+                const int64_t r0 = y * n, r1 = (y + 1) * n;  // this buffer's slice of the expert width
+                for (const int L_ : stage_layers[p]) {
+                    if (gen || grouped) {
+                        const int64_t a1 = bb.begin(gen ? "w13" : "w1", L_, -1, El * 2 * n * H, false);
+                        const int64_t a2 = bb.begin("w2", L_, -1, El * n * H, false);
+                        for (int64_t j = 0; j < El; ++j) {
+                            const int e = int(x * El + j);
+                            if (gen) {
+                                const int64_t base = a1 + j * 2 * n * H * eb;
+                                bb.frag(LT_EX_GATE, L_, e, r0, r1, 0, H, base, H);
+                                bb.frag(LT_EX_UP, L_, e, r0, r1, 0, H, base + n * H * eb, H);
+                                bb.frag(LT_EX_DOWN, L_, e, 0, H, r0, r1, a2 + j * H * n * eb, n);
+                            } else {
+                                // [expert][in][out]: logical (out r, in c) sits at column-major position
+                                const int64_t base = a1 + j * H * 2 * n * eb;
+                                bb.frag(LT_EX_GATE, L_, e, r0, r1, 0, H, base, 2 * n, true);
+                                bb.frag(LT_EX_UP, L_, e, r0, r1, 0, H, base + n * eb, 2 * n, true);
+                                bb.frag(LT_EX_DOWN, L_, e, 0, H, r0, r1, a2 + j * n * H * eb, H, true);
+                            }
+                        }
+                    } else {
+                        for (int64_t j = 0; j < El; ++j) {
+                            const int e = int(x * El + j);
+                            const int64_t a1 = bb.begin("fc1", L_, e, 2 * n * H, false);
+                            bb.frag(LT_EX_GATE, L_, e, r0, r1, 0, H, a1, H);
+                            bb.frag(LT_EX_UP, L_, e, r0, r1, 0, H, a1 + n * H * eb, H);
+                            const int64_t a2 = bb.begin("fc2", L_, e, H * n, false);
+                            bb.frag(LT_EX_DOWN, L_, e, 0, H, r0, r1, a2, n);
                         }
                     }
-                } else {
-                    for (int64_t j = 0; j < El; ++j) {
-                        const int e = int(x * El + j);
-                        const int64_t a1 = bb.begin("fc1", L_, e, 2 * Ie * H, false);
-                        bb.frag(LT_EX_GATE, L_, e, 0, Ie, 0, H, a1, H);
-                        bb.frag(LT_EX_UP, L_, e, 0, Ie, 0, H, a1 + Ie * H * eb, H);
-                        const int64_t a2 = bb.begin("fc2", L_, e, H * Ie, false);
-                        bb.frag(LT_EX_DOWN, L_, e, 0, H, 0, Ie, a2, Ie);
-                    }
                 }
+                out.buf_bytes[b] = bb.finish();
             }
-            out.buf_bytes[b] = bb.finish();
-        }
     }
     std::stable_sort(out.tensors.begin(), out.tensors.end(),
                      [](const reshard_tensor_info &a, const reshard_tensor_info &b) { return a.buffer < b.buffer; });

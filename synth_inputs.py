@@ -26,10 +26,11 @@ _SPEC_DEFAULTS = dict(
 # "grouped"; the two filters select one rank of the layout (-1 = every rank).
 # `vpp`: virtual pipeline size (interleaved layer chunks); `first_stage_layers` /
 # `last_stage_layers`: uneven pipeline split (0 = even); `vocab_padded`: rows the
-# embedding / lm_head are padded to before the tensor-parallel split (0 = V).
+# embedding / lm_head are padded to before the tensor-parallel split (0 = V); `etp`:
+# expert tensor parallelism, 1 (whole experts) or tp (every expert split like a dense FFN).
 _LAYOUT_DEFAULTS = dict(kind="train", tp=1, pp=1, ep=1,
                         expert_layout="per_expert", tp_filter=-1, ep_filter=-1,
-                        vpp=1, first_stage_layers=0, last_stage_layers=0, vocab_padded=0)
+                        vpp=1, first_stage_layers=0, last_stage_layers=0, vocab_padded=0, etp=1)
 
 
 def make_spec(**kw) -> dict:
@@ -166,6 +167,14 @@ TINY = {
         make_layout(kind="train", tp=4, pp=2, vocab_padded=64),
         make_layout(kind="gen", tp=2, vocab_padded=54),
         2007, "tiny dense, vocabulary 50 padded to 64 (TP4 PP2) -> padded to 54 (TP2)"),
+    # Experts split over the tensor ranks as well (expert tensor parallelism) on both sides,
+    # grouped orientation on the training side.
+    "tiny_etp": _wl(
+        "tiny_etp",
+        make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=4, d=8, V=48, E=4, Ie=24, n_shared=1),
+        make_layout(kind="train", tp=4, pp=1, ep=2, etp=4, expert_layout="grouped"),
+        make_layout(kind="gen", tp=2, ep=1, etp=2),
+        2008, "tiny MoE, expert tensor parallelism TP4 EP2 ETP4 (grouped) -> TP2 EP1 ETP2"),
     "tiny_mla": _wl(
         "tiny_mla",
         make_spec(family="moe_mla", L=2, H=40, nq=4, V=0, has_embeddings=0, E=8,

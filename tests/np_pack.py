@@ -44,7 +44,7 @@ def _layout_chunks(spec, lay, lg, fill=0):
         chunks = np.arange(L).reshape(vpp, P, L // (P * vpp))
         stage_layers = [chunks[:, p, :].reshape(-1) for p in range(P)]
     nd = P * T
-    bufs = [[] for _ in range(nd + (P * X if moe else 0))]
+    bufs = [[] for _ in range(nd + (P * X * lay.get("etp", 1) if moe else 0))]
     Vp = lay.get("vocab_padded", 0) or spec["V"]
 
     def vocab_padded(a):  # padding rows appended before the split; they hold the gap value
@@ -114,11 +114,15 @@ def _layout_chunks(spec, lay, lg, fill=0):
                     for t in range(T):
                         dense[t] += [np.concatenate([ga[t], up[t]], axis=0), dn[t]]
                 El = spec["E"] // X
+                Y = lay.get("etp", 1)
                 for x in range(X):
-                    eb = bufs[nd + p * X + x]
+                  for y in range(Y):
+                    eb = bufs[nd + (p * X + x) * Y + y]
                     ex = range(x * El, (x + 1) * El)
-                    fc1 = [np.concatenate([lg[("ex_gate", l, e)], lg[("ex_up", l, e)]], axis=0) for e in ex]
-                    fc2 = [lg[("ex_down", l, e)] for e in ex]
+                    # expert-tensor rank y: its rows of gate and up, its columns of down
+                    fc1 = [np.concatenate([np.split(lg[("ex_gate", l, e)], Y, axis=0)[y],
+                                           np.split(lg[("ex_up", l, e)], Y, axis=0)[y]], axis=0) for e in ex]
+                    fc2 = [np.split(lg[("ex_down", l, e)], Y, axis=1)[y] for e in ex]
                     if gen:
                         eb += [np.stack(fc1), np.stack(fc2)]
                     elif grouped:

@@ -21,11 +21,11 @@ static reshard_model_spec spec(int family, int L, int H, int nq, int nkv, int d,
     return s;
 }
 static reshard_layout lay(int kind, int tp, int pp, int ep, int grouped = 0, int tf = -1, int ef = -1, int vpp = 1,
-                          int first = 0, int last = 0, int vpad = 0) {
+                          int first = 0, int last = 0, int vpad = 0, int etp = 1) {
     reshard_layout l{};
     l.struct_size = sizeof l;
     l.kind = kind; l.tp = tp; l.pp = pp; l.ep = ep; l.expert_layout = grouped;
-    l.tp_rank_filter = tf; l.ep_rank_filter = ef; l.vpp = vpp; l.first_stage_layers = first; l.last_stage_layers = last; l.vocab_padded = vpad;
+    l.tp_rank_filter = tf; l.ep_rank_filter = ef; l.vpp = vpp; l.first_stage_layers = first; l.last_stage_layers = last; l.vocab_padded = vpad; l.etp = etp;
     return l;
 }
 
@@ -86,6 +86,8 @@ int main() {
             bad += run(spec(0, 8, 48, 8, 2, 8, 40, 64, 1, 1, 0, 0, 0, eb, 1), lay(TR, 4, 2, 1, 0, -1, -1, 2), lay(GEN, 8, 1, 1), tn, true);
             bad += run(spec(0, 8, 32, 8, 2, 8, 24, 48, 0, 1, 0, 0, 0, eb), lay(TR, 4, 4, 1, 0, -1, -1, 1, 3, 1), lay(GEN, 2, 1, 1, 0, 1), tn, true);
             bad += run(spec(0, 2, 7, 3, 3, 5, 9, 6, 1, 1, 0, 0, 0, 1), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, true);
+            bad += run(spec(1, 2, 32, 4, 4, 8, 0, 48, 0, 1, 4, 24, 1, eb), lay(TR, 4, 1, 2, 1, -1, -1, 1, 0, 0, 0, 4),
+                       lay(GEN, 2, 1, 1, 0, 1, -1, 1, 0, 0, 0, 2), tn, true);
             bad += run(spec(0, 2, 24, 4, 4, 8, 24, 50, 0, 1, 0, 0, 0, eb), lay(TR, 4, 2, 1, 0, -1, -1, 1, 0, 0, 64),
                        lay(GEN, 2, 1, 1, 0, -1, -1, 1, 0, 0, 54), tn, true);
         }
@@ -96,6 +98,7 @@ int main() {
         bad += run(spec(1, 4, 64, 4, 4, 8, 0, 64, 0, 1, 512, 8, 0, 2), lay(TR, 1, 1, 512), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, 0), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, -1, -1, 1, 0, 0, 1000), lay(GEN, 1, 1, 1), tn, false);
+        bad += run(spec(1, 2, 32, 4, 4, 8, 0, 48, 0, 1, 4, 24, 1, 2), lay(TR, 4, 1, 2, 1, -1, -1, 1, 0, 0, 0, 2), lay(GEN, 2, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, -1, -1, 1, 0, 0, 1025), lay(GEN, 1, 1, 1), tn, false);
     }
     std::printf(bad ? "FAILED %d\n" : "ok\n", bad);

@@ -71,7 +71,7 @@ TILE_TUNINGS = [dict(), dict(tile_bytes=4096, transpose_rows=64, transpose_cols=
 
 
 @pytest.mark.parametrize("tuning", TILE_TUNINGS)
-@pytest.mark.parametrize("name", ["tiny_dense", "tiny_moe_grouped", "mid_moe_grouped", "tiny_kvrep", "tiny_vocabpad", "C0"])
+@pytest.mark.parametrize("name", ["tiny_dense", "tiny_moe_grouped", "mid_moe_grouped", "tiny_kvrep", "tiny_vocabpad", "tiny_etp", "C0"])
 def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, tuning):
     """The cut into device tiles (rows per tile, runs of long rows, vector width, the three
     levels of transposing tiles) moves exactly what the descriptors say."""
@@ -350,6 +350,7 @@ def test_invalid_requests_return_error_codes():
         (spec, make_layout(kind="train", tp=2), make_layout(kind="gen", tp=1, tp_filter=1), binding.ERR_INVALID_ARG),
         (dict(spec, elem_bytes=3), make_layout(kind="train", tp=2), gen, binding.ERR_INVALID_ARG),
         (dict(spec, V=1023), make_layout(kind="train", tp=2), gen, binding.ERR_UNSUPPORTED),
+        (TINY["tiny_etp"]["spec"], make_layout(kind="train", tp=4, ep=2, etp=2), make_layout(kind="gen", ep=1), binding.ERR_UNSUPPORTED),
         (spec, make_layout(kind="train", tp=2, vocab_padded=1000), gen, binding.ERR_INVALID_ARG),   # below V
         (spec, make_layout(kind="train", tp=2, vocab_padded=1025), gen, binding.ERR_UNSUPPORTED),   # not divisible
         (dict(spec, L=0), make_layout(kind="train", tp=2), gen, binding.ERR_INVALID_ARG),
