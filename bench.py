@@ -37,6 +37,9 @@ def parse():
                          "copies with shader kernels instead of the DMA engines, which starves the repack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-step timings on stderr")
+    ap.add_argument("--streaming", action="store_true",
+                    help="after the timed steps, also run the streaming flow once (one source buffer resident at a "
+                         "time) and report its peak HBM")
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--tuning", default="", help="e.g. tile_bytes=65536,unroll=8")
     return ap.parse_args()
@@ -203,6 +206,40 @@ def main():
         torch.cuda.synchronize()
         assert check == [None if s is None else int(s[::4099].to(torch.int64).sum()) for s in src], "swap round trip changed the weights"
 
+    streaming = None
+    if a.streaming:
+        # the gathered shards "arrive" one buffer at a time: repack what reads it, swap it out, drop it
+        plan.release_host()
+        src = None
+        torch.cuda.empty_cache()
+        splan = Plan(wl["spec"], wl["src"], wl["dst"])
+        splan.prepare()
+        base = torch.cuda.memory_allocated()
+        torch.cuda.reset_peak_memory_stats()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i, (n, u) in enumerate(zip(sizes_s, used_s)):
+            if not u:
+                continue
+            buf = torch.empty(n // 2, dtype=torch.int16, device="cuda")
+            splan.execute_source(i, buf.data_ptr(), ptrs(dst), h)
+            splan.swap_out_source(i, h)
+            splan.swap_wait_buffer(i)
+            splan.mark_src_buffer_released(i)
+            del buf
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        sst = splan.mem_stats()
+        streaming = {"total_ms": round((t1 - t0) * 1e3, 2), "ledger_peak_device": sst["peak_device"],
+                     "torch_peak_allocated": torch.cuda.max_memory_allocated(), "dst_bytes": sst["dst_live"],
+                     "largest_src_buffer": max(n for n, u in zip(sizes_s, used_s) if u), "state": sst["state"],
+                     "one_shot_peak_device": plan.mem_stats()["peak_device"], "allocated_before": base}
+        src = alloc_src(False)  # a device home again, and the weights back, so the rest of the run goes on
+        splan.bind_src(ptrs(src))
+        splan.swap_in(h)
+        splan.swap_wait()
+        splan.release_host()
+
     moved = info["bytes_moved"]
     k_avg = sum(kernel_ms) / len(kernel_ms) / 1e3
     repack_gbps = 2 * moved / k_avg / 1e9
@@ -262,6 +299,8 @@ def main():
         if link:
             out["swap"]["out_frac_of_link"] = round(src_bytes / so / 1e9 / link["d2h"], 3)
             out["swap"]["in_frac_of_link"] = round(src_bytes / si / 1e9 / link["h2d"], 3)
+    if streaming:
+        out["streaming"] = streaming
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, plan, src)
     print(json.dumps(out))

@@ -193,7 +193,8 @@ enum {
     RESHARD_SRC_SWAPPING_OUT = 2, /* device-to-host copies in flight */
     RESHARD_SRC_ON_HOST = 3,      /* host copy complete; device copy may be released */
     RESHARD_SRC_RELEASED = 4,     /* caller freed the device copy; rebind before swap-in */
-    RESHARD_SRC_SWAPPING_IN = 5   /* host-to-device copies in flight */
+    RESHARD_SRC_SWAPPING_IN = 5,  /* host-to-device copies in flight */
+    RESHARD_SRC_MIXED = 6         /* plan level only: the source buffers are in different states (streaming) */
 };
 
 /* Byte ledger of a plan (pure host bookkeeping of what the caller told the plan). */
@@ -202,7 +203,7 @@ typedef struct reshard_mem_stats_t {
     int64_t dst_live;     /* bytes of bound, not released destination buffers */
     int64_t host_pinned;  /* pinned host bytes the plan currently owns */
     int64_t peak_device;  /* max over time of src_live + dst_live (the plan's own table is in plan_info) */
-    int64_t released;     /* bytes returned by the last reshard_mark_src_released */
+    int64_t released;     /* bytes of source buffers currently marked released */
     int32_t state;        /* RESHARD_SRC_* */
 } reshard_mem_stats_t;
 
@@ -306,6 +307,30 @@ int reshard_execute(reshard_plan *plan, const void *const *src_ptrs, void *const
  */
 int reshard_plan_prepare(reshard_plan *plan);
 
+/*
+ * Streaming form of the repack, for callers that never hold all source buffers at once (the
+ * gathered shards arrive, are repacked and are swapped out or dropped one buffer at a time, so
+ * the peak is the destination plus the buffers in flight instead of source plus destination):
+ * runs the part of the plan that READS source buffer `src_index` (device pointer `src_ptr`,
+ * 256-byte aligned) and writes into dst_ptrs (all used destination buffers must be given every
+ * time).  After it has been called once for every used source buffer the destination is
+ * complete and bit-identical to one reshard_execute.  The first call uploads a second copy of
+ * the tile table, regrouped by source buffer.  The buffer becomes RESIDENT; the plan-level
+ * state is RESHARD_SRC_MIXED while buffers differ.
+ * Errors: INVALID_ARG, BAD_STATE (this buffer is swapped out / in flight), OOM, HIP.
+ */
+int reshard_execute_source(reshard_plan *plan, int src_index, const void *src_ptr, void *const *dst_ptrs,
+                           void *stream);
+
+/* Per-buffer forms of swap-out and release for the streaming flow.  reshard_swap_out_source needs
+ * the buffer RESIDENT (-> SWAPPING_OUT; complete it with reshard_swap_wait_buffer(host_wait = 1) or
+ * reshard_swap_wait); reshard_mark_src_buffer_released needs it ON_HOST (-> RELEASED).  When every
+ * used buffer is RELEASED the plan is RELEASED and continues with reshard_bind_src / reshard_swap_in. */
+int reshard_swap_out_source(reshard_plan *plan, int src_index, void *stream);
+int reshard_mark_src_buffer_released(reshard_plan *plan, int src_index);
+/* RESHARD_SRC_* of one source buffer (negative = error). */
+int reshard_src_buffer_state(const reshard_plan *plan, int src_index);
+
 /* Bind (or re-bind, after the caller re-allocated) the source pointers without
  * running the repack.  Allowed in UNBOUND, RESIDENT, ON_HOST and RELEASED; from
  * RELEASED the state becomes ON_HOST again (a device home for swap-in exists). */
@@ -338,7 +363,8 @@ int reshard_swap_in(reshard_plan *plan, void *stream);
  * buffer order).  With host_wait != 0 the host blocks until that buffer's copy of the swap in
  * flight (or the last finished one) is done; otherwise `stream` is made to wait for it, so a
  * consumer can start on the first pipeline stage's weights while later buffers still stream
- * in.  The plan's state is not changed (reshard_swap_wait still completes the swap).
+ * in.  A host wait also completes that buffer's state change (SWAPPING_OUT -> ON_HOST,
+ * SWAPPING_IN -> RESIDENT); reshard_swap_wait completes the rest.
  * Errors: INVALID_ARG (index, unused buffer), BAD_STATE (no swap was ever started), HIP.
  */
 int reshard_swap_wait_buffer(reshard_plan *plan, int index, void *stream, int host_wait);

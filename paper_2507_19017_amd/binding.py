@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libreshard.so")
 FAMILY = {"dense_gqa": 0, "moe_gqa": 1, "moe_mla": 2}
 KIND = {"train": 0, "gen": 1}
 EXPERT_LAYOUT = {"per_expert": 0, "grouped": 1}
-STATE = {0: "unbound", 1: "resident", 2: "swapping_out", 3: "on_host", 4: "released", 5: "swapping_in"}
+STATE = {0: "unbound", 1: "resident", 2: "swapping_out", 3: "on_host", 4: "released", 5: "swapping_in", 6: "mixed"}
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_OOM, ERR_HOST_OOM, ERR_BAD_STATE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 _ERR_NAMES = {-1: "INVALID_ARG", -2: "UNSUPPORTED", -3: "OOM", -4: "HOST_OOM", -5: "BAD_STATE", -6: "HIP"}
@@ -105,6 +105,10 @@ def lib():
             "reshard_plan_tile": (C.c_int, [P, C.c_int64, C.POINTER(TileView)]),
             "reshard_plan_prepare": (C.c_int, [P]),
             "reshard_execute": (C.c_int, [P, C.POINTER(P), C.POINTER(P), P]),
+            "reshard_execute_source": (C.c_int, [P, C.c_int, P, C.POINTER(P), P]),
+            "reshard_swap_out_source": (C.c_int, [P, C.c_int, P]),
+            "reshard_mark_src_buffer_released": (C.c_int, [P, C.c_int]),
+            "reshard_src_buffer_state": (C.c_int, [P, C.c_int]),
             "reshard_bind_src": (C.c_int, [P, C.POINTER(P)]),
             "reshard_swap_out": (C.c_int, [P, P]),
             "reshard_swap_in": (C.c_int, [P, P]),
@@ -130,7 +134,8 @@ EXPORTS = (
     "reshard_plan_create", "reshard_plan_destroy", "reshard_plan_num_bufs", "reshard_plan_buf_bytes",
     "reshard_plan_buf_used", "reshard_plan_num_tensors", "reshard_plan_tensor", "reshard_plan_get_info",
     "reshard_plan_class_bytes", "reshard_redundant_memory_bytes",
-    "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
+    "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_execute_source",
+    "reshard_swap_out_source", "reshard_mark_src_buffer_released", "reshard_src_buffer_state", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
     "reshard_swap_wait", "reshard_swap_wait_buffer", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
 )
@@ -278,6 +283,18 @@ class Plan:
 
     def execute(self, src_ptrs, dst_ptrs, stream: int = 0) -> None:
         _check(lib().reshard_execute(self._h, _ptr_array(src_ptrs), _ptr_array(dst_ptrs), C.c_void_p(stream)))
+
+    def execute_source(self, src_index: int, src_ptr: int, dst_ptrs, stream: int = 0) -> None:
+        _check(lib().reshard_execute_source(self._h, src_index, C.c_void_p(src_ptr), _ptr_array(dst_ptrs), C.c_void_p(stream)))
+
+    def swap_out_source(self, src_index: int, stream: int = 0) -> None:
+        _check(lib().reshard_swap_out_source(self._h, src_index, C.c_void_p(stream)))
+
+    def mark_src_buffer_released(self, src_index: int) -> None:
+        _check(lib().reshard_mark_src_buffer_released(self._h, src_index))
+
+    def src_buffer_state(self, src_index: int) -> str:
+        return STATE[_check(lib().reshard_src_buffer_state(self._h, src_index))]
 
     def bind_src(self, src_ptrs) -> None:
         _check(lib().reshard_bind_src(self._h, _ptr_array(src_ptrs)))

@@ -13,7 +13,9 @@
 namespace reshard {
 const char *last_error_cstr();
 int ensure_device_table(reshard_plan *plan);
+int ensure_by_source_table(reshard_plan *plan);
 int launch_repack(reshard_plan *plan, hipStream_t stream);
+int launch_source(reshard_plan *plan, int src_index, hipStream_t stream);
 }  // namespace reshard
 
 using namespace reshard;
@@ -50,6 +52,41 @@ int check_ptrs(const Side &s, const void *const *ptrs, const char *what) {
     return RESHARD_OK;
 }
 
+// ---- per-buffer residency ------------------------------------------------------------
+// Every used source buffer carries its own RESHARD_SRC_* state; the plan-level state is the
+// common state of the used buffers, or RESHARD_SRC_MIXED while they differ (streaming).
+
+bool is_live(int st) {
+    return st == RESHARD_SRC_RESIDENT || st == RESHARD_SRC_SWAPPING_OUT || st == RESHARD_SRC_ON_HOST ||
+           st == RESHARD_SRC_SWAPPING_IN;
+}
+
+// Recomputes the plan-level state and the ledger's source figures from the buffer states.
+void recompute(reshard_plan *p) {
+    int common = -1;
+    bool mixed = false;
+    int64_t live = 0, released = 0;
+    for (size_t i = 0; i < p->buf_state.size(); ++i) {
+        if (!p->src.used[i]) continue;
+        const int st = p->buf_state[i];
+        if (common < 0) common = st;
+        else if (common != st) mixed = true;
+        // a buffer on the host whose device pointer was dropped is not live
+        if (is_live(st) && p->src_ptrs[i]) live += p->src.buf_bytes[i];
+        if (st == RESHARD_SRC_RELEASED) released += p->src.buf_bytes[i];
+    }
+    p->state = common < 0 ? RESHARD_SRC_UNBOUND : mixed ? RESHARD_SRC_MIXED : common;
+    p->src_live = live;
+    p->released = released;
+    p->touch_peak();
+}
+
+void set_all(reshard_plan *p, int st) {
+    for (size_t i = 0; i < p->buf_state.size(); ++i)
+        if (p->src.used[i]) p->buf_state[i] = st;
+    recompute(p);
+}
+
 int ensure_swap_objects(reshard_plan *p) {
     if (!p->side_stream) {
         hipStream_t s;
@@ -60,11 +97,6 @@ int ensure_swap_objects(reshard_plan *p) {
         hipEvent_t ev;
         if (hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) return hip_fail(e, "hipEventCreate");
         p->ev_ready = ev;
-    }
-    if (!p->ev_done) {
-        hipEvent_t ev;
-        if (hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) return hip_fail(e, "hipEventCreate");
-        p->ev_done = ev;
     }
     if (p->ev_buf.empty()) p->ev_buf.assign(p->src.buf_bytes.size(), nullptr);
     for (size_t i = 0; i < p->ev_buf.size(); ++i) {
@@ -84,19 +116,20 @@ void free_host_copies(reshard_plan *p) {
     p->host_pinned = 0;
 }
 
-// All-or-nothing allocation of the pinned copies.
-int ensure_host_copies(reshard_plan *p) {
+// All-or-nothing allocation of the pinned copies of the buffers selected by `only` (-1 = all used).
+int ensure_host_copies(reshard_plan *p, int only = -1) {
     const Side &s = p->src;
+    auto wanted = [&](size_t i) { return s.used[i] && !p->host_copy[i] && (only < 0 || size_t(only) == i); };
     int64_t need = 0;
     for (size_t i = 0; i < s.buf_bytes.size(); ++i)
-        if (s.used[i] && !p->host_copy[i]) need += s.buf_bytes[i];
+        if (wanted(i)) need += s.buf_bytes[i];
     if (need == 0) return RESHARD_OK;
     const int64_t limit = g_host_limit.load();
     if (limit >= 0 && p->host_pinned + need > limit)
         return fail(RESHARD_ERR_HOST_OOM, "pinned host allocation refused by the configured limit");
     std::vector<size_t> fresh;
     for (size_t i = 0; i < s.buf_bytes.size(); ++i) {
-        if (!s.used[i] || p->host_copy[i]) continue;
+        if (!wanted(i)) continue;
         void *h = nullptr;
         if (hipError_t e = hipHostMalloc(&h, size_t(s.buf_bytes[i]), hipHostMallocDefault)) {
             (void)hipGetLastError();
@@ -114,10 +147,46 @@ int ensure_host_copies(reshard_plan *p) {
     return RESHARD_OK;
 }
 
+// Completes the copy of one buffer on the host side (blocks until its event has fired).
+int finish_buffer(reshard_plan *p, size_t i) {
+    const int st = p->buf_state[i];
+    if (st != RESHARD_SRC_SWAPPING_OUT && st != RESHARD_SRC_SWAPPING_IN) return RESHARD_OK;
+    if (hipError_t e = hipEventSynchronize(static_cast<hipEvent_t>(p->ev_buf[i]))) return hip_fail(e, "hipEventSynchronize");
+    p->buf_state[i] = st == RESHARD_SRC_SWAPPING_OUT ? RESHARD_SRC_ON_HOST : RESHARD_SRC_RESIDENT;
+    return RESHARD_OK;
+}
+
 int finish_swap(reshard_plan *p) {
-    if (p->state != RESHARD_SRC_SWAPPING_OUT && p->state != RESHARD_SRC_SWAPPING_IN) return RESHARD_OK;
-    if (hipError_t e = hipEventSynchronize(static_cast<hipEvent_t>(p->ev_done))) return hip_fail(e, "hipEventSynchronize");
-    p->state = p->state == RESHARD_SRC_SWAPPING_OUT ? RESHARD_SRC_ON_HOST : RESHARD_SRC_RESIDENT;
+    for (size_t i = 0; i < p->buf_state.size(); ++i)
+        if (p->src.used[i])
+            if (int rc = finish_buffer(p, i)) return rc;
+    recompute(p);
+    return RESHARD_OK;
+}
+
+bool overlaps(const void *a, int64_t an, const void *b, int64_t bn) {
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), a1 = a0 + uintptr_t(an);
+    const uintptr_t b0 = reinterpret_cast<uintptr_t>(b), b1 = b0 + uintptr_t(bn);
+    return a0 < b1 && b0 < a1;
+}
+
+// One device-to-host or host-to-device copy of buffer i on the side stream, followed by its event.
+int queue_copy(reshard_plan *p, size_t i, bool to_host) {
+    hipStream_t side = static_cast<hipStream_t>(p->side_stream);
+    const size_t n = size_t(p->src.buf_bytes[i]);
+    hipError_t e = to_host ? hipMemcpyAsync(p->host_copy[i], p->src_ptrs[i], n, hipMemcpyDeviceToHost, side)
+                           : hipMemcpyAsync(const_cast<void *>(p->src_ptrs[i]), p->host_copy[i], n, hipMemcpyHostToDevice, side);
+    if (e) return hip_fail(e, to_host ? "hipMemcpyAsync device-to-host" : "hipMemcpyAsync host-to-device");
+    if (hipError_t e2 = hipEventRecord(static_cast<hipEvent_t>(p->ev_buf[i]), side)) return hip_fail(e2, "hipEventRecord");
+    p->swapped_once = true;
+    return RESHARD_OK;
+}
+
+// Makes the side stream wait for everything queued on `stream` so far.
+int order_after(reshard_plan *p, void *stream) {
+    hipEvent_t ready = static_cast<hipEvent_t>(p->ev_ready);
+    if (hipError_t e = hipEventRecord(ready, static_cast<hipStream_t>(stream))) return hip_fail(e, "hipEventRecord");
+    if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(p->side_stream), ready, 0)) return hip_fail(e, "hipStreamWaitEvent");
     return RESHARD_OK;
 }
 
@@ -174,6 +243,7 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
         p->src_ptrs.assign(ns, nullptr);
         p->dst_ptrs.assign(nd, nullptr);
         p->host_copy.assign(ns, nullptr);
+        p->buf_state.assign(ns, RESHARD_SRC_UNBOUND);
     } catch (const std::bad_alloc &) {
         delete p;
         return fail(RESHARD_ERR_OOM, "out of host memory while building the plan");
@@ -184,15 +254,16 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
 
 extern "C" int reshard_plan_destroy(reshard_plan *p) {
     if (!p) return RESHARD_OK;
-    if (p->state == RESHARD_SRC_SWAPPING_OUT || p->state == RESHARD_SRC_SWAPPING_IN)
-        (void)hipEventSynchronize(static_cast<hipEvent_t>(p->ev_done));
+    for (size_t i = 0; i < p->buf_state.size(); ++i)  // copies still in flight use the host blocks
+        if (p->src.used[i] && (p->buf_state[i] == RESHARD_SRC_SWAPPING_OUT || p->buf_state[i] == RESHARD_SRC_SWAPPING_IN))
+            (void)hipEventSynchronize(static_cast<hipEvent_t>(p->ev_buf[i]));
     free_host_copies(p);
     if (p->side_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(p->side_stream));
     if (p->ev_ready) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev_ready));
-    if (p->ev_done) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev_done));
     for (void *ev : p->ev_buf)
         if (ev) (void)hipEventDestroy(static_cast<hipEvent_t>(ev));
     if (p->d_tiles) (void)hipFree(p->d_tiles);
+    if (p->d_by_src) (void)hipFree(p->d_by_src);
     delete p;
     return RESHARD_OK;
 }
@@ -284,14 +355,13 @@ extern "C" int reshard_plan_prepare(reshard_plan *p) {
 
 extern "C" int reshard_bind_src(reshard_plan *p, const void *const *src_ptrs) {
     if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
-    if (p->state == RESHARD_SRC_SWAPPING_OUT || p->state == RESHARD_SRC_SWAPPING_IN)
-        return fail(RESHARD_ERR_BAD_STATE, "swap copies are in flight; call reshard_swap_wait first");
+    if (p->state != RESHARD_SRC_UNBOUND && p->state != RESHARD_SRC_RESIDENT && p->state != RESHARD_SRC_ON_HOST &&
+        p->state != RESHARD_SRC_RELEASED)
+        return fail(RESHARD_ERR_BAD_STATE, "swap copies are in flight, or the buffers are in different states");
     if (int rc = check_ptrs(p->src, src_ptrs, "src_ptrs")) return rc;
     for (size_t i = 0; i < p->src_ptrs.size(); ++i) p->src_ptrs[i] = p->src.used[i] ? src_ptrs[i] : nullptr;
-    p->src_live = used_bytes(p->src);
-    if (p->state == RESHARD_SRC_UNBOUND) p->state = RESHARD_SRC_RESIDENT;
-    if (p->state == RESHARD_SRC_RELEASED) p->state = RESHARD_SRC_ON_HOST;
-    p->touch_peak();
+    set_all(p, p->state == RESHARD_SRC_UNBOUND ? RESHARD_SRC_RESIDENT
+             : p->state == RESHARD_SRC_RELEASED ? RESHARD_SRC_ON_HOST : p->state);
     return RESHARD_OK;
 }
 
@@ -300,37 +370,52 @@ extern "C" int reshard_execute(reshard_plan *p, const void *const *src_ptrs, voi
     // while a swap-out is in flight the sources are still valid in HBM and only read
     const bool swapping_out = p->state == RESHARD_SRC_SWAPPING_OUT;
     if (p->state != RESHARD_SRC_UNBOUND && p->state != RESHARD_SRC_RESIDENT && !swapping_out)
-        return fail(RESHARD_ERR_BAD_STATE, "the source weights are not resident on the device");
+        return fail(RESHARD_ERR_BAD_STATE, "the source weights are not (all) resident on the device");
     if (int rc = check_ptrs(p->src, src_ptrs, "src_ptrs")) return rc;
     if (swapping_out)
         for (size_t i = 0; i < p->src_ptrs.size(); ++i)
             if (p->src.used[i] && src_ptrs[i] != p->src_ptrs[i])
                 return fail(RESHARD_ERR_BAD_STATE, "a swap-out of other source pointers is in flight");
     if (int rc = check_ptrs(p->dst, reinterpret_cast<const void *const *>(dst_ptrs), "dst_ptrs")) return rc;
-    // the two sets must not overlap
     for (size_t i = 0; i < p->src.buf_bytes.size(); ++i) {
         if (!p->src.used[i]) continue;
-        const uintptr_t a0 = reinterpret_cast<uintptr_t>(src_ptrs[i]), a1 = a0 + uintptr_t(p->src.buf_bytes[i]);
-        for (size_t j = 0; j < p->dst.buf_bytes.size(); ++j) {
-            if (!p->dst.used[j]) continue;
-            const uintptr_t b0 = reinterpret_cast<uintptr_t>(dst_ptrs[j]), b1 = b0 + uintptr_t(p->dst.buf_bytes[j]);
-            if (a0 < b1 && b0 < a1) return fail(RESHARD_ERR_INVALID_ARG, "a source and a destination buffer overlap");
-        }
+        for (size_t j = 0; j < p->dst.buf_bytes.size(); ++j)
+            if (p->dst.used[j] && overlaps(src_ptrs[i], p->src.buf_bytes[i], dst_ptrs[j], p->dst.buf_bytes[j]))
+                return fail(RESHARD_ERR_INVALID_ARG, "a source and a destination buffer overlap");
     }
     if (int rc = ensure_device_table(p)) return rc;
-    {
-        int dev = -1;
-        if (hipError_t e = hipGetDevice(&dev)) return hip_fail(e, "hipGetDevice");
-        if (dev != p->device) return fail(RESHARD_ERR_INVALID_ARG, "the plan's tile table lives on another device than the current one");
-    }
     for (size_t i = 0; i < p->src_ptrs.size(); ++i) p->src_ptrs[i] = p->src.used[i] ? src_ptrs[i] : nullptr;
     for (size_t j = 0; j < p->dst_ptrs.size(); ++j) p->dst_ptrs[j] = p->dst.used[j] ? dst_ptrs[j] : nullptr;
     if (int rc = launch_repack(p, static_cast<hipStream_t>(stream))) return rc;
-    if (!swapping_out) p->state = RESHARD_SRC_RESIDENT;
     p->dst_bound = true;
-    p->src_live = used_bytes(p->src);
     p->dst_live = used_bytes(p->dst);
-    p->touch_peak();
+    if (swapping_out) recompute(p);
+    else set_all(p, RESHARD_SRC_RESIDENT);
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_execute_source(reshard_plan *p, int src_index, const void *src_ptr, void *const *dst_ptrs,
+                                      void *stream) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    if (src_index < 0 || src_index >= int(p->src.buf_bytes.size()) || !p->src.used[size_t(src_index)])
+        return fail(RESHARD_ERR_INVALID_ARG, "src_index does not name a used source buffer");
+    const size_t i = size_t(src_index);
+    if (p->buf_state[i] != RESHARD_SRC_UNBOUND && p->buf_state[i] != RESHARD_SRC_RESIDENT)
+        return fail(RESHARD_ERR_BAD_STATE, "this source buffer is not resident on the device");
+    if (!src_ptr || reinterpret_cast<uintptr_t>(src_ptr) % 256)
+        return fail(RESHARD_ERR_INVALID_ARG, "src_ptr is NULL or not 256-byte aligned");
+    if (int rc = check_ptrs(p->dst, reinterpret_cast<const void *const *>(dst_ptrs), "dst_ptrs")) return rc;
+    for (size_t j = 0; j < p->dst.buf_bytes.size(); ++j)
+        if (p->dst.used[j] && overlaps(src_ptr, p->src.buf_bytes[i], dst_ptrs[j], p->dst.buf_bytes[j]))
+            return fail(RESHARD_ERR_INVALID_ARG, "the source buffer overlaps a destination buffer");
+    if (int rc = ensure_by_source_table(p)) return rc;
+    p->src_ptrs[i] = src_ptr;
+    for (size_t j = 0; j < p->dst_ptrs.size(); ++j) p->dst_ptrs[j] = p->dst.used[j] ? dst_ptrs[j] : nullptr;
+    if (int rc = launch_source(p, src_index, static_cast<hipStream_t>(stream))) return rc;
+    p->dst_bound = true;
+    p->dst_live = used_bytes(p->dst);
+    p->buf_state[i] = RESHARD_SRC_RESIDENT;
+    recompute(p);
     return RESHARD_OK;
 }
 
@@ -339,41 +424,46 @@ extern "C" int reshard_swap_out(reshard_plan *p, void *stream) {
     if (p->state != RESHARD_SRC_RESIDENT) return fail(RESHARD_ERR_BAD_STATE, "swap_out needs bound, resident source buffers");
     if (int rc = ensure_host_copies(p)) return rc;
     if (int rc = ensure_swap_objects(p)) return rc;
-    hipStream_t side = static_cast<hipStream_t>(p->side_stream);
-    hipEvent_t ready = static_cast<hipEvent_t>(p->ev_ready), done = static_cast<hipEvent_t>(p->ev_done);
-    if (hipError_t e = hipEventRecord(ready, static_cast<hipStream_t>(stream))) return hip_fail(e, "hipEventRecord");
-    if (hipError_t e = hipStreamWaitEvent(side, ready, 0)) return hip_fail(e, "hipStreamWaitEvent");
-    for (size_t i = 0; i < p->src_ptrs.size(); ++i) {
-        if (!p->src.used[i]) continue;
-        if (hipError_t e = hipMemcpyAsync(p->host_copy[i], p->src_ptrs[i], size_t(p->src.buf_bytes[i]), hipMemcpyDeviceToHost, side))
-            return hip_fail(e, "hipMemcpyAsync device-to-host");
-        if (hipError_t e = hipEventRecord(static_cast<hipEvent_t>(p->ev_buf[i]), side)) return hip_fail(e, "hipEventRecord");
-    }
-    p->swapped_once = true;
-    if (hipError_t e = hipEventRecord(done, side)) return hip_fail(e, "hipEventRecord");
-    p->state = RESHARD_SRC_SWAPPING_OUT;
+    if (int rc = order_after(p, stream)) return rc;
+    for (size_t i = 0; i < p->src_ptrs.size(); ++i)
+        if (p->src.used[i])
+            if (int rc = queue_copy(p, i, true)) return rc;
+    set_all(p, RESHARD_SRC_SWAPPING_OUT);
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_swap_out_source(reshard_plan *p, int src_index, void *stream) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    if (src_index < 0 || src_index >= int(p->src.buf_bytes.size()) || !p->src.used[size_t(src_index)])
+        return fail(RESHARD_ERR_INVALID_ARG, "src_index does not name a used source buffer");
+    const size_t i = size_t(src_index);
+    if (p->buf_state[i] != RESHARD_SRC_RESIDENT) return fail(RESHARD_ERR_BAD_STATE, "this source buffer is not bound and resident");
+    if (int rc = ensure_host_copies(p, src_index)) return rc;
+    if (int rc = ensure_swap_objects(p)) return rc;
+    if (int rc = order_after(p, stream)) return rc;
+    if (int rc = queue_copy(p, i, true)) return rc;
+    p->buf_state[i] = RESHARD_SRC_SWAPPING_OUT;
+    recompute(p);
     return RESHARD_OK;
 }
 
 extern "C" int reshard_swap_in(reshard_plan *p, void *stream) {
     if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
     if (p->state == RESHARD_SRC_RELEASED) return fail(RESHARD_ERR_BAD_STATE, "the device copy was released: bind new source pointers first");
-    if (p->state != RESHARD_SRC_ON_HOST) return fail(RESHARD_ERR_BAD_STATE, "swap_in needs a completed swap_out");
+    if (p->state != RESHARD_SRC_ON_HOST) return fail(RESHARD_ERR_BAD_STATE, "swap_in needs a completed swap_out of every buffer");
     if (int rc = ensure_swap_objects(p)) return rc;
-    hipStream_t side = static_cast<hipStream_t>(p->side_stream);
-    hipEvent_t ready = static_cast<hipEvent_t>(p->ev_ready), done = static_cast<hipEvent_t>(p->ev_done);
     // work already queued on `stream` may still use the memory being overwritten
-    if (hipError_t e = hipEventRecord(ready, static_cast<hipStream_t>(stream))) return hip_fail(e, "hipEventRecord");
-    if (hipError_t e = hipStreamWaitEvent(side, ready, 0)) return hip_fail(e, "hipStreamWaitEvent");
+    if (int rc = order_after(p, stream)) return rc;
+    size_t last = 0;
     for (size_t i = 0; i < p->src_ptrs.size(); ++i) {
         if (!p->src.used[i]) continue;
-        if (hipError_t e = hipMemcpyAsync(const_cast<void *>(p->src_ptrs[i]), p->host_copy[i], size_t(p->src.buf_bytes[i]), hipMemcpyHostToDevice, side))
-            return hip_fail(e, "hipMemcpyAsync host-to-device");
-        if (hipError_t e = hipEventRecord(static_cast<hipEvent_t>(p->ev_buf[i]), side)) return hip_fail(e, "hipEventRecord");
+        if (int rc = queue_copy(p, i, false)) return rc;
+        last = i;
     }
-    if (hipError_t e = hipEventRecord(done, side)) return hip_fail(e, "hipEventRecord");
-    if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), done, 0)) return hip_fail(e, "hipStreamWaitEvent");
-    p->state = RESHARD_SRC_SWAPPING_IN;
+    // the copies run in buffer order, so the last buffer's event marks the end of all of them
+    if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(p->ev_buf[last]), 0))
+        return hip_fail(e, "hipStreamWaitEvent");
+    set_all(p, RESHARD_SRC_SWAPPING_IN);
     return RESHARD_OK;
 }
 
@@ -383,10 +473,16 @@ extern "C" int reshard_swap_wait_buffer(reshard_plan *p, int index, void *stream
         return fail(RESHARD_ERR_INVALID_ARG, "index does not name a used source buffer");
     if (!p->swapped_once || p->ev_buf.empty() || !p->ev_buf[size_t(index)])
         return fail(RESHARD_ERR_BAD_STATE, "no swap has been started on this plan");
-    hipEvent_t ev = static_cast<hipEvent_t>(p->ev_buf[size_t(index)]);
     if (host_wait) {
-        if (hipError_t e = hipEventSynchronize(ev)) return hip_fail(e, "hipEventSynchronize");
-    } else if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), ev, 0)) {
+        // also completes this buffer's state change (SWAPPING_OUT -> ON_HOST, SWAPPING_IN -> RESIDENT)
+        const int st = p->buf_state[size_t(index)];
+        if (st == RESHARD_SRC_SWAPPING_OUT || st == RESHARD_SRC_SWAPPING_IN) {
+            if (int rc = finish_buffer(p, size_t(index))) return rc;
+            recompute(p);
+        } else if (hipError_t e = hipEventSynchronize(static_cast<hipEvent_t>(p->ev_buf[size_t(index)]))) {
+            return hip_fail(e, "hipEventSynchronize");
+        }
+    } else if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(p->ev_buf[size_t(index)]), 0)) {
         return hip_fail(e, "hipStreamWaitEvent");
     }
     return RESHARD_OK;
@@ -400,10 +496,20 @@ extern "C" int reshard_swap_wait(reshard_plan *p) {
 extern "C" int reshard_mark_src_released(reshard_plan *p) {
     if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
     if (p->state != RESHARD_SRC_ON_HOST) return fail(RESHARD_ERR_BAD_STATE, "sources can be released only after a completed swap_out");
-    p->released = p->src_live;
-    p->src_live = 0;
     std::fill(p->src_ptrs.begin(), p->src_ptrs.end(), nullptr);
-    p->state = RESHARD_SRC_RELEASED;
+    set_all(p, RESHARD_SRC_RELEASED);
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_mark_src_buffer_released(reshard_plan *p, int src_index) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    if (src_index < 0 || src_index >= int(p->src.buf_bytes.size()) || !p->src.used[size_t(src_index)])
+        return fail(RESHARD_ERR_INVALID_ARG, "src_index does not name a used source buffer");
+    if (p->buf_state[size_t(src_index)] != RESHARD_SRC_ON_HOST)
+        return fail(RESHARD_ERR_BAD_STATE, "a source buffer can be released only after its swap-out has completed");
+    p->src_ptrs[size_t(src_index)] = nullptr;
+    p->buf_state[size_t(src_index)] = RESHARD_SRC_RELEASED;
+    recompute(p);
     return RESHARD_OK;
 }
 
@@ -426,6 +532,11 @@ extern "C" int reshard_release_host(reshard_plan *p) {
 extern "C" const void *reshard_host_copy(const reshard_plan *p, int index) {
     if (!p || index < 0 || index >= int(p->host_copy.size())) return nullptr;
     return p->host_copy[size_t(index)];
+}
+
+extern "C" int reshard_src_buffer_state(const reshard_plan *p, int src_index) {
+    if (!p || src_index < 0 || src_index >= int(p->buf_state.size())) return fail(RESHARD_ERR_INVALID_ARG, "bad plan or index");
+    return p->buf_state[size_t(src_index)];
 }
 
 extern "C" int reshard_mem_stats(const reshard_plan *p, reshard_mem_stats_t *out) {

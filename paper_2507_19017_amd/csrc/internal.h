@@ -99,6 +99,11 @@ struct reshard_plan {
     int device = -1;
     void *d_tiles = nullptr;  // copy, fast transposing, 64 x 64 transposing, generic transposing tiles
     int num_cus = 0;
+    // streaming (created by the first execute_source): the tiles regrouped by source buffer
+    struct SrcSlice { uint32_t first[4] = {0, 0, 0, 0}, count[4] = {0, 0, 0, 0}; };
+    std::vector<SrcSlice> src_slices;
+    std::vector<reshard::Tile> by_src_tiles;
+    void *d_by_src = nullptr;
 
     // bound pointers
     std::vector<const void *> src_ptrs;
@@ -111,8 +116,8 @@ struct reshard_plan {
     int64_t host_pinned = 0;
     void *side_stream = nullptr;
     void *ev_ready = nullptr;  // recorded on the caller's stream
-    void *ev_done = nullptr;   // recorded on the side stream
-    std::vector<void *> ev_buf; // per source buffer: recorded after that buffer's copy (lazy)
+    std::vector<void *> ev_buf; // per source buffer: recorded on the side stream after that buffer's copy
+    std::vector<int> buf_state; // per source buffer: RESHARD_SRC_*; `state` is their common value or MIXED
     bool swapped_once = false;
 
     // ledger

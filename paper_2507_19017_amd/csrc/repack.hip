@@ -338,33 +338,27 @@ Tuning current_tuning() {
     return g_tuning;
 }
 
-// Uploads the tile table on first use; returns RESHARD_OK or an error code.
-int ensure_device_table(reshard_plan *plan) {
-    if (plan->d_tiles || plan->info.num_tiles == 0) {
-        if (plan->device < 0) {
-            int dev = 0;
-            if (hipError_t e = hipGetDevice(&dev)) return hip_fail(e, "hipGetDevice");
-            plan->device = dev;
-        }
-        if (plan->num_cus == 0) {
-            int cus = 0;
-            if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, plan->device))
-                return hip_fail(e, "hipDeviceGetAttribute");
-            plan->num_cus = cus;
-        }
-        return RESHARD_OK;
-    }
-    int dev = 0;
+namespace {
+
+int query_device(reshard_plan *plan) {
+    int dev = 0, cus = 0;
     if (hipError_t e = hipGetDevice(&dev)) return hip_fail(e, "hipGetDevice");
-    int cus = 0;
-    if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))
-        return hip_fail(e, "hipDeviceGetAttribute");
-    const std::vector<Tile> *lists[4] = {&plan->copy_tiles, &plan->fast_transpose_tiles,
-                                         &plan->edge_transpose_tiles, &plan->transpose_tiles};
+    if (plan->device >= 0 && plan->device != dev)
+        return fail(RESHARD_ERR_INVALID_ARG, "the plan's tile table lives on another device than the current one");
+    if (plan->num_cus == 0) {
+        if (hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))
+            return hip_fail(e, "hipDeviceGetAttribute");
+        plan->num_cus = cus;
+    }
+    plan->device = dev;
+    return RESHARD_OK;
+}
+
+int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
     size_t total = 0;
     for (auto *l : lists) total += l->size();
     void *mem = nullptr;
-    if (hipError_t e = hipMalloc(&mem, total * sizeof(Tile))) {
+    if (hipError_t e = hipMalloc(&mem, std::max<size_t>(total, 1) * sizeof(Tile))) {
         (void)hipGetLastError();
         return fail(RESHARD_ERR_OOM, std::string("hipMalloc of the tile table: ") + hipGetErrorString(e));
     }
@@ -377,54 +371,41 @@ int ensure_device_table(reshard_plan *plan) {
         }
         at += l->size();
     }
-    plan->d_tiles = mem;
-    plan->device = dev;
-    plan->num_cus = cus;
+    *out = mem;
     return RESHARD_OK;
 }
 
-int launch_repack(reshard_plan *plan, hipStream_t stream) {
-    const Tuning tn = current_tuning();
-    PtrTable pt;
-    std::memset(&pt, 0, sizeof pt);
-    const int ns = plan->info.num_src_bufs, nd = plan->info.num_dst_bufs;
-    for (int i = 0; i < ns; ++i) pt.p[i] = const_cast<char *>(static_cast<const char *>(plan->src_ptrs[i]));
-    for (int i = 0; i < nd; ++i) pt.p[ns + i] = static_cast<char *>(plan->dst_ptrs[i]);
-    const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
-    const uint32_t nc = uint32_t(plan->copy_tiles.size()), nf = uint32_t(plan->fast_transpose_tiles.size()),
-                   ne = uint32_t(plan->edge_transpose_tiles.size()), nt = uint32_t(plan->transpose_tiles.size());
+// Launches `n` tiles of one class (0 copy, 1 register transpose in the tuned shape, 2 register
+// transpose 64 x 64, 3 generic transpose) starting at device address `t`.
+int launch_class(const reshard_plan *plan, const Tuning &tn, int cls, const Tile *t, uint32_t n,
+                 const PtrTable &pt, hipStream_t stream) {
+    if (!n) return RESHARD_OK;
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
     const uint32_t wanted = tn.blocks_per_cu ? uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu) : 0xFFFFFFFFu;
-    if (nc && tn.blocks_per_cu) {
-        dim3 grid(std::min(nc, wanted)), block(tn.block_threads);
-        launch_copy(tn, grid, block, stream, tiles, nc, pt);
+    const int by_xcd = (tn.flags & 8) ? 1 : 0;
+    if (cls == 0 && tn.blocks_per_cu) {
+        launch_copy(tn, dim3(std::min(n, wanted)), dim3(tn.block_threads), stream, t, n, pt);
         if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
-    } else if (nc) {
-        // one tile per workgroup; a launch may not exceed 2^32 - 1 lanes in x, so very long
-        // tables go out in slices
+    } else if (cls == 0) {
+        // a launch may not exceed 2^32 - 1 lanes in x, so very long tables go out in slices
         const uint32_t per_launch = (0xFFFFFFFFu / uint32_t(tn.block_threads)) & ~7u;
-        for (uint32_t first = 0; first < nc; first += per_launch) {
-            const uint32_t n = std::min(per_launch, nc - first);
-            launch_copy(tn, dim3(n), dim3(tn.block_threads), stream, tiles + first, n, pt);
+        for (uint32_t first = 0; first < n; first += per_launch) {
+            const uint32_t m = std::min(per_launch, n - first);
+            launch_copy(tn, dim3(m), dim3(tn.block_threads), stream, t + first, m, pt);
             if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
         }
-    }
-    // register-transposed tiles: the interior in the tuned shape, the strips in 64 x 64
-    struct FastClass { uint32_t first, count; int rows, cols; };
-    const FastClass classes[2] = {{nc, nf, plan->fast_rows, plan->fast_cols}, {nc + nf, ne, 64, 64}};
-    for (const FastClass &fc : classes) {
-        if (!fc.count) continue;
-        const int shape = fc.rows * 1000 + fc.cols;
-        const int by_xcd = (tn.flags & 8) ? 1 : 0;
-        const uint32_t threads = uint32_t(std::min(fc.rows * fc.cols / 64, 1024));
-        const uint32_t per_launch = (0xFFFFFFFFu / threads) & ~7u;  // at most 2^32 - 1 lanes per launch
-        for (uint32_t first = 0; first < fc.count; first += per_launch) {
-            const Tile *ft = tiles + fc.first + first;
-            const uint32_t n = std::min(per_launch, fc.count - first);
-            const dim3 grid(by_xcd ? (n + 7) / 8 * 8 : n), block(threads);
+    } else if (cls == 1 || cls == 2) {
+        const int rows = cls == 1 ? plan->fast_rows : 64, cols = cls == 1 ? plan->fast_cols : 64;
+        const int shape = rows * 1000 + cols;
+        const uint32_t threads = uint32_t(std::min(rows * cols / 64, 1024));
+        const uint32_t per_launch = (0xFFFFFFFFu / threads) & ~7u;
+        for (uint32_t first = 0; first < n; first += per_launch) {
+            const Tile *ft = t + first;
+            const uint32_t m = std::min(per_launch, n - first);
+            const dim3 grid(by_xcd ? (m + 7) / 8 * 8 : m), block(threads);
 #define RESHARD_T16(TI, TK)                                                                                  \
     case TI * 1000 + TK:                                                                                     \
-        hipLaunchKernelGGL((repack_transpose16_kernel<TI, TK>), grid, block, 0, stream, ft, n, pt, by_xcd);  \
+        hipLaunchKernelGGL((repack_transpose16_kernel<TI, TK>), grid, block, 0, stream, ft, m, pt, by_xcd);  \
         break;
             switch (shape) {
                 RESHARD_T16(64, 64) RESHARD_T16(64, 128) RESHARD_T16(64, 256)
@@ -435,18 +416,86 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
 #undef RESHARD_T16
             if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the register-transpose kernel");
         }
-    }
-    if (nt) {
-        dim3 grid(std::min(nt, wanted)), block(256);
-        const Tile *tt = tiles + nc + nf + ne;
+    } else {
+        dim3 grid(std::min(n, wanted)), block(256);
         switch (plan->spec.elem_bytes) {
-            case 1: hipLaunchKernelGGL(repack_transpose_kernel<uint8_t>, grid, block, 0, stream, tt, nt, pt); break;
-            case 2: hipLaunchKernelGGL(repack_transpose_kernel<uint16_t>, grid, block, 0, stream, tt, nt, pt); break;
-            case 4: hipLaunchKernelGGL(repack_transpose_kernel<uint32_t>, grid, block, 0, stream, tt, nt, pt); break;
-            default: hipLaunchKernelGGL(repack_transpose_kernel<uint64_t>, grid, block, 0, stream, tt, nt, pt); break;
+            case 1: hipLaunchKernelGGL(repack_transpose_kernel<uint8_t>, grid, block, 0, stream, t, n, pt); break;
+            case 2: hipLaunchKernelGGL(repack_transpose_kernel<uint16_t>, grid, block, 0, stream, t, n, pt); break;
+            case 4: hipLaunchKernelGGL(repack_transpose_kernel<uint32_t>, grid, block, 0, stream, t, n, pt); break;
+            default: hipLaunchKernelGGL(repack_transpose_kernel<uint64_t>, grid, block, 0, stream, t, n, pt); break;
         }
         if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the transpose kernel");
     }
+    return RESHARD_OK;
+}
+
+void fill_ptrs(const reshard_plan *plan, PtrTable &pt) {
+    std::memset(&pt, 0, sizeof pt);
+    const int ns = plan->info.num_src_bufs, nd = plan->info.num_dst_bufs;
+    for (int i = 0; i < ns; ++i) pt.p[i] = const_cast<char *>(static_cast<const char *>(plan->src_ptrs[i]));
+    for (int i = 0; i < nd; ++i) pt.p[ns + i] = static_cast<char *>(plan->dst_ptrs[i]);
+}
+
+const std::vector<Tile> &class_list(const reshard_plan *plan, int cls) {
+    return cls == 0 ? plan->copy_tiles : cls == 1 ? plan->fast_transpose_tiles
+         : cls == 2 ? plan->edge_transpose_tiles : plan->transpose_tiles;
+}
+
+}  // namespace
+
+// Uploads the tile table on first use; returns RESHARD_OK or an error code.
+int ensure_device_table(reshard_plan *plan) {
+    if (int rc = query_device(plan)) return rc;
+    if (plan->d_tiles || plan->info.num_tiles == 0) return RESHARD_OK;
+    return upload({&plan->copy_tiles, &plan->fast_transpose_tiles, &plan->edge_transpose_tiles, &plan->transpose_tiles},
+                  &plan->d_tiles);
+}
+
+int launch_repack(reshard_plan *plan, hipStream_t stream) {
+    const Tuning tn = current_tuning();
+    PtrTable pt;
+    fill_ptrs(plan, pt);
+    const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
+    for (int cls = 0; cls < 4; ++cls) {
+        const uint32_t n = uint32_t(class_list(plan, cls).size());
+        if (int rc = launch_class(plan, tn, cls, tiles, n, pt, stream)) return rc;
+        tiles += n;
+    }
+    return RESHARD_OK;
+}
+
+// Streaming: the same tiles regrouped by the source buffer they read, so that the part of the
+// plan that needs one source buffer can run as soon as that buffer has arrived.  Built and
+// uploaded on first use (a second copy of the table).
+int ensure_by_source_table(reshard_plan *plan) {
+    if (int rc = query_device(plan)) return rc;
+    if (plan->d_by_src) return RESHARD_OK;
+    const size_t ns = size_t(plan->info.num_src_bufs);
+    plan->src_slices.assign(ns, reshard_plan::SrcSlice{});
+    for (int cls = 0; cls < 4; ++cls)
+        for (const Tile &t : class_list(plan, cls)) ++plan->src_slices[t.src_buf].count[cls];
+    uint32_t at = 0;
+    for (size_t b = 0; b < ns; ++b)
+        for (int cls = 0; cls < 4; ++cls) {
+            plan->src_slices[b].first[cls] = at;
+            at += plan->src_slices[b].count[cls];
+        }
+    plan->by_src_tiles.resize(at);
+    std::vector<uint32_t> fill(ns * 4, 0);
+    for (int cls = 0; cls < 4; ++cls)
+        for (const Tile &t : class_list(plan, cls))  // table order is kept inside every group
+            plan->by_src_tiles[plan->src_slices[t.src_buf].first[cls] + fill[size_t(t.src_buf) * 4 + cls]++] = t;
+    return upload({&plan->by_src_tiles}, &plan->d_by_src);
+}
+
+int launch_source(reshard_plan *plan, int src_index, hipStream_t stream) {
+    const Tuning tn = current_tuning();
+    PtrTable pt;
+    fill_ptrs(plan, pt);
+    const Tile *base = static_cast<const Tile *>(plan->d_by_src);
+    const reshard_plan::SrcSlice &sl = plan->src_slices[size_t(src_index)];
+    for (int cls = 0; cls < 4; ++cls)
+        if (int rc = launch_class(plan, tn, cls, base + sl.first[cls], sl.count[cls], pt, stream)) return rc;
     return RESHARD_OK;
 }
 

@@ -198,6 +198,77 @@ def test_execute_on_a_side_stream_and_inside_a_hip_graph():
         G.assert_equal_buffers(dst, G.oracle_destinations(wl, G.to_host(src), 4), f"replay {replay}")
 
 
+# ------------------------------------------------------------- streaming ----
+@pytest.mark.parametrize("name", sorted(TINY) + ["C0"])
+def test_streaming_one_source_buffer_at_a_time(name):
+    """The gathered shards arrive one buffer at a time, are repacked, swapped out and dropped:
+    the destination equals the oracle's, only one source buffer is ever live, and the swapped
+    copies come back bit for bit."""
+    wl = {**TINY, **WORKLOADS}[name]
+    print("streaming", name, flush=True)
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    sizes, used = plan.buf_bytes(0), plan.buf_used(0)
+    dst = G.device_destinations(plan)
+    h = G.stream_handle()
+    keep = {}
+    order = [i for i, u in enumerate(used) if u][::-1]  # any order works; take the last buffer first
+    for n, i in enumerate(order):
+        buf = fill_buffer(sizes[i], wl["seed"] * 1000 + i, "cuda", "raw16")  # this buffer "arrives"
+        keep[i] = buf.cpu().numpy()
+        plan.execute_source(i, buf.data_ptr(), G.ptrs(dst), h)
+        assert plan.src_buffer_state(i) == "resident"
+        assert plan.mem_stats()["src_live"] == sizes[i]
+        plan.swap_out_source(i, h)
+        with pytest.raises(ReshardError) as e:
+            plan.execute_source(i, buf.data_ptr(), G.ptrs(dst), h)
+        assert e.value.code == binding.ERR_BAD_STATE
+        with pytest.raises(ReshardError) as e:
+            plan.mark_src_buffer_released(i)  # its copy has not been waited for
+        assert e.value.code == binding.ERR_BAD_STATE
+        plan.swap_wait_buffer(i)
+        assert plan.src_buffer_state(i) == "on_host"
+        plan.mark_src_buffer_released(i)
+        del buf
+        want_state = "released" if n == len(order) - 1 else "mixed"
+        assert plan.mem_stats()["state"] == want_state
+    torch.cuda.synchronize()
+    st = plan.mem_stats()
+    ndst = sum(b for b, u in zip(plan.buf_bytes(1), plan.buf_used(1)) if u)
+    assert st["src_live"] == 0 and st["released"] == sum(sizes[i] for i in order)
+    assert st["peak_device"] == ndst + max(sizes[i] for i in order)  # never more than one source buffer
+    host_src = [keep.get(i) for i in range(len(sizes))]
+    G.assert_equal_buffers(dst, G.oracle_destinations(wl, host_src, 4), name)
+    # before the next update: bind a fresh device home and swap everything back in
+    fresh = [torch.zeros(n // 2, dtype=torch.int16, device="cuda") if u else None for n, u in zip(sizes, used)]
+    plan.bind_src(G.ptrs(fresh))
+    assert plan.mem_stats()["state"] == "on_host"
+    plan.swap_in(h)
+    plan.swap_wait()
+    torch.cuda.synchronize()
+    for i in order:
+        assert np.array_equal(fresh[i].cpu().numpy(), keep[i])
+
+
+@pytest.mark.parametrize("name", ["C1", "C3"])
+def test_streaming_equals_one_shot_at_full_size(name):
+    wl = WORKLOADS[name]
+    print("streaming full size", name, flush=True)
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    src = G.device_sources(plan, wl)
+    one = G.device_destinations(plan)
+    h = G.stream_handle()
+    plan.execute(G.ptrs(src), G.ptrs(one), h)
+    stream_plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    two = G.device_destinations(stream_plan)
+    for i, s_ in enumerate(src):
+        if s_ is not None:
+            stream_plan.execute_source(i, s_.data_ptr(), G.ptrs(two), h)
+    torch.cuda.synchronize()
+    for a, b in zip(one, two):
+        assert (a is None and b is None) or torch.equal(a, b)
+    assert stream_plan.mem_stats()["state"] == "resident"
+
+
 # ------------------------------------------------------------------ swap ----
 def test_swap_round_trip_ledger_and_rebinding():
     wl = WORKLOADS["C0"]
