@@ -521,6 +521,11 @@ extern "C" int reshard_mark_dst_released(reshard_plan *p) {
     return RESHARD_OK;
 }
 
+extern "C" int reshard_reserve_host(reshard_plan *p) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    return ensure_host_copies(p);
+}
+
 extern "C" int reshard_release_host(reshard_plan *p) {
     if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
     if (p->state != RESHARD_SRC_UNBOUND && p->state != RESHARD_SRC_RESIDENT)

@@ -401,6 +401,8 @@ def test_pinned_allocation_failure_leaves_the_ledger_unchanged():
         assert plan.mem_stats() == before
     finally:
         binding.set_host_limit(-1)
+    plan.reserve_host()  # allocation ahead of the first swap-out
+    assert plan.mem_stats()["host_pinned"] == sum(plan.buf_bytes(0)) and plan.host_copy(0) != 0
     plan.swap_out(G.stream_handle())
     plan.swap_wait()
     assert plan.mem_stats()["state"] == "on_host"
