@@ -216,8 +216,10 @@ typedef struct reshard_tuning {
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
                                barrier between a tile's load burst and its store burst, bit 3: each XCD
                                walks a contiguous eighth of the tile table (default 15); -1 = none */
-    int32_t transpose_rows; /* shape of a register-transposed tile of 2-byte elements: source rows */
-    int32_t transpose_cols; /* ... and source columns; each 64, 128 or 256 (default 256 x 256) */
+    int32_t transpose_rows; /* shape of a register-transposed tile in elements: source rows ... */
+    int32_t transpose_cols; /* ... and source columns; each 64, 128, 256 or 512.  0, or a shape the plan's
+                             * element size does not allow (the tile must fit 128 KiB): the default for
+                             * that size (1 byte 512 x 256, 2 bytes 256 x 256, 4 bytes 128 x 256, 8 bytes 128 x 128) */
 } reshard_tuning;
 
 /* Thread-local message of the last failing call on this thread ("" if none). */

@@ -220,7 +220,10 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
         const Tuning tuning = current_tuning();
         p->fast_rows = tuning.transpose_rows;
         p->fast_cols = tuning.transpose_cols;
-        if (int rc = cut_tiles(p->descs, ns, tuning, p->copy_tiles, p->fast_transpose_tiles, p->edge_transpose_tiles,
+        if (!transpose_shape_ok(spec->elem_bytes, p->fast_rows, p->fast_cols))
+            transpose_default_shape(spec->elem_bytes, p->fast_rows, p->fast_cols);
+        p->edge_dim = transpose_edge_dim(spec->elem_bytes);
+        if (int rc = cut_tiles(p->descs, ns, tuning, p->fast_rows, p->fast_cols, p->edge_dim, p->copy_tiles, p->fast_transpose_tiles, p->edge_transpose_tiles,
                                p->transpose_tiles)) {
             delete p;
             return rc;

@@ -66,10 +66,28 @@ struct Tuning {
     int unroll = 8;
     int flags = 15;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
                                   // bit 3: each XCD walks a contiguous eighth of the tile table
-    int transpose_rows = 256;     // register-transposed tiles of 2-byte elements: rows x cols of the source
-    int transpose_cols = 256;
+    int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;
+    int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size
 };
 Tuning current_tuning();
+
+// Shapes the register-transpose kernel is built for: E-byte elements, ti x tk elements per tile.
+// (16 / E) x (16 / E) blocks, one per lane and round; at least eight 16-byte chunks per
+// destination row (the LDS swizzle needs them); whole waves; at most 128 KiB of LDS.
+constexpr bool transpose_shape_ok(int E, int ti, int tk) {
+    auto listed = [](int v) { return v == 64 || v == 128 || v == 256 || v == 512; };
+    if (!listed(ti) || !listed(tk) || (E != 1 && E != 2 && E != 4 && E != 8)) return false;
+    const int ve = 16 / E, blocks = (ti / ve) * (tk / ve);
+    if (E == 1 ? tk < 128 : (ti > 256 || tk > 256)) return false;  // shapes nobody needs are not built
+    return ti / ve >= 8 && blocks >= 64 && ti * tk * E <= 128 * 1024;
+}
+// Shape used when the tuning names none (or one the element size does not allow).
+inline void transpose_default_shape(int E, int &ti, int &tk) {
+    ti = E == 8 ? 128 : E == 4 ? 128 : E == 1 ? 512 : 256;
+    tk = E == 8 ? 128 : 256;
+}
+// The strips the big tiles leave over are cut into squares of this many elements.
+inline int transpose_edge_dim(int E) { return E == 1 ? 128 : 64; }
 
 void set_error(const std::string &msg);
 int fail(int code, const std::string &msg);
@@ -79,7 +97,7 @@ int build_side(const reshard_model_spec &spec, const reshard_layout &lay, bool i
 int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
                         std::vector<reshard_desc> &descs);
 int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
-              std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
+              int fast_rows, int fast_cols, int edge_dim, std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
               std::vector<Tile> &edge_transpose_tiles, std::vector<Tile> &transpose_tiles);
 
 }  // namespace reshard
@@ -88,16 +106,16 @@ struct reshard_plan {
     reshard_model_spec spec{};
     reshard::Side src, dst;
     std::vector<reshard_desc> descs;
-    // copy tiles; full tiles of 2-byte transposes (register path); remaining transposing tiles
+    // copy tiles; full transposing tiles (register path); remaining transposing tiles
     // (the register path takes the interior in fast_rows x fast_cols tiles and the strips
-    // left over in 64 x 64 tiles; what is still left goes to the generic kernel)
+    // left over in edge_dim x edge_dim tiles; what is still left goes to the generic kernel)
     std::vector<reshard::Tile> copy_tiles, fast_transpose_tiles, edge_transpose_tiles, transpose_tiles;
-    int fast_rows = 0, fast_cols = 0;  // tile shape the fast tiles were cut with
+    int fast_rows = 0, fast_cols = 0, edge_dim = 0;  // tile shapes the register-path tiles were cut with
     reshard_plan_info info{};
 
     // device side (created lazily by the first execute)
     int device = -1;
-    void *d_tiles = nullptr;  // copy, fast transposing, 64 x 64 transposing, generic transposing tiles
+    void *d_tiles = nullptr;  // copy, fast transposing, edge transposing, generic transposing tiles
     int num_cus = 0;
     // streaming (created by the first execute_source): the tiles regrouped by source buffer
     struct SrcSlice { uint32_t first[4] = {0, 0, 0, 0}, count[4] = {0, 0, 0, 0}; };

@@ -452,7 +452,7 @@ int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
 }
 
 int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
-              std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
+              int fast_rows, int fast_cols, int edge_dim, std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
               std::vector<Tile> &edge_transpose_tiles, std::vector<Tile> &transpose_tiles) {
     const int tile_bytes = tuning.tile_bytes;
     copy_tiles.clear();
@@ -501,22 +501,24 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
                         transpose_tiles.push_back(t);
                     }
             };
-            const bool reg_path = d.elem_bytes == 2 && (d.src_off | d.dst_off | d.src_stride | d.dst_stride) % 16 == 0;
+            const bool reg_path = (d.src_off | d.dst_off | d.src_stride | d.dst_stride) % 16 == 0 &&
+                                  transpose_shape_ok(d.elem_bytes, fast_rows, fast_cols) &&
+                                  transpose_shape_ok(d.elem_bytes, edge_dim, edge_dim);
             if (!reg_path) {
                 generic_rect(0, d.rows, 0, cols);
                 continue;
             }
-            // interior in big register-transposed tiles; the right and bottom strips in 64 x 64
-            // register-transposed tiles; what is left of those (under 64 wide or high) generic
+            // interior in big register-transposed tiles; the right and bottom strips in small square
+            // register-transposed tiles; what is left of those (under one such square wide or high) generic
             int64_t fi, fk;
-            tile_rect(0, d.rows, 0, cols, tuning.transpose_rows, tuning.transpose_cols, fast_transpose_tiles, fi, fk);
+            tile_rect(0, d.rows, 0, cols, fast_rows, fast_cols, fast_transpose_tiles, fi, fk);
             struct Rect { int64_t i0, i1, k0, k1; };
             const Rect strips[2] = {{0, fi, fk, cols}, {fi, d.rows, 0, cols}};  // right of the interior; below it
             for (const Rect &r : strips) {
                 if (r.i0 >= r.i1 || r.k0 >= r.k1) continue;
                 int64_t ei, ek;
-                tile_rect(r.i0, r.i1, r.k0, r.k1, 64, 64, edge_transpose_tiles, ei, ek);
-                generic_rect(r.i0, r.i0 + ei, r.k0 + ek, r.k1);  // right of the 64 x 64 part
+                tile_rect(r.i0, r.i1, r.k0, r.k1, edge_dim, edge_dim, edge_transpose_tiles, ei, ek);
+                generic_rect(r.i0, r.i0 + ei, r.k0 + ek, r.k1);  // right of the squares
                 generic_rect(r.i0 + ei, r.i1, r.k0, r.k1);       // below it
             }
             continue;

@@ -195,21 +195,50 @@ __global__ __launch_bounds__(256) void repack_transpose_kernel(const Tile *__res
     }
 }
 
-// Full TI x TK tiles of 2-byte elements, dst[k][i] = src[i][k].  Each lane loads an
-// 8 x 8 block (8 rows x 16 bytes, lanes adjacent along the source row), transposes it
-// in registers, and parks the 8 transposed 16-byte rows in LDS; after a barrier the
+// Row c of the transposed VE x VE block of E-byte elements held in r[0..VE) (VE = 16 / E, one
+// 16-byte source row per register quad): element m of the result is element c of r[m].
+template <int E>
+__device__ __forceinline__ u32x4 transposed_row(const u32x4 *r, int c) {
+    u32x4 o;
+    if constexpr (E == 8) {
+        o[0] = r[0][2 * c]; o[1] = r[0][2 * c + 1]; o[2] = r[1][2 * c]; o[3] = r[1][2 * c + 1];
+    } else if constexpr (E == 4) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) o[m] = r[m][c];
+    } else if constexpr (E == 2) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t x = r[2 * m][c >> 1], y = r[2 * m + 1][c >> 1];
+            o[m] = (c & 1) ? ((x >> 16) | (y & 0xFFFF0000u)) : ((x & 0xFFFFu) | (y << 16));
+        }
+    } else {
+        const int sh = 8 * (c & 3);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t b0 = (r[4 * m][c >> 2] >> sh) & 0xFFu, b1 = (r[4 * m + 1][c >> 2] >> sh) & 0xFFu;
+            const uint32_t b2 = (r[4 * m + 2][c >> 2] >> sh) & 0xFFu, b3 = (r[4 * m + 3][c >> 2] >> sh) & 0xFFu;
+            o[m] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+        }
+    }
+    return o;
+}
+
+// Full TI x TK tiles of E-byte elements, dst[k][i] = src[i][k].  With VE = 16 / E, each lane
+// loads a VE x VE block (VE rows x 16 bytes, lanes adjacent along the source row), transposes
+// it in registers, and parks the VE transposed 16-byte rows in LDS; after a barrier the
 // lanes read 16-byte chunks back along destination rows and store them.  Every
 // global and LDS access is 16 bytes wide.  LDS holds the tile as [k][i] with the
-// 16-byte chunks of a row XOR-swizzled by (k / 8) so that neither the writes (lanes
-// 8 rows apart) nor the reads (lanes along a row) pile onto one bank group.
-template <int TI, int TK>
-__global__ __launch_bounds__((TI * TK / 64) < 1024 ? (TI * TK / 64) : 1024)
+// 16-byte chunks of a row XOR-swizzled by (k / VE) so that neither the writes (lanes
+// VE rows apart) nor the reads (lanes along a row) pile onto one bank group.
+template <int E, int TI, int TK>
+__global__ __launch_bounds__((TI * TK * E * E / 256) < 1024 ? (TI * TK * E * E / 256) : 1024)
 void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, PtrTable ptrs, int by_xcd) {
-    constexpr int THREADS = (TI * TK / 64) < 1024 ? (TI * TK / 64) : 1024;
-    constexpr int BLOCKS = TI / 8 * (TK / 8);      // 8 x 8 blocks in a tile
+    constexpr int VE = 16 / E;
+    constexpr int BLOCKS = TI / VE * (TK / VE);    // VE x VE blocks in a tile
+    constexpr int THREADS = BLOCKS < 1024 ? BLOCKS : 1024;
     constexpr int ROUNDS = BLOCKS / THREADS;
-    constexpr int KB = TK / 8, IC = TI / 8;        // blocks along k; 16-byte chunks per LDS row
-    static_assert(BLOCKS % THREADS == 0 && IC >= 8, "tile shape");
+    constexpr int KB = TK / VE, IC = TI / VE;      // blocks along k; 16-byte chunks per LDS row
+    static_assert(BLOCKS % THREADS == 0 && THREADS % 64 == 0 && IC >= 8 && TI * TK * E <= 128 * 1024, "tile shape");
     __shared__ u32x4 lds[TK * IC];
     const uint32_t ti = tile_of_workgroup(blockIdx.x, ntiles, by_xcd != 0);
     if (ti >= ntiles) return;  // uniform for the workgroup: nobody reaches the barrier below
@@ -217,35 +246,28 @@ void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, 
     const char *s = ptrs.p[t.src_buf] + t.src_off;
     char *d = ptrs.p[t.dst_buf] + t.dst_off;
     const uint32_t tid = threadIdx.x;
-    u32x4 r[ROUNDS][8];
+    u32x4 r[ROUNDS][VE];
 #pragma unroll
     for (int q = 0; q < ROUNDS; ++q) {
         const uint32_t b = tid + q * THREADS, kb = b % KB, ib = b / KB;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            r[q][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(s + uint64_t(ib * 8 + j) * t.src_stride + kb * 16));
+        for (int j = 0; j < VE; ++j)
+            r[q][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(s + uint64_t(ib * VE + j) * t.src_stride + kb * 16));
     }
 #pragma unroll
     for (int q = 0; q < ROUNDS; ++q) {
         const uint32_t b = tid + q * THREADS, kb = b % KB, ib = b / KB;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            // transposed row c of the block: elements (i0..i0+7, k0+c)
-            u32x4 o;
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const uint32_t x = r[q][2 * m][c >> 1], y = r[q][2 * m + 1][c >> 1];
-                o[m] = (c & 1) ? ((x >> 16) | (y & 0xFFFF0000u)) : ((x & 0xFFFFu) | (y << 16));
-            }
-            const uint32_t k = kb * 8 + c;
-            lds[k * IC + (ib ^ (kb & 7))] = o;     // (k >> 3) == kb
+        for (int c = 0; c < VE; ++c) {
+            const uint32_t k = kb * VE + c;        // (k / VE) == kb
+            lds[k * IC + (ib ^ (kb & 7))] = transposed_row<E>(r[q], c);
         }
     }
     __syncthreads();
 #pragma unroll
-    for (int q = 0; q < ROUNDS * 8; ++q) {
+    for (int q = 0; q < ROUNDS * VE; ++q) {
         const uint32_t u = tid + q * THREADS, ic = u % IC, k = u / IC;
-        const u32x4 v = lds[k * IC + (ic ^ ((k >> 3) & 7))];
+        const u32x4 v = lds[k * IC + (ic ^ ((k / VE) & 7))];
         __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d + uint64_t(k) * t.dst_stride + ic * 16));
     }
 }
@@ -395,22 +417,33 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, int cls, const Tile
             if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
         }
     } else if (cls == 1 || cls == 2) {
-        const int rows = cls == 1 ? plan->fast_rows : 64, cols = cls == 1 ? plan->fast_cols : 64;
-        const int shape = rows * 1000 + cols;
-        const uint32_t threads = uint32_t(std::min(rows * cols / 64, 1024));
+        const int rows = cls == 1 ? plan->fast_rows : plan->edge_dim, cols = cls == 1 ? plan->fast_cols : plan->edge_dim;
+        const int E = plan->spec.elem_bytes;
+        if (!transpose_shape_ok(E, rows, cols)) return fail(RESHARD_ERR_INVALID_ARG, "unsupported transposing tile shape");
+        const int shape = (E * 1000 + rows) * 1000 + cols;
+        const uint32_t threads = uint32_t(std::min(rows * cols * E * E / 256, 1024));
         const uint32_t per_launch = (0xFFFFFFFFu / threads) & ~7u;
         for (uint32_t first = 0; first < n; first += per_launch) {
             const Tile *ft = t + first;
             const uint32_t m = std::min(per_launch, n - first);
             const dim3 grid(by_xcd ? (m + 7) / 8 * 8 : m), block(threads);
-#define RESHARD_T16(TI, TK)                                                                                  \
-    case TI * 1000 + TK:                                                                                     \
-        hipLaunchKernelGGL((repack_transpose16_kernel<TI, TK>), grid, block, 0, stream, ft, m, pt, by_xcd);  \
+#define RESHARD_T16(E, TI, TK)                                                                                 \
+    case (E * 1000 + TI) * 1000 + TK:                                                                          \
+        static_assert(transpose_shape_ok(E, TI, TK), "shape");                                                 \
+        hipLaunchKernelGGL((repack_transpose16_kernel<E, TI, TK>), grid, block, 0, stream, ft, m, pt, by_xcd); \
         break;
             switch (shape) {
-                RESHARD_T16(64, 64) RESHARD_T16(64, 128) RESHARD_T16(64, 256)
-                RESHARD_T16(128, 64) RESHARD_T16(128, 128) RESHARD_T16(128, 256)
-                RESHARD_T16(256, 64) RESHARD_T16(256, 128) RESHARD_T16(256, 256)
+                RESHARD_T16(1, 128, 128) RESHARD_T16(1, 128, 256) RESHARD_T16(1, 128, 512)
+                RESHARD_T16(1, 256, 128) RESHARD_T16(1, 256, 256) RESHARD_T16(1, 256, 512)
+                RESHARD_T16(1, 512, 128) RESHARD_T16(1, 512, 256)
+                RESHARD_T16(2, 64, 64) RESHARD_T16(2, 64, 128) RESHARD_T16(2, 64, 256)
+                RESHARD_T16(2, 128, 64) RESHARD_T16(2, 128, 128) RESHARD_T16(2, 128, 256)
+                RESHARD_T16(2, 256, 64) RESHARD_T16(2, 256, 128) RESHARD_T16(2, 256, 256)
+                RESHARD_T16(4, 64, 64) RESHARD_T16(4, 64, 128) RESHARD_T16(4, 64, 256)
+                RESHARD_T16(4, 128, 64) RESHARD_T16(4, 128, 128) RESHARD_T16(4, 128, 256)
+                RESHARD_T16(4, 256, 64) RESHARD_T16(4, 256, 128)
+                RESHARD_T16(8, 64, 64) RESHARD_T16(8, 64, 128) RESHARD_T16(8, 64, 256)
+                RESHARD_T16(8, 128, 64) RESHARD_T16(8, 128, 128) RESHARD_T16(8, 256, 64)
                 default: return fail(RESHARD_ERR_INVALID_ARG, "unsupported transposing tile shape");
             }
 #undef RESHARD_T16
@@ -528,8 +561,8 @@ extern "C" int reshard_set_tuning(const reshard_tuning *t) {
             n.unroll = u;
         }
         for (int v : {t->transpose_rows, t->transpose_cols})
-            if (v != 0 && v != 64 && v != 128 && v != 256)
-                return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128 or 256");
+            if (v != 0 && v != 64 && v != 128 && v != 256 && v != 512)
+                return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 256 or 512");
         if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
         if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
         if (t->flags < -1 || t->flags > 15) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 15]");

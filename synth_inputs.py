@@ -143,6 +143,14 @@ TINY = {
         make_layout(kind="train", tp=1, pp=1, ep=2, expert_layout="grouped"),
         make_layout(kind="gen", tp=2, ep=1),
         2004, "mid-size MoE, grouped experts (transposing), EP2 -> TP2 EP1"),
+    # The same with matrices that hold several of the largest transposing tiles (512 long) and
+    # ragged strips of every kind; all rows are multiples of 16 bytes at every element size.
+    "big_moe_grouped": _wl(
+        "big_moe_grouped",
+        make_spec(family="moe_gqa", L=1, H=1232, nq=4, nkv=2, d=16, V=64, E=2, Ie=464),
+        make_layout(kind="train", tp=1, pp=1, ep=2, expert_layout="grouped"),
+        make_layout(kind="gen", tp=1, ep=1),
+        2010, "grouped experts (transposing) with 1232 x 464 and 464 x 1232 matrices, EP2 -> EP1"),
     # KV-head replication: 2 KV heads on 4 tensor ranks (training) and 8 (the way back is
     # exercised by the round-trip tests), interleaved pipeline chunks, tied embeddings.
     "tiny_kvrep": _wl(

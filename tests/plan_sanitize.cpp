@@ -37,7 +37,9 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
     int rc = build_side(s, a, true, S);
     if (!rc) rc = build_side(s, b, false, D);
     if (!rc) rc = compile_descriptors(s, S, D, descs);
-    if (!rc) rc = cut_tiles(descs, int(S.buf_bytes.size()), tn, c, f, e, g);
+    int fr = tn.transpose_rows, fc = tn.transpose_cols;
+    if (!transpose_shape_ok(s.elem_bytes, fr, fc)) transpose_default_shape(s.elem_bytes, fr, fc);
+    if (!rc) rc = cut_tiles(descs, int(S.buf_bytes.size()), tn, fr, fc, transpose_edge_dim(s.elem_bytes), c, f, e, g);
     if ((rc == 0) != expect_ok) {
         std::printf("unexpected result %d (expected %s)\n", rc, expect_ok ? "ok" : "an error");
         return 1;

@@ -97,21 +97,36 @@ def test_every_launch_shape_gives_the_same_bits(tuning):
         set_tuning()
 
 
-@pytest.mark.parametrize("shape", [(64, 64), (64, 128), (64, 256), (128, 64), (128, 128), (128, 256),
-                                   (256, 64), (256, 128), (256, 256)])
-def test_register_transpose_tile_shapes(shape):
-    """Grouped (transposing) experts at a size with full tiles and ragged edges, every tile shape;
-    plus a shape whose expert dimensions are exact multiples of every tile shape."""
-    print("transpose shape", shape, flush=True)
+def _transpose_shapes():
+    """Every (element size, tile shape) the register-transpose kernel is built for."""
+    out = []
+    for eb in (2, 1, 4, 8):
+        for ti in (64, 128, 256, 512):
+            for tk in (64, 128, 256, 512):
+                fits = ti * tk * eb <= 131072
+                if fits and ((ti >= 128 and tk >= 128) if eb == 1 else max(ti, tk) <= 256):
+                    out.append((eb, ti, tk))
+    return out
+
+
+@pytest.mark.parametrize("eb,ti,tk", _transpose_shapes())
+def test_register_transpose_tile_shapes(eb, ti, tk):
+    """Grouped (transposing) experts at sizes with full tiles and ragged edges, every element size
+    and tile shape; plus a shape whose expert dimensions are exact multiples of every tile shape."""
+    print("transpose shape", eb, ti, tk, flush=True)
     exact = dict(TINY["mid_moe_grouped"])
     exact["spec"] = dict(exact["spec"], H=512, Ie=256)
     try:
-        set_tuning(transpose_rows=shape[0], transpose_cols=shape[1])
-        for wl in (TINY["mid_moe_grouped"], exact):
+        set_tuning(transpose_rows=ti, transpose_cols=tk)
+        for wl in (TINY["mid_moe_grouped"], TINY["big_moe_grouped"], exact):
+            wl = with_eb(wl, eb)
             plan, _, _ = run_case(wl, "raw16")
             # way back: generation [out][in] -> grouped [in][out] is a transpose as well
             gen = dict(wl["dst"])
             run_case(wl, "raw16", gen, wl["src"])
+            classes = {t["tile_class"] for t in plan.tiles()}
+            if wl["name"] == "big_moe_grouped":
+                assert 1 in classes and 3 in classes, "full tiles and ragged strips both present"
         assert plan.info()["num_transpose_tiles"] > 0
     finally:
         set_tuning()

@@ -68,15 +68,31 @@ def run_tiles(tiles, src, dst, counts):
 
 TILE_TUNINGS = [dict(), dict(tile_bytes=4096, transpose_rows=64, transpose_cols=128),
                 dict(tile_bytes=8192, transpose_rows=128, transpose_cols=64), dict(transpose_rows=64, transpose_cols=64)]
+TILE_CASES = [(n, 2, t) for n in ["tiny_dense", "tiny_moe_grouped", "mid_moe_grouped", "tiny_kvrep", "tiny_vocabpad",
+                                  "tiny_etp", "C0"] for t in TILE_TUNINGS]
+# transposing tiles at the other element sizes: the default shape of each, and the longest tiles
+TILE_CASES += [("big_moe_grouped", eb, t) for eb, t in [
+    (1, dict()), (1, dict(transpose_rows=512, transpose_cols=256)), (1, dict(transpose_rows=128, transpose_cols=512)),
+    (2, dict()), (4, dict()), (4, dict(transpose_rows=256, transpose_cols=64)), (8, dict()),
+    (8, dict(transpose_rows=64, transpose_cols=256))]]
+TILE_CASES += [("mid_moe_grouped", eb, dict()) for eb in (1, 4, 8)]
 
 
-@pytest.mark.parametrize("tuning", TILE_TUNINGS)
-@pytest.mark.parametrize("name", ["tiny_dense", "tiny_moe_grouped", "mid_moe_grouped", "tiny_kvrep", "tiny_vocabpad", "tiny_etp", "C0"])
-def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, tuning):
+def transpose_shape(eb, tuning):
+    """Tile shape the library documents for an element size: the tuning's if it fits 128 KiB
+    (and is one it builds), else the default of that size."""
+    default = {1: (512, 256), 2: (256, 256), 4: (128, 256), 8: (128, 128)}[eb]
+    ti, tk = tuning.get("transpose_rows", 0), tuning.get("transpose_cols", 0)
+    ok = ti and tk and ti * tk * eb <= 131072 and (ti >= 128 and tk >= 128 if eb == 1 else max(ti, tk) <= 256)
+    return (ti, tk) if ok else default
+
+
+@pytest.mark.parametrize("name,eb,tuning", TILE_CASES)
+def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, eb, tuning):
     """The cut into device tiles (rows per tile, runs of long rows, vector width, the three
     levels of transposing tiles) moves exactly what the descriptors say."""
     w = {**TINY, **WORKLOADS}[name]
-    spec = w["spec"]
+    spec = with_eb(w["spec"], eb)
     try:
         set_tuning(**tuning)
         plan = Plan(spec, w["src"], w["dst"])
@@ -98,11 +114,12 @@ def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, tunin
         for off, nb in D.owned(b):
             owned[off:off + nb] = True
         assert np.all(cnt[b][owned] == 1) and np.all(cnt[b][~owned] == 0)
+    shape, edge = transpose_shape(eb, tuning), (128 if eb == 1 else 64)
     for t in tiles:
         units = t["rows"] * t["row_units"]
-        assert 1 <= units <= 32768 and t["vec_bytes"] in (1, 2, 4, 8, 16)
+        assert units >= 1 and t["vec_bytes"] in (1, 2, 4, 8, 16)
         if t["kind"] == 0:
-            assert t["tile_class"] == 0
+            assert t["tile_class"] == 0 and units <= 32768
             assert (t["src_off"] | t["dst_off"]) % t["vec_bytes"] == 0
             if t["rows"] > 1:
                 assert (t["src_stride"] | t["dst_stride"]) % t["vec_bytes"] == 0
@@ -110,11 +127,13 @@ def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, tunin
             assert t["tile_class"] in (1, 2, 3)
             if t["tile_class"] in (1, 2):  # register path: full tiles, 16-byte accesses
                 assert (t["src_off"] | t["dst_off"] | t["src_stride"] | t["dst_stride"]) % 16 == 0
-                assert t["rows"] % 64 == 0 and t["row_units"] % 64 == 0
-    if name == "mid_moe_grouped":  # every level of the transposing cut is exercised
-        shape = (tuning.get("transpose_rows", 256), tuning.get("transpose_cols", 256))
+                assert (t["rows"], t["row_units"]) == (shape if t["tile_class"] == 1 else (edge, edge))
+                assert t["vec_bytes"] == eb
+    if name == "mid_moe_grouped" and eb == 2:  # every level of the transposing cut is exercised
         want_classes = {(256, 256): {0, 2, 3}, (64, 64): {0, 1, 3}}.get(shape, {0, 1, 2, 3})
         assert {t["tile_class"] for t in tiles} == want_classes
+    if name == "big_moe_grouped":
+        assert {t["tile_class"] for t in tiles} == ({0, 1, 3} if shape == (edge, edge) else {0, 1, 2, 3})
 
 
 CASES = [(n, eb) for n in sorted(TINY) for eb in (1, 2, 4, 8)]
@@ -407,8 +426,8 @@ def test_state_machine_errors_without_a_device():
 def test_tuning_is_validated():
     set_tuning()
     base = get_tuning()
-    assert base == dict(tile_bytes=65536, block_threads=1024, blocks_per_cu=0, unroll=8, flags=15, transpose_rows=256,
-                        transpose_cols=256)
+    assert base == dict(tile_bytes=65536, block_threads=1024, blocks_per_cu=0, unroll=8, flags=15, transpose_rows=0,
+                        transpose_cols=0)
     set_tuning(tile_bytes=16384, unroll=4)
     assert get_tuning()["tile_bytes"] == 16384 and get_tuning()["unroll"] == 4
     w = WORKLOADS["C1"]
