@@ -428,10 +428,14 @@ extern "C" int reshard_swap_out(reshard_plan *p, void *stream) {
     if (int rc = ensure_host_copies(p)) return rc;
     if (int rc = ensure_swap_objects(p)) return rc;
     if (int rc = order_after(p, stream)) return rc;
-    for (size_t i = 0; i < p->src_ptrs.size(); ++i)
-        if (p->src.used[i])
-            if (int rc = queue_copy(p, i, true)) return rc;
-    set_all(p, RESHARD_SRC_SWAPPING_OUT);
+    // states change buffer by buffer, so that after a failure half way the copies already
+    // queued are still waited for (the plan is then MIXED; reshard_swap_wait settles it)
+    for (size_t i = 0; i < p->src_ptrs.size(); ++i) {
+        if (!p->src.used[i]) continue;
+        if (int rc = queue_copy(p, i, true)) { recompute(p); return rc; }
+        p->buf_state[i] = RESHARD_SRC_SWAPPING_OUT;
+    }
+    recompute(p);
     return RESHARD_OK;
 }
 
@@ -460,13 +464,14 @@ extern "C" int reshard_swap_in(reshard_plan *p, void *stream) {
     size_t last = 0;
     for (size_t i = 0; i < p->src_ptrs.size(); ++i) {
         if (!p->src.used[i]) continue;
-        if (int rc = queue_copy(p, i, false)) return rc;
+        if (int rc = queue_copy(p, i, false)) { recompute(p); return rc; }
+        p->buf_state[i] = RESHARD_SRC_SWAPPING_IN;
         last = i;
     }
+    recompute(p);
     // the copies run in buffer order, so the last buffer's event marks the end of all of them
     if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(p->ev_buf[last]), 0))
         return hip_fail(e, "hipStreamWaitEvent");
-    set_all(p, RESHARD_SRC_SWAPPING_IN);
     return RESHARD_OK;
 }
 

@@ -194,6 +194,74 @@ TINY = {
 }
 
 
+def random_case(seed: int) -> dict:
+    """A small random workload that the shape rules allow (divisibility only: no layout
+    arithmetic): family, sizes, both layouts and every layout option drawn from `seed`."""
+    import math
+    import random
+
+    r = random.Random(seed)
+    family = r.choice(["dense_gqa", "dense_gqa", "moe_gqa", "moe_gqa", "moe_mla"])
+    moe = family != "dense_gqa"
+    dst_train = r.random() < 0.2
+    tp_s, tp_d = r.choice([1, 2, 4]), r.choice([1, 2, 4, 8])
+    m = math.lcm(tp_s, tp_d)
+    nkv = r.choice([1, 2, 4, 8])
+    # heads: nq a multiple of both degrees and of nkv
+    g = m // math.gcd(m, nkv) * r.choice([1, 2])
+    nq = nkv * g if family != "moe_mla" else m * r.choice([1, 2])
+    pp_s = r.choice([1, 1, 2, 4])
+    pp_d = r.choice([1, 2]) if dst_train else 1
+    src = dict(kind="train", tp=tp_s, pp=pp_s)
+    dst = dict(kind="train" if dst_train else "gen", tp=tp_d, pp=pp_d)
+    L = pp_s * pp_d * r.choice([1, 2])
+    if pp_s >= 2 and r.random() < 0.3:  # uneven stages
+        first, last = r.choice([1, 2, 3]), r.choice([1, 2])
+        mid = (pp_s - 2) * r.choice([1, 2])
+        L = (first + mid + last) * (2 if pp_d == 2 and (first + mid + last) % 2 else 1)
+        if L != first + mid + last:  # keep the sum exact: fold the doubling into the stage sizes
+            first, mid, last = 2 * first, 2 * mid, 2 * last
+        src.update(first_stage_layers=first, last_stage_layers=last)
+    elif r.random() < 0.4:
+        src["vpp"] = 2
+        L *= 2
+    spec = dict(family=family, L=L, H=8 * r.choice([2, 3, 5, 8]), nq=nq, elem_bytes=r.choice([1, 2, 2, 4, 8]))
+    if family != "moe_mla":
+        spec.update(nkv=nkv, d=r.choice([4, 8, 16]), qkv_bias=r.choice([0, 1]))
+    else:
+        spec.update(q_lora=r.choice([8, 24]), kv_lora=r.choice([8, 16]), nope=r.choice([4, 8]), rope=r.choice([4, 8]),
+                    v_dim=r.choice([4, 8]))
+    if family == "dense_gqa":
+        spec["I"] = m * r.choice([3, 5, 8])
+    else:
+        E = r.choice([2, 4, 8])
+        spec.update(E=E, Ie=m * r.choice([1, 3, 4]), n_shared=r.choice([0, 1, 2]))
+        src["ep"] = r.choice([x for x in (1, 2, 4, 8) if E % x == 0])
+        dst["ep"] = r.choice([x for x in (1, 2, 4, 8) if E % x == 0])
+        src["expert_layout"] = r.choice(["per_expert", "grouped"])
+        if dst_train:
+            dst["expert_layout"] = r.choice(["per_expert", "grouped"])
+        if r.random() < 0.3:
+            src["etp"] = tp_s
+        if r.random() < 0.3:
+            dst["etp"] = tp_d
+    if r.random() < 0.8:
+        V = r.choice([40, 50, 64, 96])
+        spec.update(V=V, has_embeddings=1, tied_embeddings=r.choice([0, 0, 1]))
+        for lay in (src, dst):
+            pad = -V % lay["tp"]
+            if pad or r.random() < 0.3:
+                lay["vocab_padded"] = V + pad + lay["tp"] * r.choice([0, 1, 3])
+    else:
+        spec.update(V=0, has_embeddings=0)
+    if r.random() < 0.25 and tp_d > 1:
+        dst["tp_filter"] = r.randrange(tp_d)
+    if r.random() < 0.25 and dst.get("ep", 1) > 1:
+        dst["ep_filter"] = r.randrange(dst["ep"])
+    return _wl("random_%d" % seed, make_spec(**spec), make_layout(**src), make_layout(**dst), 3000 + seed,
+               "random small workload")
+
+
 def fill_buffer(nbytes: int, seed: int, device="cpu", mode: str = "normal") -> torch.Tensor:
     """A flat int16 tensor of nbytes/2 words filled from `seed`.
 

@@ -8,7 +8,7 @@ import torch
 import gpu_util as G
 from oracle import fast, locate
 from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, get_tuning, set_tuning
-from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout, make_spec
+from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout, make_spec, random_case
 
 pytestmark = pytest.mark.gpu
 
@@ -39,6 +39,15 @@ def run_case(wl, mode="normal", src_lay=None, dst_lay=None, threads=16):
 def test_tiny_models_all_element_sizes(name, eb):
     print("case", name, eb, flush=True)
     run_case(with_eb(TINY[name], eb), mode="raw16")
+
+
+@pytest.mark.parametrize("first", range(0, 160, 20))
+def test_random_small_workloads(first):
+    """Random shapes, degrees and layout options (the cases the CPU tests hold against the
+    numpy constructions), twenty per test."""
+    for seed in range(first, first + 20):
+        print("case random", seed, flush=True)
+        run_case(random_case(seed), mode="raw16", threads=2)
 
 
 @pytest.mark.parametrize("mode", ["normal", "raw16"])
