@@ -225,18 +225,27 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         in_flight = []  # (index, tensor): at most two source buffers are resident at any time
+        host_ms = {"alloc": 0.0, "execute": 0.0, "swap_queue": 0.0, "wait": 0.0}
+        clock = time.perf_counter
         for i, (n, u) in enumerate(zip(sizes_s, used_s)):
             if not u:
                 continue
+            c0 = clock()
             buf = torch.empty(n // 2, dtype=torch.int16, device="cuda")
+            c1 = clock()
             splan.execute_source(i, buf.data_ptr(), ptrs(dst), h)
+            c2 = clock()
             splan.swap_out_source(i, h)      # its copy runs while the next buffer is repacked
+            c3 = clock()
             in_flight.append((i, buf))
             if len(in_flight) == 2:
                 j, old = in_flight.pop(0)
                 splan.swap_wait_buffer(j)
                 splan.mark_src_buffer_released(j)
                 del old
+            c4 = clock()
+            for k, v in zip(host_ms, (c1 - c0, c2 - c1, c3 - c2, c4 - c3)):
+                host_ms[k] += v * 1e3
         for j, old in in_flight:
             splan.swap_wait_buffer(j)
             splan.mark_src_buffer_released(j)
@@ -247,7 +256,7 @@ def main():
         streaming = {"total_ms": round((t1 - t0) * 1e3, 2), "ledger_peak_device": sst["peak_device"],
                      "torch_peak_allocated": torch.cuda.max_memory_allocated(), "dst_bytes": sst["dst_live"],
                      "largest_src_buffer": max(n for n, u in zip(sizes_s, used_s) if u), "buffers_in_flight": 2,
-                     "state": sst["state"],
+                     "host_ms": {k: round(v, 1) for k, v in host_ms.items()}, "state": sst["state"],
                      "one_shot_peak_device": plan.mem_stats()["peak_device"], "allocated_before": base}
         src = alloc_src(False)  # a device home again, and the weights back, so the rest of the run goes on
         splan.bind_src(ptrs(src))
