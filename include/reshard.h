@@ -330,6 +330,13 @@ int reshard_execute_source(reshard_plan *plan, int src_index, const void *src_pt
  * used buffer is RELEASED the plan is RELEASED and continues with reshard_bind_src / reshard_swap_in. */
 int reshard_swap_out_source(reshard_plan *plan, int src_index, void *stream);
 int reshard_mark_src_buffer_released(reshard_plan *plan, int src_index);
+/* Per-buffer swap-in (the host-to-device copy "in advance", one buffer at a time, so the trainer's
+ * memory can come back stage by stage): the buffer must be ON_HOST or RELEASED.  `src_ptr` is its
+ * new device home (256-byte aligned); NULL keeps the pointer still bound (ON_HOST only).  The copy
+ * is ordered after work already queued on `stream`, and `stream` waits for it; the buffer becomes
+ * SWAPPING_IN (complete it with reshard_swap_wait_buffer(host_wait = 1) or reshard_swap_wait).
+ * Errors: INVALID_ARG, BAD_STATE, HIP. */
+int reshard_swap_in_source(reshard_plan *plan, int src_index, void *src_ptr, void *stream);
 /* RESHARD_SRC_* of one source buffer (negative = error). */
 int reshard_src_buffer_state(const reshard_plan *plan, int src_index);
 

@@ -116,6 +116,7 @@ def lib():
             "reshard_swap_wait_buffer": (C.c_int, [P, C.c_int, P, C.c_int]),
             "reshard_mark_src_released": (C.c_int, [P]),
             "reshard_mark_dst_released": (C.c_int, [P]),
+            "reshard_swap_in_source": (C.c_int, [P, C.c_int, C.c_void_p, C.c_void_p]),
             "reshard_reserve_host": (C.c_int, [P]),
             "reshard_release_host": (C.c_int, [P]),
             "reshard_host_copy": (P, [P, C.c_int]),
@@ -137,7 +138,7 @@ EXPORTS = (
     "reshard_plan_class_bytes", "reshard_redundant_memory_bytes",
     "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_execute_source",
     "reshard_swap_out_source", "reshard_mark_src_buffer_released", "reshard_src_buffer_state", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
-    "reshard_swap_wait", "reshard_swap_wait_buffer", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_reserve_host", "reshard_release_host",
+    "reshard_swap_wait", "reshard_swap_wait_buffer", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_swap_in_source", "reshard_reserve_host", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
 )
 
@@ -317,6 +318,9 @@ class Plan:
 
     def mark_dst_released(self) -> None:
         _check(lib().reshard_mark_dst_released(self._h))
+
+    def swap_in_source(self, src_index: int, src_ptr: int = 0, stream: int = 0) -> None:
+        _check(lib().reshard_swap_in_source(self._h, src_index, C.c_void_p(src_ptr or None), C.c_void_p(stream)))
 
     def reserve_host(self) -> None:
         _check(lib().reshard_reserve_host(self._h))

@@ -475,6 +475,29 @@ extern "C" int reshard_swap_in(reshard_plan *p, void *stream) {
     return RESHARD_OK;
 }
 
+extern "C" int reshard_swap_in_source(reshard_plan *p, int src_index, void *src_ptr, void *stream) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    if (src_index < 0 || src_index >= int(p->src.buf_bytes.size()) || !p->src.used[size_t(src_index)])
+        return fail(RESHARD_ERR_INVALID_ARG, "src_index does not name a used source buffer");
+    const size_t i = size_t(src_index);
+    const int st = p->buf_state[i];
+    if (st != RESHARD_SRC_ON_HOST && st != RESHARD_SRC_RELEASED)
+        return fail(RESHARD_ERR_BAD_STATE, "this source buffer has no completed swap-out to bring back");
+    if (reinterpret_cast<uintptr_t>(src_ptr) % 256) return fail(RESHARD_ERR_INVALID_ARG, "src_ptr is not 256-byte aligned");
+    if (!src_ptr && !p->src_ptrs[i])
+        return fail(RESHARD_ERR_BAD_STATE, "the device copy was released: give the buffer's new device pointer");
+    if (int rc = ensure_swap_objects(p)) return rc;
+    if (int rc = order_after(p, stream)) return rc;
+    if (src_ptr) p->src_ptrs[i] = src_ptr;
+    p->buf_state[i] = RESHARD_SRC_ON_HOST;
+    if (int rc = queue_copy(p, i, false)) { recompute(p); return rc; }
+    p->buf_state[i] = RESHARD_SRC_SWAPPING_IN;
+    recompute(p);
+    if (hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(p->ev_buf[i]), 0))
+        return hip_fail(e, "hipStreamWaitEvent");
+    return RESHARD_OK;
+}
+
 extern "C" int reshard_swap_wait_buffer(reshard_plan *p, int index, void *stream, int host_wait) {
     if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
     if (index < 0 || index >= int(p->src.buf_bytes.size()) || !p->src.used[size_t(index)])

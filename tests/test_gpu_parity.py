@@ -271,6 +271,34 @@ def test_streaming_one_source_buffer_at_a_time(name):
     torch.cuda.synchronize()
     for i in order:
         assert np.array_equal(fresh[i].cpu().numpy(), keep[i])
+    # the same way back one buffer at a time: out again, released, then each buffer to a new home
+    plan.swap_out(h)
+    plan.swap_wait()
+    plan.mark_src_released()
+    del fresh
+    with pytest.raises(ReshardError) as e:
+        plan.swap_in_source(order[0], 0, h)  # released: a new device pointer is needed
+    assert e.value.code == binding.ERR_BAD_STATE
+    homes = {}
+    for n, i in enumerate(order):
+        homes[i] = torch.zeros(sizes[i] // 2, dtype=torch.int16, device="cuda")
+        plan.swap_in_source(i, homes[i].data_ptr(), h)
+        assert plan.src_buffer_state(i) == "swapping_in"
+        with pytest.raises(ReshardError) as e:
+            plan.swap_in_source(i, homes[i].data_ptr(), h)  # already on its way
+        assert e.value.code == binding.ERR_BAD_STATE
+        assert plan.mem_stats()["src_live"] == sum(sizes[j] for j in order[:n + 1])
+        # the caller's stream waits for the copy: work queued on it now sees the weights
+        assert np.array_equal(homes[i].cpu().numpy(), keep[i])
+        plan.swap_wait_buffer(i)
+        assert plan.src_buffer_state(i) == "resident"
+        assert plan.mem_stats()["state"] == ("resident" if n == len(order) - 1 else "mixed")
+    # and the plan carries on as after an ordinary swap-in
+    again = G.device_destinations(plan)
+    plan.execute(G.ptrs([homes.get(i) for i in range(len(sizes))]), G.ptrs(again), h)
+    torch.cuda.synchronize()
+    for a, b in zip(dst, again):
+        assert (a is None and b is None) or torch.equal(a, b)
 
 
 @pytest.mark.parametrize("name", ["C1", "C3"])

@@ -9,6 +9,7 @@ tests only and is not a product path.
 import ctypes as C
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -417,6 +418,12 @@ def test_state_machine_errors_without_a_device():
         plan.swap_wait_buffer(0)
     assert e.value.code == binding.ERR_BAD_STATE
     with pytest.raises(ReshardError) as e:
+        plan.swap_in_source(0, 256)  # nothing was swapped out
+    assert e.value.code == binding.ERR_BAD_STATE
+    with pytest.raises(ReshardError) as e:
+        plan.swap_in_source(9, 256)
+    assert e.value.code == binding.ERR_INVALID_ARG
+    with pytest.raises(ReshardError) as e:
         plan.swap_wait_buffer(7)
     assert e.value.code == binding.ERR_INVALID_ARG
     plan.release_host()
@@ -448,3 +455,39 @@ def test_library_exports_every_symbol_the_header_declares():
     l = binding.lib()
     for name in sorted(declared):
         assert getattr(l, name) is not None
+
+
+def test_a_plain_c_client_sees_what_the_binding_sees(tmp_path):
+    """reshard.h is C99, and a C program that uses nothing but the header gets the same
+    answers as the ctypes binding (host-side calls only)."""
+    libdir = os.path.join(ROOT, "paper_2507_19017_amd")
+    exe = str(tmp_path / "c_abi_client")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I" + os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "c_abi_client.c"), "-o", exe, "-L" + libdir, "-l:libreshard.so",
+                           "-Wl,-rpath," + libdir])
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
+    got = {}
+    for line in out.splitlines():
+        k, *v = line.split()
+        got.setdefault(k, []).append(v)
+    w = WORKLOADS["C0"]
+    plan = Plan(w["spec"], w["src"], w["dst"])
+    info = plan.info()
+    assert got["create_null_out"] == [[str(binding.ERR_INVALID_ARG), "1"]]
+    assert got["create_tp3"] == [[str(binding.ERR_UNSUPPORTED), "1"]]
+    assert got["create_bad_size"] == [[str(binding.ERR_INVALID_ARG)]]
+    assert got["create"] == [["0"]] and got["destroy"] == [["0"]]
+    assert got["num_bufs"] == [["0", "2"], ["1", "1"]]
+    want_bufs = [[str(s), str(b), str(n), str(int(u))] for s in (0, 1)
+                 for b, (n, u) in enumerate(zip(plan.buf_bytes(s), plan.buf_used(s)))]
+    assert got["buf"] == want_bufs
+    assert got["info"] == [["0", str(info["num_descs"]), str(info["num_tiles"]), str(info["bytes_moved"])]]
+    d0 = plan.descs()[0]
+    assert got["desc0"] == [["0"] + [str(d0[k]) for k in ("src_buf", "dst_buf", "src_off", "dst_off", "rows", "row_bytes")]]
+    assert got["desc_out_of_range"] == [[str(binding.ERR_INVALID_ARG)]]
+    assert got["class_bytes"] == [["0"] + [str(plan.class_bytes(1)[k]) for k in "TEC"]]
+    assert got["mem_stats"] == [["0", "0", "0", "0"]]
+    assert got["swap_out_unbound"] == [[str(binding.ERR_BAD_STATE)]] and got["swap_in_unbound"] == [[str(binding.ERR_BAD_STATE)]]
+    assert got["tensors"] == [[str(len(plan.tensors(1)))]]
+    assert got["eq3"] == [["8000000000.0"]]  # 2 * (8e9 / 4 + 4e9 / 2)
+    assert got["version"][0][0] == "reshard"
