@@ -194,13 +194,15 @@ TINY = {
 }
 
 
-def random_case(seed: int) -> dict:
+def random_case(seed: int, scale: int = 1) -> dict:
     """A small random workload that the shape rules allow (divisibility only: no layout
-    arithmetic): family, sizes, both layouts and every layout option drawn from `seed`."""
+    arithmetic): family, sizes, both layouts and every layout option drawn from `seed`.
+    `scale` multiplies the widths (hidden size, head size, feed-forward widths, vocabulary):
+    1 gives kilobyte tensors, 8 to 16 tensors of many tiles with ragged ends."""
     import math
     import random
 
-    r = random.Random(seed)
+    r = random.Random(seed * 1000 + scale)
     family = r.choice(["dense_gqa", "dense_gqa", "moe_gqa", "moe_gqa", "moe_mla"])
     moe = family != "dense_gqa"
     dst_train = r.random() < 0.2
@@ -225,17 +227,17 @@ def random_case(seed: int) -> dict:
     elif r.random() < 0.4:
         src["vpp"] = 2
         L *= 2
-    spec = dict(family=family, L=L, H=8 * r.choice([2, 3, 5, 8]), nq=nq, elem_bytes=r.choice([1, 2, 2, 4, 8]))
+    spec = dict(family=family, L=L, H=8 * r.choice([2, 3, 5, 8]) * scale, nq=nq, elem_bytes=r.choice([1, 2, 2, 4, 8]))
     if family != "moe_mla":
-        spec.update(nkv=nkv, d=r.choice([4, 8, 16]), qkv_bias=r.choice([0, 1]))
+        spec.update(nkv=nkv, d=r.choice([4, 8, 16]) * min(scale, 8), qkv_bias=r.choice([0, 1]))
     else:
-        spec.update(q_lora=r.choice([8, 24]), kv_lora=r.choice([8, 16]), nope=r.choice([4, 8]), rope=r.choice([4, 8]),
-                    v_dim=r.choice([4, 8]))
+        spec.update(q_lora=r.choice([8, 24]) * scale, kv_lora=r.choice([8, 16]) * scale, nope=r.choice([4, 8]) * min(scale, 8),
+                    rope=r.choice([4, 8]) * min(scale, 8), v_dim=r.choice([4, 8]) * min(scale, 8))
     if family == "dense_gqa":
-        spec["I"] = m * r.choice([3, 5, 8])
+        spec["I"] = m * r.choice([3, 5, 8]) * scale
     else:
         E = r.choice([2, 4, 8])
-        spec.update(E=E, Ie=m * r.choice([1, 3, 4]), n_shared=r.choice([0, 1, 2]))
+        spec.update(E=E, Ie=m * r.choice([1, 3, 4]) * scale, n_shared=r.choice([0, 1, 2]))
         src["ep"] = r.choice([x for x in (1, 2, 4, 8) if E % x == 0])
         dst["ep"] = r.choice([x for x in (1, 2, 4, 8) if E % x == 0])
         src["expert_layout"] = r.choice(["per_expert", "grouped"])
@@ -246,7 +248,7 @@ def random_case(seed: int) -> dict:
         if r.random() < 0.3:
             dst["etp"] = tp_d
     if r.random() < 0.8:
-        V = r.choice([40, 50, 64, 96])
+        V = r.choice([40, 50, 64, 96]) * scale + (r.choice([0, 1, 7]) if scale > 1 else 0)
         spec.update(V=V, has_embeddings=1, tied_embeddings=r.choice([0, 0, 1]))
         for lay in (src, dst):
             pad = -V % lay["tp"]
@@ -258,7 +260,7 @@ def random_case(seed: int) -> dict:
         dst["tp_filter"] = r.randrange(tp_d)
     if r.random() < 0.25 and dst.get("ep", 1) > 1:
         dst["ep_filter"] = r.randrange(dst["ep"])
-    return _wl("random_%d" % seed, make_spec(**spec), make_layout(**src), make_layout(**dst), 3000 + seed,
+    return _wl("random_%d_x%d" % (seed, scale), make_spec(**spec), make_layout(**src), make_layout(**dst), 3000 + seed + 7919 * (scale - 1),
                "random small workload")
 
 

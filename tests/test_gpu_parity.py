@@ -50,6 +50,15 @@ def test_random_small_workloads(first):
         run_case(random_case(seed), mode="raw16", threads=2)
 
 
+@pytest.mark.parametrize("first", range(0, 64, 16))
+def test_random_midsize_workloads(first):
+    """The random generator with widths scaled by 16: tensors of many tiles with ragged ends,
+    3 MB to 1 GB per case, every element size, transposing descriptors on the register path."""
+    for seed in range(first, first + 16):
+        print("case random x16", seed, flush=True)
+        run_case(random_case(seed, 16), mode="raw16", threads=8)
+
+
 @pytest.mark.parametrize("mode", ["normal", "raw16"])
 def test_toy_config_c0(mode):
     print("case C0", mode, flush=True)

@@ -16,7 +16,7 @@ from oracle import fast, locate
 from paper_2507_19017_amd import Plan
 from synth_inputs import random_case
 from test_oracle import DT, SENT, run_both
-from test_plan_host import run_descs
+from test_plan_host import run_descs, run_tiles
 
 SEEDS = list(range(160))
 
@@ -49,3 +49,27 @@ def test_random_case_agrees_across_all_formulations(seed):
         assert cnt[b].max(initial=0) <= 1
         assert np.array_equal(c3[b].reshape(-1, eb)[:, 0], cnt[b].astype(np.int32)), "bytes written once, pads never"
     assert nbytes == total == plan.info()["bytes_moved"]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_midsize_tile_tables(seed):
+    """The same generator with widths scaled up, so that tensors span several tiles with ragged
+    ends and the transposing descriptors reach the register-path tile shapes: the device tile
+    table, interpreted on the host, against the loop oracle."""
+    w = random_case(seed, 4)
+    spec, eb = w["spec"], w["spec"]["elem_bytes"]
+    plan = Plan(spec, w["src"], w["dst"])
+    rng = np.random.default_rng(w["seed"])
+    src = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in plan.buf_bytes(0)]
+    used = plan.buf_used(1)
+    got = [np.full(n, SENT[1], dtype=np.uint8) for n in plan.buf_bytes(1)]
+    cnt = [np.zeros(n, dtype=np.int32) for n in plan.buf_bytes(1)]
+    run_tiles(plan.tiles(), src, got, cnt)
+    want = [np.full(n // eb, SENT[eb], dtype=DT[eb]) if u else None for n, u in zip(plan.buf_bytes(1), used)]
+    nbytes = fast.reshard(spec, w["src"], w["dst"], [x.view(DT[eb]) for x in src], want, threads=4)
+    for b, u in enumerate(used):
+        if u:
+            assert np.array_equal(got[b].view(DT[eb]), want[b]), f"buffer {b}"
+        else:
+            assert not cnt[b].any()
+    assert sum(int(c.sum()) for c in cnt) == nbytes and max(int(c.max(initial=0)) for c in cnt) <= 1
