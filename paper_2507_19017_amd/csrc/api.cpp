@@ -222,23 +222,22 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
         p->fast_cols = tuning.transpose_cols;
         if (!transpose_shape_ok(spec->elem_bytes, p->fast_rows, p->fast_cols))
             transpose_default_shape(spec->elem_bytes, p->fast_rows, p->fast_cols);
-        p->edge_dim = transpose_edge_dim(spec->elem_bytes);
-        if (int rc = cut_tiles(p->descs, ns, tuning, p->fast_rows, p->fast_cols, p->edge_dim, p->copy_tiles, p->fast_transpose_tiles, p->edge_transpose_tiles,
-                               p->transpose_tiles)) {
+        if (int rc = cut_tiles(p->descs, ns, tuning, p->fast_rows, p->fast_cols, p->classes)) {
             delete p;
             return rc;
         }
-        if (p->copy_tiles.size() > 0x7FFFFFF0ull || p->transpose_tiles.size() > 0x7FFFFFF0ull ||
-            p->fast_transpose_tiles.size() > 0x7FFFFFF0ull || p->edge_transpose_tiles.size() > 0x7FFFFFF0ull) {
-            delete p;
-            return fail(RESHARD_ERR_UNSUPPORTED, "too many tiles");
+        p->info.num_tiles = p->info.num_transpose_tiles = 0;
+        for (const TileClass &c : p->classes) {
+            if (c.tiles.size() > 0x7FFFFFF0ull) {
+                delete p;
+                return fail(RESHARD_ERR_UNSUPPORTED, "too many tiles");
+            }
+            p->info.num_tiles += int64_t(c.tiles.size());
+            if (c.kind != 0) p->info.num_transpose_tiles += int64_t(c.tiles.size());
         }
         p->info.num_src_bufs = ns;
         p->info.num_dst_bufs = nd;
         p->info.num_descs = int64_t(p->descs.size());
-        p->info.num_transpose_tiles = int64_t(p->transpose_tiles.size() + p->fast_transpose_tiles.size() +
-                                              p->edge_transpose_tiles.size());
-        p->info.num_tiles = int64_t(p->copy_tiles.size()) + p->info.num_transpose_tiles;
         int64_t moved = 0;
         for (const reshard_desc &d : p->descs) moved += d.rows * d.row_bytes;
         p->info.bytes_moved = moved;
@@ -330,16 +329,15 @@ extern "C" int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshar
 
 extern "C" int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshard_tile *out) {
     if (!plan || !out || index < 0 || index >= plan->info.num_tiles) return fail(RESHARD_ERR_INVALID_ARG, "bad plan, index or out");
-    const std::vector<Tile> *lists[4] = {&plan->copy_tiles, &plan->fast_transpose_tiles, &plan->edge_transpose_tiles,
-                                         &plan->transpose_tiles};
-    int cls = 0;
-    size_t at = size_t(index);
-    while (at >= lists[cls]->size()) at -= lists[cls++]->size();
-    const Tile &t = (*lists[cls])[at];
+    size_t cls = 0, at = size_t(index);
+    while (at >= plan->classes[cls].tiles.size()) at -= plan->classes[cls++].tiles.size();
+    const TileClass &c = plan->classes[cls];
+    const Tile &t = c.tiles[at];
     out->src_buf = t.src_buf;
     out->dst_buf = int32_t(t.dst_buf) - plan->info.num_src_bufs;
     out->kind = t.kind;
-    out->tile_class = cls;
+    // 0 copy; 1 register transpose of the preferred shape; 2 register transpose of another shape; 3 generic
+    out->tile_class = c.kind == 0 ? 0 : c.kind == 2 ? 3 : cls == 1 ? 1 : 2;
     out->src_off = int64_t(t.src_off);
     out->dst_off = int64_t(t.dst_off);
     out->rows = t.rows;

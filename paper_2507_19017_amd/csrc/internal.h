@@ -86,8 +86,13 @@ inline void transpose_default_shape(int E, int &ti, int &tk) {
     ti = E == 8 ? 128 : E == 4 ? 128 : E == 1 ? 512 : 256;
     tk = E == 8 ? 128 : 256;
 }
-// The strips the big tiles leave over are cut into squares of this many elements.
-inline int transpose_edge_dim(int E) { return E == 1 ? 128 : 64; }
+
+// Tiles of one kind that go out in one launch.
+struct TileClass {
+    int kind = 0;            // 0 strided copy, 1 register transpose of rows x cols elements, 2 generic transpose
+    int rows = 0, cols = 0;  // kind 1 only
+    std::vector<Tile> tiles;
+};
 
 void set_error(const std::string &msg);
 int fail(int code, const std::string &msg);
@@ -96,9 +101,10 @@ int fail(int code, const std::string &msg);
 int build_side(const reshard_model_spec &spec, const reshard_layout &lay, bool is_source, Side &out);
 int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
                         std::vector<reshard_desc> &descs);
+// classes[0]: copy tiles; classes[1]: register-transposed tiles of the preferred shape
+// (fast_rows x fast_cols); then one class per other register shape used; last: generic transposes.
 int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
-              int fast_rows, int fast_cols, int edge_dim, std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
-              std::vector<Tile> &edge_transpose_tiles, std::vector<Tile> &transpose_tiles);
+              int fast_rows, int fast_cols, std::vector<TileClass> &classes);
 
 }  // namespace reshard
 
@@ -106,19 +112,17 @@ struct reshard_plan {
     reshard_model_spec spec{};
     reshard::Side src, dst;
     std::vector<reshard_desc> descs;
-    // copy tiles; full transposing tiles (register path); remaining transposing tiles
-    // (the register path takes the interior in fast_rows x fast_cols tiles and the strips
-    // left over in edge_dim x edge_dim tiles; what is still left goes to the generic kernel)
-    std::vector<reshard::Tile> copy_tiles, fast_transpose_tiles, edge_transpose_tiles, transpose_tiles;
-    int fast_rows = 0, fast_cols = 0, edge_dim = 0;  // tile shapes the register-path tiles were cut with
+    // copy tiles; register-transposed tiles by shape (the preferred shape first); generic transposes
+    std::vector<reshard::TileClass> classes;
+    int fast_rows = 0, fast_cols = 0;  // preferred shape of the register-transposed tiles
     reshard_plan_info info{};
 
     // device side (created lazily by the first execute)
     int device = -1;
-    void *d_tiles = nullptr;  // copy, fast transposing, edge transposing, generic transposing tiles
+    void *d_tiles = nullptr;  // the classes' tiles one after another
     int num_cus = 0;
     // streaming (created by the first execute_source): the tiles regrouped by source buffer
-    struct SrcSlice { uint32_t first[4] = {0, 0, 0, 0}, count[4] = {0, 0, 0, 0}; };
+    struct SrcSlice { std::vector<uint32_t> first, count; };  // per class
     std::vector<SrcSlice> src_slices;
     std::vector<reshard::Tile> by_src_tiles;
     void *d_by_src = nullptr;

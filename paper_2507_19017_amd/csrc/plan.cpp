@@ -452,13 +452,26 @@ int compile_descriptors(const reshard_model_spec &spec, Side &src, Side &dst,
 }
 
 int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tuning &tuning,
-              int fast_rows, int fast_cols, int edge_dim, std::vector<Tile> &copy_tiles, std::vector<Tile> &fast_transpose_tiles,
-              std::vector<Tile> &edge_transpose_tiles, std::vector<Tile> &transpose_tiles) {
+              int fast_rows, int fast_cols, std::vector<TileClass> &classes) {
     const int tile_bytes = tuning.tile_bytes;
-    copy_tiles.clear();
-    fast_transpose_tiles.clear();
-    edge_transpose_tiles.clear();
-    transpose_tiles.clear();
+    classes.clear();
+    classes.resize(2);
+    classes[0].kind = 0;
+    classes[1].kind = 1;
+    classes[1].rows = fast_rows;
+    classes[1].cols = fast_cols;
+    TileClass generic;
+    generic.kind = 2;
+    auto reg_class = [&](int ti, int tk) -> std::vector<Tile> & {
+        for (size_t c = 1; c < classes.size(); ++c)
+            if (classes[c].rows == ti && classes[c].cols == tk) return classes[c].tiles;
+        TileClass n;
+        n.kind = 1;
+        n.rows = ti;
+        n.cols = tk;
+        classes.push_back(n);
+        return classes.back().tiles;
+    };
     auto fits32 = [](int64_t v) { return v >= 0 && v <= 0xFFFFFFFFll; };
     for (const reshard_desc &d : descs) {
         if (!fits32(d.src_stride) || !fits32(d.dst_stride))
@@ -471,58 +484,66 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
         if (d.kind == 1) {
             int lg = 0;
             while ((1 << lg) < d.elem_bytes) ++lg;
+            const int E = d.elem_bytes;
             const int64_t cols = d.row_bytes / d.elem_bytes;
             t.kind = 1;
             t.vec_log2 = uint8_t(lg);
-            // Tiles the rectangle [i0,i1) x [k0,k1) of the source matrix with full ti x tk tiles
-            // starting at its corner; returns the extent covered (a multiple of the tile shape).
-            auto tile_rect = [&](int64_t i0, int64_t i1, int64_t k0, int64_t k1, int64_t ti, int64_t tk,
-                                 std::vector<Tile> &out, int64_t &ci, int64_t &ck) {
-                ci = (i1 - i0) / ti * ti;
-                ck = (k1 - k0) / tk * tk;
-                if (ci == 0 || ck == 0) { ci = ck = 0; return; }
-                for (int64_t i = i0; i < i0 + ci; i += ti)
-                    for (int64_t k = k0; k < k0 + ck; k += tk) {
-                        t.rows = uint32_t(std::min(ti, i1 - i));
-                        t.row_units = uint32_t(std::min(tk, k1 - k));
-                        t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
-                        t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
-                        out.push_back(t);
-                    }
+            auto emit = [&](int64_t i, int64_t k, int64_t ni, int64_t nk, std::vector<Tile> &out) {
+                t.rows = uint32_t(ni);
+                t.row_units = uint32_t(nk);
+                t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
+                t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
+                out.push_back(t);
             };
             // generic tiles: any extent, cut at kTransposeDim
             auto generic_rect = [&](int64_t i0, int64_t i1, int64_t k0, int64_t k1) {
                 for (int64_t i = i0; i < i1; i += kTransposeDim)
-                    for (int64_t k = k0; k < k1; k += kTransposeDim) {
-                        t.rows = uint32_t(std::min<int64_t>(kTransposeDim, i1 - i));
-                        t.row_units = uint32_t(std::min<int64_t>(kTransposeDim, k1 - k));
-                        t.src_off = uint64_t(d.src_off + i * d.src_stride + k * d.elem_bytes);
-                        t.dst_off = uint64_t(d.dst_off + k * d.dst_stride + i * d.elem_bytes);
-                        transpose_tiles.push_back(t);
-                    }
+                    for (int64_t k = k0; k < k1; k += kTransposeDim)
+                        emit(i, k, std::min<int64_t>(kTransposeDim, i1 - i), std::min<int64_t>(kTransposeDim, k1 - k),
+                             generic.tiles);
             };
-            const bool reg_path = (d.src_off | d.dst_off | d.src_stride | d.dst_stride) % 16 == 0 &&
-                                  transpose_shape_ok(d.elem_bytes, fast_rows, fast_cols) &&
-                                  transpose_shape_ok(d.elem_bytes, edge_dim, edge_dim);
-            if (!reg_path) {
-                generic_rect(0, d.rows, 0, cols);
-                continue;
-            }
-            // interior in big register-transposed tiles; the right and bottom strips in small square
-            // register-transposed tiles; what is left of those (under one such square wide or high) generic
-            int64_t fi, fk;
-            tile_rect(0, d.rows, 0, cols, fast_rows, fast_cols, fast_transpose_tiles, fi, fk);
+            const bool reg_path = (d.src_off | d.dst_off | d.src_stride | d.dst_stride) % 16 == 0;
+            // Largest register-path shape that fits an R x C rectangle: the preferred shape if it
+            // fits, else the fitting shape of the largest area (the longer source rows on a tie).
+            auto best_shape = [&](int64_t R, int64_t C, int &ti, int &tk) {
+                if (fast_rows <= R && fast_cols <= C && transpose_shape_ok(E, fast_rows, fast_cols)) {
+                    ti = fast_rows;
+                    tk = fast_cols;
+                    return true;
+                }
+                int64_t best = 0;
+                for (int a : {512, 256, 128, 64})
+                    for (int b : {512, 256, 128, 64})
+                        if (a <= R && b <= C && transpose_shape_ok(E, a, b) && int64_t(a) * b > best) {
+                            best = int64_t(a) * b;
+                            ti = a;
+                            tk = b;
+                        }
+                return best > 0;
+            };
+            // Full tiles of the best shape from the rectangle's corner, then the same again for the
+            // strip to the right of them and the strip below; what no shape fits goes to the generic kernel.
             struct Rect { int64_t i0, i1, k0, k1; };
-            const Rect strips[2] = {{0, fi, fk, cols}, {fi, d.rows, 0, cols}};  // right of the interior; below it
-            for (const Rect &r : strips) {
+            std::vector<Rect> todo{{0, d.rows, 0, cols}};
+            while (!todo.empty()) {
+                const Rect r = todo.back();
+                todo.pop_back();
                 if (r.i0 >= r.i1 || r.k0 >= r.k1) continue;
-                int64_t ei, ek;
-                tile_rect(r.i0, r.i1, r.k0, r.k1, edge_dim, edge_dim, edge_transpose_tiles, ei, ek);
-                generic_rect(r.i0, r.i0 + ei, r.k0 + ek, r.k1);  // right of the squares
-                generic_rect(r.i0 + ei, r.i1, r.k0, r.k1);       // below it
+                int ti = 0, tk = 0;
+                if (!reg_path || !best_shape(r.i1 - r.i0, r.k1 - r.k0, ti, tk)) {
+                    generic_rect(r.i0, r.i1, r.k0, r.k1);
+                    continue;
+                }
+                const int64_t ci = (r.i1 - r.i0) / ti * ti, ck = (r.k1 - r.k0) / tk * tk;
+                std::vector<Tile> &out = reg_class(ti, tk);
+                for (int64_t i = r.i0; i < r.i0 + ci; i += ti)
+                    for (int64_t k = r.k0; k < r.k0 + ck; k += tk) emit(i, k, ti, tk, out);
+                todo.push_back({r.i0 + ci, r.i1, r.k0, r.k1});       // below
+                todo.push_back({r.i0, r.i0 + ci, r.k0 + ck, r.k1});  // right of the tiles
             }
             continue;
         }
+        std::vector<Tile> &copy_tiles = classes[0].tiles;  // (no class is added below: the reference holds)
         // widest vector that every row start and the row length allow
         int vec = 16;
         auto misfit = [&](int v) {
@@ -564,6 +585,7 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
             }
         }
     }
+    classes.push_back(std::move(generic));
     return RESHARD_OK;
 }
 

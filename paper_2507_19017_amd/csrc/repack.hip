@@ -397,11 +397,12 @@ int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
     return RESHARD_OK;
 }
 
-// Launches `n` tiles of one class (0 copy, 1 register transpose in the tuned shape, 2 register
-// transpose 64 x 64, 3 generic transpose) starting at device address `t`.
-int launch_class(const reshard_plan *plan, const Tuning &tn, int cls, const Tile *t, uint32_t n,
+// Launches `n` tiles of class `tc` (copy, register transpose of one shape, generic transpose)
+// starting at device address `t`.
+int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc, const Tile *t, uint32_t n,
                  const PtrTable &pt, hipStream_t stream) {
     if (!n) return RESHARD_OK;
+    const int cls = tc.kind;
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
     const uint32_t wanted = tn.blocks_per_cu ? uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu) : 0xFFFFFFFFu;
     const int by_xcd = (tn.flags & 8) ? 1 : 0;
@@ -416,8 +417,8 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, int cls, const Tile
             launch_copy(tn, dim3(m), dim3(tn.block_threads), stream, t + first, m, pt);
             if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
         }
-    } else if (cls == 1 || cls == 2) {
-        const int rows = cls == 1 ? plan->fast_rows : plan->edge_dim, cols = cls == 1 ? plan->fast_cols : plan->edge_dim;
+    } else if (cls == 1) {
+        const int rows = tc.rows, cols = tc.cols;
         const int E = plan->spec.elem_bytes;
         if (!transpose_shape_ok(E, rows, cols)) return fail(RESHARD_ERR_INVALID_ARG, "unsupported transposing tile shape");
         const int shape = (E * 1000 + rows) * 1000 + cols;
@@ -469,19 +470,15 @@ void fill_ptrs(const reshard_plan *plan, PtrTable &pt) {
     for (int i = 0; i < nd; ++i) pt.p[ns + i] = static_cast<char *>(plan->dst_ptrs[i]);
 }
 
-const std::vector<Tile> &class_list(const reshard_plan *plan, int cls) {
-    return cls == 0 ? plan->copy_tiles : cls == 1 ? plan->fast_transpose_tiles
-         : cls == 2 ? plan->edge_transpose_tiles : plan->transpose_tiles;
-}
-
 }  // namespace
 
 // Uploads the tile table on first use; returns RESHARD_OK or an error code.
 int ensure_device_table(reshard_plan *plan) {
     if (int rc = query_device(plan)) return rc;
     if (plan->d_tiles || plan->info.num_tiles == 0) return RESHARD_OK;
-    return upload({&plan->copy_tiles, &plan->fast_transpose_tiles, &plan->edge_transpose_tiles, &plan->transpose_tiles},
-                  &plan->d_tiles);
+    std::vector<const std::vector<Tile> *> lists;
+    for (const TileClass &c : plan->classes) lists.push_back(&c.tiles);
+    return upload(lists, &plan->d_tiles);
 }
 
 int launch_repack(reshard_plan *plan, hipStream_t stream) {
@@ -489,9 +486,9 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     PtrTable pt;
     fill_ptrs(plan, pt);
     const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
-    for (int cls = 0; cls < 4; ++cls) {
-        const uint32_t n = uint32_t(class_list(plan, cls).size());
-        if (int rc = launch_class(plan, tn, cls, tiles, n, pt, stream)) return rc;
+    for (const TileClass &c : plan->classes) {
+        const uint32_t n = uint32_t(c.tiles.size());
+        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream)) return rc;
         tiles += n;
     }
     return RESHARD_OK;
@@ -503,21 +500,24 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
 int ensure_by_source_table(reshard_plan *plan) {
     if (int rc = query_device(plan)) return rc;
     if (plan->d_by_src) return RESHARD_OK;
-    const size_t ns = size_t(plan->info.num_src_bufs);
-    plan->src_slices.assign(ns, reshard_plan::SrcSlice{});
-    for (int cls = 0; cls < 4; ++cls)
-        for (const Tile &t : class_list(plan, cls)) ++plan->src_slices[t.src_buf].count[cls];
+    const size_t ns = size_t(plan->info.num_src_bufs), nc = plan->classes.size();
+    reshard_plan::SrcSlice empty;
+    empty.first.assign(nc, 0);
+    empty.count.assign(nc, 0);
+    plan->src_slices.assign(ns, empty);
+    for (size_t cls = 0; cls < nc; ++cls)
+        for (const Tile &t : plan->classes[cls].tiles) ++plan->src_slices[t.src_buf].count[cls];
     uint32_t at = 0;
     for (size_t b = 0; b < ns; ++b)
-        for (int cls = 0; cls < 4; ++cls) {
+        for (size_t cls = 0; cls < nc; ++cls) {
             plan->src_slices[b].first[cls] = at;
             at += plan->src_slices[b].count[cls];
         }
     plan->by_src_tiles.resize(at);
-    std::vector<uint32_t> fill(ns * 4, 0);
-    for (int cls = 0; cls < 4; ++cls)
-        for (const Tile &t : class_list(plan, cls))  // table order is kept inside every group
-            plan->by_src_tiles[plan->src_slices[t.src_buf].first[cls] + fill[size_t(t.src_buf) * 4 + cls]++] = t;
+    std::vector<uint32_t> fill(ns * nc, 0);
+    for (size_t cls = 0; cls < nc; ++cls)
+        for (const Tile &t : plan->classes[cls].tiles)  // table order is kept inside every group
+            plan->by_src_tiles[plan->src_slices[t.src_buf].first[cls] + fill[size_t(t.src_buf) * nc + cls]++] = t;
     return upload({&plan->by_src_tiles}, &plan->d_by_src);
 }
 
@@ -527,8 +527,8 @@ int launch_source(reshard_plan *plan, int src_index, hipStream_t stream) {
     fill_ptrs(plan, pt);
     const Tile *base = static_cast<const Tile *>(plan->d_by_src);
     const reshard_plan::SrcSlice &sl = plan->src_slices[size_t(src_index)];
-    for (int cls = 0; cls < 4; ++cls)
-        if (int rc = launch_class(plan, tn, cls, base + sl.first[cls], sl.count[cls], pt, stream)) return rc;
+    for (size_t cls = 0; cls < plan->classes.size(); ++cls)
+        if (int rc = launch_class(plan, tn, plan->classes[cls], base + sl.first[cls], sl.count[cls], pt, stream)) return rc;
     return RESHARD_OK;
 }
 

@@ -100,6 +100,16 @@ WORKLOADS = {
         make_layout(kind="train", tp=1, pp=2, ep=8, expert_layout="per_expert"),
         make_layout(kind="gen", tp=2, ep=4),
         1003, "Qwen3-30B-A3B-shaped, EP8 TP1 PP2 (per-expert) -> EP4 TP2"),
+    # Not a task config: the same model with every expert also split over the tensor ranks
+    # (expert tensor parallelism) on both sides, grouped source experts: TP2 ETP2 EP4 PP2 ->
+    # TP4 ETP4 EP2.  Half- and quarter-width transposes at full size.
+    "C3E": _wl(
+        "C3E",
+        make_spec(family="moe_gqa", L=48, H=2048, nq=32, nkv=4, d=128, V=151936,
+                  E=128, Ie=768),
+        make_layout(kind="train", tp=2, pp=2, ep=4, etp=2, expert_layout="grouped"),
+        make_layout(kind="gen", tp=4, ep=2, etp=4),
+        1006, "Qwen3-30B-A3B-shaped, TP2 ETP2 EP4 PP2 (grouped experts) -> TP4 ETP4 EP2"),
     # DeepSeek-671B-shaped share: 8 MoE layers, EP64 -> rank 0 of EP8.
     "C4": _wl(
         "C4",

@@ -33,13 +33,13 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
                bool expect_ok) {
     Side S, D;
     std::vector<reshard_desc> descs;
-    std::vector<Tile> c, f, e, g;
     int rc = build_side(s, a, true, S);
     if (!rc) rc = build_side(s, b, false, D);
     if (!rc) rc = compile_descriptors(s, S, D, descs);
     int fr = tn.transpose_rows, fc = tn.transpose_cols;
     if (!transpose_shape_ok(s.elem_bytes, fr, fc)) transpose_default_shape(s.elem_bytes, fr, fc);
-    if (!rc) rc = cut_tiles(descs, int(S.buf_bytes.size()), tn, fr, fc, transpose_edge_dim(s.elem_bytes), c, f, e, g);
+    std::vector<TileClass> classes;
+    if (!rc) rc = cut_tiles(descs, int(S.buf_bytes.size()), tn, fr, fc, classes);
     if ((rc == 0) != expect_ok) {
         std::printf("unexpected result %d (expected %s)\n", rc, expect_ok ? "ok" : "an error");
         return 1;
@@ -64,7 +64,16 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
             if (s_end > sb || d_end > db) { std::printf("tile leaves its buffer\n"); std::exit(1); }
         }
     };
-    check(c); check(f); check(e); check(g);
+    for (const TileClass &c : classes) {
+        check(c.tiles);
+        // register-path tiles are whole tiles of their class's shape, in a shape the kernel is built for
+        if (c.kind == 1)
+            for (const Tile &t : c.tiles)
+                if (int(t.rows) != c.rows || int(t.row_units) != c.cols || !transpose_shape_ok(s.elem_bytes, c.rows, c.cols)) {
+                    std::printf("register-path tile of a wrong shape\n");
+                    return 1;
+                }
+    }
     if (dbytes != tbytes) { std::printf("tile bytes %lld != descriptor bytes %lld\n", tbytes, dbytes); return 1; }
     return 0;
 }

@@ -580,6 +580,28 @@ def test_c3_qwen3_moe_shape_sampled(name):
     assert np.array_equal(dst[nd + 2].cpu().numpy(), want[nd + 2])
 
 
+def test_c3e_expert_tensor_parallelism_at_full_size():
+    wl = WORKLOADS["C3E"]
+    print("case C3E", flush=True)
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    src = G.device_sources(plan, wl)
+    dst = G.device_destinations(plan)
+    plan.execute(G.ptrs(src), G.ptrs(dst), G.stream_handle())
+    torch.cuda.synchronize()
+    n = sampled(wl, plan, src, dst, 48, 3000, 23)
+    print("C3E sampled pairs", n, flush=True)
+    pads_untouched(plan, dst)
+    # tensor rank 1 whole: its dense buffer and its quarter of expert rank 1's experts
+    only = dict(wl["dst"], tp_filter=1, ep_filter=1)
+    host_src = needed_sources_on_host(wl, only, src)
+    want = G.oracle_destinations(wl, host_src, 16, only)
+    nd, etp = wl["dst"]["tp"], wl["dst"]["etp"]
+    assert [i for i, w in enumerate(want) if w is not None] == [1, nd + 1 * etp + 1]
+    assert np.array_equal(dst[1].cpu().numpy(), want[1])
+    assert np.array_equal(dst[nd + etp + 1].cpu().numpy(), want[nd + etp + 1])
+    assert plan.info()["num_transpose_tiles"] > 0
+
+
 def test_c4_deepseek_shape_share_whole_output():
     print("case C4 full", flush=True)
     plan, src, dst = run_case(WORKLOADS["C4"], "normal")
