@@ -52,6 +52,15 @@ def oracle_destinations(wl, src_host, threads=16, dst_lay=None, src_lay=None):
     return dst
 
 
+def host_copy_view(plan, index):
+    """The plan's pinned host copy of one source buffer as an int16 numpy array (no copy)."""
+    import ctypes
+
+    n = plan.buf_bytes(0)[index] // 2
+    raw = (ctypes.c_int16 * n).from_address(plan.host_copy(index))
+    return np.frombuffer(raw, dtype=np.int16)
+
+
 def to_host(bufs):
     return [None if b is None else b.cpu().numpy() for b in bufs]
 

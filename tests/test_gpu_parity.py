@@ -19,7 +19,7 @@ def with_eb(wl, eb):
     return w
 
 
-def run_case(wl, mode="normal", src_lay=None, dst_lay=None, threads=16):
+def run_case(wl, mode="normal", src_lay=None, dst_lay=None, threads=16, via_swap=False):
     src_lay = src_lay or wl["src"]
     dst_lay = dst_lay or wl["dst"]
     plan = Plan(wl["spec"], src_lay, dst_lay)
@@ -27,7 +27,14 @@ def run_case(wl, mode="normal", src_lay=None, dst_lay=None, threads=16):
     dst = G.device_destinations(plan)
     plan.execute(G.ptrs(src), G.ptrs(dst), G.stream_handle())
     torch.cuda.synchronize()
-    host_src = [None if s is None else s.cpu().numpy() for s in src]
+    if via_swap:
+        # the oracle reads the library's own pinned swap copies (a 57 GB/s copy instead of a pageable
+        # one), which also holds the swap-out to the same bar: a wrong byte there shows in the result
+        plan.swap_out(G.stream_handle())
+        plan.swap_wait()
+        host_src = [None if s is None else G.host_copy_view(plan, i) for i, s in enumerate(src)]
+    else:
+        host_src = [None if s is None else s.cpu().numpy() for s in src]
     # the oracle needs every source buffer it reads; unused ones may stay None
     want = G.oracle_destinations(wl, host_src, threads, dst_lay, src_lay)
     G.assert_equal_buffers(dst, want, wl["name"])
@@ -493,19 +500,21 @@ def pads_untouched(plan, dst):
         assert bool((d[end // 2:] == G.SENT16).all())
 
 
-def needed_sources_on_host(wl, dst_lay, src):
-    """Host copies of only the source buffers a filtered destination reads (the
-    oracle dereferences nothing else); the others stay None."""
-    used = Plan(wl["spec"], wl["src"], dst_lay).buf_used(0)
-    rng = np.random.default_rng(1)
-    sb = locate.sample_pairs(wl["spec"], wl["src"], dst_lay, 2, rng, 500)[0]
-    assert all(used[int(b)] for b in np.unique(sb))
-    return [s.cpu().numpy() if u else None for s, u in zip(src, used)]
-
-
 def test_c1_qwen25_7b_shape_whole_output_against_the_oracle():
     print("case C1 full", flush=True)
     plan, src, dst = run_case(WORKLOADS["C1"], "normal")
+    pads_untouched(plan, dst)
+
+
+def test_c1_one_destination_rank_only():
+    """A plan for one destination rank (what a single device of the generation side would run):
+    only its buffer is written, and it equals the same rank of the unfiltered result."""
+    wl = WORKLOADS["C1"]
+    print("case C1 rank filter", flush=True)
+    only = dict(wl["dst"], tp_filter=1)
+    plan, src, dst = run_case(wl, "normal", dst_lay=only)
+    assert dst[0] is None and plan.buf_used(1) == [False, True]
+    assert plan.info()["bytes_moved"] < 0.51 * Plan(wl["spec"], wl["src"], wl["dst"]).info()["bytes_moved"]
     pads_untouched(plan, dst)
 
 
@@ -541,65 +550,18 @@ def test_c1r_kv_replication_and_interleaved_stages_at_full_size():
     pads_untouched(plan, dst)
 
 
-def test_c2_qwen25_32b_shape_sampled_and_one_rank_whole():
-    wl = WORKLOADS["C2"]
-    print("case C2", flush=True)
-    plan = Plan(wl["spec"], wl["src"], wl["dst"])
-    src = G.device_sources(plan, wl)
-    dst = G.device_destinations(plan)
-    plan.execute(G.ptrs(src), G.ptrs(dst), G.stream_handle())
-    torch.cuda.synchronize()
-    n = sampled(wl, plan, src, dst, 64, 600, 21)
-    print("C2 sampled pairs", n, flush=True)
-    pads_untouched(plan, dst)
-    # destination rank 1 of 4, whole, from the oracle under a rank filter
-    only = dict(wl["dst"], tp_filter=1)
-    host_src = needed_sources_on_host(wl, only, src)
-    want = G.oracle_destinations(wl, host_src, 16, only)
-    assert np.array_equal(dst[1].cpu().numpy(), want[1])
-
-
-@pytest.mark.parametrize("name", ["C3", "C3P"])
-def test_c3_qwen3_moe_shape_sampled(name):
+@pytest.mark.parametrize("name", ["C2", "C3", "C3P", "C3E"])
+def test_largest_shapes_whole_output_and_sampled_pairs(name):
+    """The 61-65 GB workloads: every destination byte against the loop oracle (run on host copies
+    of the sources), sampled element pairs from every tensor against the definition oracle, pads
+    untouched."""
     wl = WORKLOADS[name]
-    print("case", name, flush=True)
-    plan = Plan(wl["spec"], wl["src"], wl["dst"])
-    src = G.device_sources(plan, wl)
-    dst = G.device_destinations(plan)
-    plan.execute(G.ptrs(src), G.ptrs(dst), G.stream_handle())
-    torch.cuda.synchronize()
+    print("case", name, "full", flush=True)
+    plan, src, dst = run_case(wl, "normal", via_swap=True)
     n = sampled(wl, plan, src, dst, 48, 3000, 22)
     print(name, "sampled pairs", n, flush=True)
     pads_untouched(plan, dst)
-    # one expert-parallel destination rank whole (layers of both source stages)
-    only = dict(wl["dst"], tp_filter=0, ep_filter=2)
-    host_src = needed_sources_on_host(wl, only, src)
-    want = G.oracle_destinations(wl, host_src, 16, only)
-    nd = wl["dst"]["tp"]
-    assert np.array_equal(dst[0].cpu().numpy(), want[0])
-    assert np.array_equal(dst[nd + 2].cpu().numpy(), want[nd + 2])
-
-
-def test_c3e_expert_tensor_parallelism_at_full_size():
-    wl = WORKLOADS["C3E"]
-    print("case C3E", flush=True)
-    plan = Plan(wl["spec"], wl["src"], wl["dst"])
-    src = G.device_sources(plan, wl)
-    dst = G.device_destinations(plan)
-    plan.execute(G.ptrs(src), G.ptrs(dst), G.stream_handle())
-    torch.cuda.synchronize()
-    n = sampled(wl, plan, src, dst, 48, 3000, 23)
-    print("C3E sampled pairs", n, flush=True)
-    pads_untouched(plan, dst)
-    # tensor rank 1 whole: its dense buffer and its quarter of expert rank 1's experts
-    only = dict(wl["dst"], tp_filter=1, ep_filter=1)
-    host_src = needed_sources_on_host(wl, only, src)
-    want = G.oracle_destinations(wl, host_src, 16, only)
-    nd, etp = wl["dst"]["tp"], wl["dst"]["etp"]
-    assert [i for i, w in enumerate(want) if w is not None] == [1, nd + 1 * etp + 1]
-    assert np.array_equal(dst[1].cpu().numpy(), want[1])
-    assert np.array_equal(dst[nd + etp + 1].cpu().numpy(), want[nd + etp + 1])
-    assert plan.info()["num_transpose_tiles"] > 0
+    assert (plan.info()["num_transpose_tiles"] > 0) == (wl["src"]["expert_layout"] == "grouped")
 
 
 def test_c4_deepseek_shape_share_whole_output():
