@@ -317,7 +317,7 @@ def test_streaming_one_source_buffer_at_a_time(name):
         assert (a is None and b is None) or torch.equal(a, b)
 
 
-@pytest.mark.parametrize("name", ["C1", "C3"])
+@pytest.mark.parametrize("name", ["C1", "C3E"])
 def test_streaming_equals_one_shot_at_full_size(name):
     wl = WORKLOADS[name]
     print("streaming full size", name, flush=True)
