@@ -241,7 +241,9 @@ int reshard_get_tuning(reshard_tuning *out);
  * degrees is the identity and GEN -> TRAIN is the way back.  Rank filters must
  * be -1 on the source.  *out is owned by the library until reshard_plan_destroy.
  * Errors: INVALID_ARG (NULL, struct_size), UNSUPPORTED (divisibility, more than
- * RESHARD_MAX_BUFFERS buffers, sizes beyond 32-bit strides), OOM.
+ * RESHARD_MAX_BUFFERS USED source plus destination buffers, i.e. buffers the plan reads or
+ * writes once the destination's rank filters are applied, more than 16384 buffers in one
+ * layout, sizes beyond 32-bit strides), OOM.
  */
 #define RESHARD_MAX_BUFFERS 384
 int reshard_plan_create(const reshard_model_spec *spec, const reshard_layout *src,

@@ -212,10 +212,6 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
         if (int rc = build_side(*spec, *src, true, p->src)) { delete p; return rc; }
         if (int rc = build_side(*spec, *dst, false, p->dst)) { delete p; return rc; }
         const int ns = int(p->src.buf_bytes.size()), nd = int(p->dst.buf_bytes.size());
-        if (ns + nd > RESHARD_MAX_BUFFERS) {
-            delete p;
-            return fail(RESHARD_ERR_UNSUPPORTED, "source plus destination buffers exceed RESHARD_MAX_BUFFERS");
-        }
         if (int rc = compile_descriptors(*spec, p->src, p->dst, p->descs)) { delete p; return rc; }
         const Tuning tuning = current_tuning();
         p->fast_rows = tuning.transpose_rows;
@@ -226,6 +222,29 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
             delete p;
             return rc;
         }
+        // the kernels get the pointers of the used buffers only: renumber the tiles' buffer indices
+        p->src_slot.assign(ns, -1);
+        p->dst_slot.assign(nd, -1);
+        for (int i = 0; i < ns; ++i)
+            if (p->src.used[i]) {
+                p->src_slot[i] = int(p->slot_buf.size());
+                p->slot_buf.push_back(i);
+            }
+        p->num_src_slots = int(p->slot_buf.size());
+        for (int j = 0; j < nd; ++j)
+            if (p->dst.used[j]) {
+                p->dst_slot[j] = int(p->slot_buf.size());
+                p->slot_buf.push_back(j);
+            }
+        if (p->slot_buf.size() > size_t(RESHARD_MAX_BUFFERS)) {
+            delete p;
+            return fail(RESHARD_ERR_UNSUPPORTED, "used source plus destination buffers exceed RESHARD_MAX_BUFFERS");
+        }
+        for (TileClass &c : p->classes)
+            for (Tile &t : c.tiles) {
+                t.src_buf = uint16_t(p->src_slot[t.src_buf]);
+                t.dst_buf = uint16_t(p->dst_slot[t.dst_buf - ns]);
+            }
         p->info.num_tiles = p->info.num_transpose_tiles = 0;
         for (const TileClass &c : p->classes) {
             if (c.tiles.size() > 0x7FFFFFF0ull) {
@@ -333,8 +352,8 @@ extern "C" int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshar
     while (at >= plan->classes[cls].tiles.size()) at -= plan->classes[cls++].tiles.size();
     const TileClass &c = plan->classes[cls];
     const Tile &t = c.tiles[at];
-    out->src_buf = t.src_buf;
-    out->dst_buf = int32_t(t.dst_buf) - plan->info.num_src_bufs;
+    out->src_buf = plan->slot_buf[t.src_buf];
+    out->dst_buf = plan->slot_buf[t.dst_buf];
     out->kind = t.kind;
     // 0 copy; 1 register transpose of the preferred shape; 2 register transpose of another shape; 3 generic
     out->tile_class = c.kind == 0 ? 0 : c.kind == 2 ? 3 : cls == 1 ? 1 : 2;

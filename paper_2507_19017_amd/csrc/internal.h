@@ -57,6 +57,7 @@ struct alignas(16) Tile {
 static_assert(sizeof(Tile) == 48, "tile record layout");
 
 constexpr int kMaxTileUnits = 32768;  // keeps the multiply-high row split exact
+constexpr int kMaxLayoutBuffers = 16384;  // buffers of one layout, used or not (tile records hold 16-bit indices)
 constexpr int kTransposeDim = 64;     // transposing tiles are at most 64 x 64 elements
 
 struct Tuning {
@@ -115,6 +116,10 @@ struct reshard_plan {
     // copy tiles; register-transposed tiles by shape (the preferred shape first); generic transposes
     std::vector<reshard::TileClass> classes;
     int fast_rows = 0, fast_cols = 0;  // preferred shape of the register-transposed tiles
+    // Tile records index a pointer table of the USED buffers only (used sources first, then used
+    // destinations; at most RESHARD_MAX_BUFFERS): slot of every buffer (-1 unused) and the way back.
+    std::vector<int> src_slot, dst_slot, slot_buf;
+    int num_src_slots = 0;
     reshard_plan_info info{};
 
     // device side (created lazily by the first execute)

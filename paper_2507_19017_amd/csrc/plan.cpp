@@ -199,7 +199,8 @@ int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_sou
     out.nd = P * T;
     const int Y = moe && l.etp > 0 ? l.etp : 1;  // expert-tensor ranks per expert rank
     out.ne = moe ? P * X * Y : 0;
-    if (out.nd + out.ne > RESHARD_MAX_BUFFERS) return fail(RESHARD_ERR_UNSUPPORTED, "too many buffers in one layout");
+    if (int64_t(P) * T + (moe ? int64_t(P) * X * Y : 0) > kMaxLayoutBuffers)
+        return fail(RESHARD_ERR_UNSUPPORTED, "too many buffers in one layout");
     out.buf_bytes.assign(out.nd + out.ne, 0);
     out.used.assign(out.nd + out.ne, 0);
 

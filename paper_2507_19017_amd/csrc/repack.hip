@@ -30,7 +30,7 @@ std::mutex g_tuning_mutex;
 Tuning g_tuning;
 
 struct PtrTable {
-    char *p[RESHARD_MAX_BUFFERS];  // sources first, then destinations
+    char *p[RESHARD_MAX_BUFFERS];  // the used buffers: sources first, then destinations
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -466,8 +466,10 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc
 void fill_ptrs(const reshard_plan *plan, PtrTable &pt) {
     std::memset(&pt, 0, sizeof pt);
     const int ns = plan->info.num_src_bufs, nd = plan->info.num_dst_bufs;
-    for (int i = 0; i < ns; ++i) pt.p[i] = const_cast<char *>(static_cast<const char *>(plan->src_ptrs[i]));
-    for (int i = 0; i < nd; ++i) pt.p[ns + i] = static_cast<char *>(plan->dst_ptrs[i]);
+    for (int i = 0; i < ns; ++i)
+        if (plan->src_slot[i] >= 0) pt.p[plan->src_slot[i]] = const_cast<char *>(static_cast<const char *>(plan->src_ptrs[i]));
+    for (int j = 0; j < nd; ++j)
+        if (plan->dst_slot[j] >= 0) pt.p[plan->dst_slot[j]] = static_cast<char *>(plan->dst_ptrs[j]);
 }
 
 }  // namespace
@@ -500,7 +502,7 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
 int ensure_by_source_table(reshard_plan *plan) {
     if (int rc = query_device(plan)) return rc;
     if (plan->d_by_src) return RESHARD_OK;
-    const size_t ns = size_t(plan->info.num_src_bufs), nc = plan->classes.size();
+    const size_t ns = size_t(plan->num_src_slots), nc = plan->classes.size();  // slices by source slot
     reshard_plan::SrcSlice empty;
     empty.first.assign(nc, 0);
     empty.count.assign(nc, 0);
@@ -526,7 +528,7 @@ int launch_source(reshard_plan *plan, int src_index, hipStream_t stream) {
     PtrTable pt;
     fill_ptrs(plan, pt);
     const Tile *base = static_cast<const Tile *>(plan->d_by_src);
-    const reshard_plan::SrcSlice &sl = plan->src_slices[size_t(src_index)];
+    const reshard_plan::SrcSlice &sl = plan->src_slices[size_t(plan->src_slot[size_t(src_index)])];
     for (size_t cls = 0; cls < plan->classes.size(); ++cls)
         if (int rc = launch_class(plan, tn, plan->classes[cls], base + sl.first[cls], sl.count[cls], pt, stream)) return rc;
     return RESHARD_OK;

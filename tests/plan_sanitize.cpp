@@ -106,7 +106,7 @@ int main() {
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 3), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 2, 1), tn, false);
-        bad += run(spec(1, 4, 64, 4, 4, 8, 0, 64, 0, 1, 512, 8, 0, 2), lay(TR, 1, 1, 512), lay(GEN, 1, 1, 1), tn, false);
+        bad += run(spec(1, 4, 64, 4, 4, 8, 0, 64, 0, 1, 512, 8, 0, 2), lay(TR, 1, 1, 512), lay(GEN, 1, 1, 1), tn, true);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, 0), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, -1, -1, 1, 0, 0, 1000), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(1, 2, 32, 4, 4, 8, 0, 48, 0, 1, 4, 24, 1, 2), lay(TR, 4, 1, 2, 1, -1, -1, 1, 0, 0, 0, 2), lay(GEN, 2, 1, 1), tn, false);

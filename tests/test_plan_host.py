@@ -495,3 +495,35 @@ def test_a_plain_c_client_sees_what_the_binding_sees(tmp_path):
     assert got["tensors"] == [[str(len(plan.tensors(1)))]]
     assert got["eq3"] == [["8000000000.0"]]  # 2 * (8e9 / 4 + 4e9 / 2)
     assert got["version"][0][0] == "reshard"
+
+
+def test_many_source_buffers_few_of_them_used():
+    """The buffer limit counts the buffers a plan touches, not the ranks of the layouts: 512 expert
+    ranks on the training side, of which one generation rank of eight reads 64 (plus the dense one)."""
+    spec = make_spec(family="moe_gqa", L=2, H=32, nq=4, nkv=4, d=8, V=64, E=512, Ie=8)
+    src = make_layout(kind="train", ep=512, expert_layout="grouped")
+    dst = make_layout(kind="gen", ep=8, ep_filter=3)
+    plan = Plan(spec, src, dst)
+    S, D = locate.Layout(spec, src), locate.Layout(spec, dst)
+    assert len(plan.buf_bytes(0)) == 513 and sum(plan.buf_used(0)) == 65
+    assert plan.buf_used(0) == [i == 0 or 1 + 3 * 64 <= i < 1 + 4 * 64 for i in range(513)]
+    rng = np.random.default_rng(5)
+    srcb = [rng.integers(0, 256, size=n, dtype=np.uint8) for n in S.buf_bytes]
+    for via in ("descs", "tiles"):
+        got = [np.full(n, SENT, dtype=np.uint8) for n in D.buf_bytes]
+        cnt = [np.zeros(n, dtype=np.int32) for n in D.buf_bytes]
+        if via == "descs":
+            run_descs(plan.descs(), srcb, got, cnt)
+        else:
+            run_tiles(plan.tiles(), srcb, got, cnt)
+        want = [np.full(n // 2, 0xA5A5, dtype=np.uint16) if D.buffer_used(b) else None for b, n in enumerate(D.buf_bytes)]
+        fast.reshard(spec, src, dst, [x.view(np.uint16) for x in srcb], want, threads=2)
+        for b, w in enumerate(want):
+            if w is None:
+                assert not cnt[b].any()
+            else:
+                assert np.array_equal(got[b].view(np.uint16), w), (via, b)
+    # without the filter every one of the 513 source buffers is read: over the limit
+    with pytest.raises(ReshardError) as e:
+        Plan(spec, src, make_layout(kind="gen", ep=8))
+    assert e.value.code == binding.ERR_UNSUPPORTED
