@@ -527,3 +527,37 @@ def test_many_source_buffers_few_of_them_used():
     with pytest.raises(ReshardError) as e:
         Plan(spec, src, make_layout(kind="gen", ep=8))
     assert e.value.code == binding.ERR_UNSUPPORTED
+
+
+def test_plans_can_be_built_from_several_threads_at_once():
+    """Plan creation keeps no shared mutable state besides the tuning (read under a lock), and the
+    error message is per thread: eight threads build different plans, half of them failing on
+    purpose, and each sees its own result and its own message."""
+    import threading
+
+    names = sorted(TINY)
+    want = {n: Plan(TINY[n]["spec"], TINY[n]["src"], TINY[n]["dst"]).descs() for n in names}
+    out = {}
+
+    def work(k):
+        res = []
+        for rep in range(6):
+            n = names[(k + rep) % len(names)]
+            if k % 2:
+                bad = dict(TINY[n]["src"], tp=7)  # no tiny shape has a head count divisible by 7
+                try:
+                    Plan(TINY[n]["spec"], bad, TINY[n]["dst"])
+                    res.append("no error")
+                except ReshardError as e:
+                    res.append((e.code, "tp" in str(e)))
+            else:
+                res.append(Plan(TINY[n]["spec"], TINY[n]["src"], TINY[n]["dst"]).descs() == want[n])
+        out[k] = res
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    for k in range(8):
+        assert out[k] == ([(binding.ERR_UNSUPPORTED, True)] * 6 if k % 2 else [True] * 6), (k, out[k])
