@@ -165,8 +165,9 @@ typedef struct reshard_desc {
  * kind 0: `rows` rows of `row_units` vectors of `vec_bytes` bytes each, row pitches as given.
  * kind 1: transposing tile of `rows` source rows x `row_units` elements of `vec_bytes` bytes:
  *     dst[dst_off + k*dst_stride + i*vec_bytes] = src[src_off + i*src_stride + k*vec_bytes]
- * tile_class: 0 copy kernel, 1 register-transpose kernel (tuned shape), 2 register-transpose
- * kernel (64 x 64), 3 generic transpose kernel.
+ * tile_class: 0 copy kernel; 1 register-transpose kernel, a whole tile of the plan's preferred
+ * shape; 2 register-transpose kernel, a whole tile of another shape the kernel is built for
+ * (rows x row_units says which); 3 generic transpose kernel (at most 64 x 64, any extent).
  */
 typedef struct reshard_tile {
     int32_t src_buf, dst_buf;
@@ -286,8 +287,9 @@ int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshard_desc *out
 int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshard_tile *out);
 
 /*
- * Step "select and copy", run time: one asynchronous kernel launch on `stream`
- * that fills every used destination buffer from the source buffers.
+ * Step "select and copy", run time: asynchronous kernel launches on `stream` (one for the
+ * strided copies, one per transposing tile shape in use; three or fewer for most plans, a
+ * dozen at most) that fill every used destination buffer from the source buffers.
  * src_ptrs[num_src_bufs], dst_ptrs[num_dst_bufs]: device pointers, each aligned to
  * 256 bytes and at least buf_bytes long; NULL allowed only where used == 0.  The
  * two sets must not overlap.  The memory stays caller-owned and must remain valid
