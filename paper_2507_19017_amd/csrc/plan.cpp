@@ -475,13 +475,15 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
     };
     auto fits32 = [](int64_t v) { return v >= 0 && v <= 0xFFFFFFFFll; };
     for (const reshard_desc &d : descs) {
-        if (!fits32(d.src_stride) || !fits32(d.dst_stride))
+        // a single row (a contiguous run of any length) has no pitch
+        const bool pitched = d.rows > 1 || d.kind == 1;
+        if (pitched && (!fits32(d.src_stride) || !fits32(d.dst_stride)))
             return fail(RESHARD_ERR_UNSUPPORTED, "a row pitch exceeds 4 GiB");
         Tile t{};
         t.src_buf = uint16_t(d.src_buf);
         t.dst_buf = uint16_t(num_src_bufs + d.dst_buf);
-        t.src_stride = uint32_t(d.src_stride);
-        t.dst_stride = uint32_t(d.dst_stride);
+        t.src_stride = pitched ? uint32_t(d.src_stride) : 0;
+        t.dst_stride = pitched ? uint32_t(d.dst_stride) : 0;
         if (d.kind == 1) {
             int lg = 0;
             while ((1 << lg) < d.elem_bytes) ++lg;

@@ -103,6 +103,9 @@ int main() {
                        lay(GEN, 2, 1, 1, 0, -1, -1, 1, 0, 0, 54), tn, true);
         }
         // invalid requests must be refused, not crash
+        // rows just under the 4 GiB pitch limit (64-bit offsets in every tile), and just over it
+        bad += run(spec(0, 1, 8, 2, 2, 8, (1 << 29) - 8, 8, 0, 1, 0, 0, 0, 8), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, true);
+        bad += run(spec(0, 1, 8, 2, 2, 8, 1 << 29, 8, 0, 1, 0, 0, 0, 8), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 3), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, false);
         bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 2, 1), tn, false);

@@ -497,6 +497,20 @@ def test_a_plain_c_client_sees_what_the_binding_sees(tmp_path):
     assert got["version"][0][0] == "reshard"
 
 
+def test_row_pitch_limit():
+    """Row pitches are 32-bit in the tile records: 4 GiB and more is refused, just under it is planned
+    with 64-bit offsets (the sanitizer build walks every tile of the same case against its buffer)."""
+    under = make_spec(family="dense_gqa", L=1, H=8, nq=2, nkv=2, d=8, I=(1 << 29) - 8, V=8, elem_bytes=8)
+    plan = Plan(under, make_layout(kind="train", tp=2), make_layout(kind="gen", tp=1))
+    down = [d for d in plan.descs() if d["dst_stride"] == ((1 << 29) - 8) * 8]
+    assert down and all(d["src_stride"] * 2 == d["dst_stride"] for d in down)
+    assert max(t["dst_off"] + (t["rows"] - 1) * t["dst_stride"] for t in plan.tiles()[-64:]) > 1 << 33
+    over = dict(under, I=1 << 29)
+    with pytest.raises(ReshardError) as e:
+        Plan(over, make_layout(kind="train", tp=2), make_layout(kind="gen", tp=1))
+    assert e.value.code == binding.ERR_UNSUPPORTED and "4 GiB" in str(e.value)
+
+
 def test_many_source_buffers_few_of_them_used():
     """The buffer limit counts the buffers a plan touches, not the ranks of the layouts: 512 expert
     ranks on the training side, of which one generation rank of eight reads 64 (plus the dense one)."""
