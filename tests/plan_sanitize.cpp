@@ -29,8 +29,9 @@ static reshard_layout lay(int kind, int tp, int pp, int ep, int grouped = 0, int
     return l;
 }
 
+// expect: 1 must succeed, 0 must be refused, -1 either (only the sanitizers and the invariants judge)
 static int run(const reshard_model_spec &s, const reshard_layout &a, const reshard_layout &b, const Tuning &tn,
-               bool expect_ok) {
+               int expect) {
     Side S, D;
     std::vector<reshard_desc> descs;
     int rc = build_side(s, a, true, S);
@@ -40,8 +41,8 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
     if (!transpose_shape_ok(s.elem_bytes, fr, fc)) transpose_default_shape(s.elem_bytes, fr, fc);
     std::vector<TileClass> classes;
     if (!rc) rc = cut_tiles(descs, int(S.buf_bytes.size()), tn, fr, fc, classes);
-    if ((rc == 0) != expect_ok) {
-        std::printf("unexpected result %d (expected %s)\n", rc, expect_ok ? "ok" : "an error");
+    if (expect >= 0 && (rc == 0) != (expect == 1)) {
+        std::printf("unexpected result %d (expected %s)\n", rc, expect ? "ok" : "an error");
         return 1;
     }
     if (rc) return 0;
@@ -78,42 +79,76 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
     return 0;
 }
 
-int main() {
+// Cases from a file, one per line: expect, then the 20 spec fields after struct_size in header order,
+// then the 12 fields of the source layout and of the destination layout after struct_size.
+static int run_file(const char *path, const Tuning &tn) {
+    std::FILE *f = std::fopen(path, "r");
+    if (!f) { std::printf("cannot open %s\n", path); return 1; }
+    int bad = 0, n = 0, v[45];
+    for (;;) {
+        int got = 0;
+        while (got < 45 && std::fscanf(f, "%d", &v[got]) == 1) ++got;
+        if (got < 45) break;
+        reshard_model_spec s{};
+        s.struct_size = sizeof s;
+        int32_t *sp = &s.family;
+        for (int k = 0; k < 20; ++k) sp[k] = v[1 + k];
+        reshard_layout l[2]{};
+        for (int side = 0; side < 2; ++side) {
+            l[side].struct_size = sizeof(reshard_layout);
+            int32_t *lp = &l[side].kind;
+            for (int k = 0; k < 12; ++k) lp[k] = v[21 + 12 * side + k];
+        }
+        bad += run(s, l[0], l[1], tn, v[0]);
+        ++n;
+    }
+    std::fclose(f);
+    std::printf("%d cases from file\n", n);
+    return bad;
+}
+static_assert(sizeof(reshard_model_spec) == 21 * 4 && sizeof(reshard_layout) == 13 * 4, "field counts used by run_file");
+
+int main(int argc, char **argv) {
     Tuning def;
     Tuning small; small.tile_bytes = 4096; small.transpose_rows = 64; small.transpose_cols = 128;
     int bad = 0;
+    if (argc > 1) {
+        bad = run_file(argv[1], def) + run_file(argv[1], small);
+        std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
+        return bad ? 1 : 0;
+    }
     const int TR = RESHARD_TRAIN, GEN = RESHARD_GEN;
     for (const Tuning &tn : {def, small}) {
         // the task's shapes
-        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, true);
-        bad += run(spec(0, 28, 3584, 28, 4, 128, 18944, 152064, 1, 1, 0, 0, 0, 2), lay(TR, 4, 2, 1), lay(GEN, 2, 1, 1), tn, true);
-        bad += run(spec(0, 64, 5120, 40, 8, 128, 27648, 152064, 1, 1, 0, 0, 0, 2), lay(TR, 8, 4, 1), lay(GEN, 4, 1, 1), tn, true);
-        bad += run(spec(1, 48, 2048, 32, 4, 128, 0, 151936, 0, 1, 128, 768, 0, 2), lay(TR, 1, 2, 8, 1), lay(GEN, 2, 1, 4), tn, true);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, 1);
+        bad += run(spec(0, 28, 3584, 28, 4, 128, 18944, 152064, 1, 1, 0, 0, 0, 2), lay(TR, 4, 2, 1), lay(GEN, 2, 1, 1), tn, 1);
+        bad += run(spec(0, 64, 5120, 40, 8, 128, 27648, 152064, 1, 1, 0, 0, 0, 2), lay(TR, 8, 4, 1), lay(GEN, 4, 1, 1), tn, 1);
+        bad += run(spec(1, 48, 2048, 32, 4, 128, 0, 151936, 0, 1, 128, 768, 0, 2), lay(TR, 1, 2, 8, 1), lay(GEN, 2, 1, 4), tn, 1);
         // ragged and odd shapes, every element size, filters, the way back, the layout options
         for (int eb : {1, 2, 4, 8}) {
-            bad += run(spec(0, 4, 48, 8, 4, 8, 40, 64, 1, 1, 0, 0, 0, eb), lay(TR, 4, 2, 1), lay(GEN, 2, 1, 1), tn, true);
-            bad += run(spec(1, 2, 320, 4, 2, 16, 0, 64, 0, 1, 4, 200, 1, eb), lay(TR, 1, 1, 2, 1), lay(GEN, 2, 1, 1), tn, true);
-            bad += run(spec(1, 2, 320, 4, 2, 16, 0, 64, 0, 1, 4, 200, 1, eb), lay(GEN, 2, 1, 1), lay(TR, 1, 1, 2, 1), tn, true);
-            bad += run(spec(0, 8, 48, 8, 2, 8, 40, 64, 1, 1, 0, 0, 0, eb, 1), lay(TR, 4, 2, 1, 0, -1, -1, 2), lay(GEN, 8, 1, 1), tn, true);
-            bad += run(spec(0, 8, 32, 8, 2, 8, 24, 48, 0, 1, 0, 0, 0, eb), lay(TR, 4, 4, 1, 0, -1, -1, 1, 3, 1), lay(GEN, 2, 1, 1, 0, 1), tn, true);
-            bad += run(spec(0, 2, 7, 3, 3, 5, 9, 6, 1, 1, 0, 0, 0, 1), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, true);
+            bad += run(spec(0, 4, 48, 8, 4, 8, 40, 64, 1, 1, 0, 0, 0, eb), lay(TR, 4, 2, 1), lay(GEN, 2, 1, 1), tn, 1);
+            bad += run(spec(1, 2, 320, 4, 2, 16, 0, 64, 0, 1, 4, 200, 1, eb), lay(TR, 1, 1, 2, 1), lay(GEN, 2, 1, 1), tn, 1);
+            bad += run(spec(1, 2, 320, 4, 2, 16, 0, 64, 0, 1, 4, 200, 1, eb), lay(GEN, 2, 1, 1), lay(TR, 1, 1, 2, 1), tn, 1);
+            bad += run(spec(0, 8, 48, 8, 2, 8, 40, 64, 1, 1, 0, 0, 0, eb, 1), lay(TR, 4, 2, 1, 0, -1, -1, 2), lay(GEN, 8, 1, 1), tn, 1);
+            bad += run(spec(0, 8, 32, 8, 2, 8, 24, 48, 0, 1, 0, 0, 0, eb), lay(TR, 4, 4, 1, 0, -1, -1, 1, 3, 1), lay(GEN, 2, 1, 1, 0, 1), tn, 1);
+            bad += run(spec(0, 2, 7, 3, 3, 5, 9, 6, 1, 1, 0, 0, 0, 1), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, 1);
             bad += run(spec(1, 2, 32, 4, 4, 8, 0, 48, 0, 1, 4, 24, 1, eb), lay(TR, 4, 1, 2, 1, -1, -1, 1, 0, 0, 0, 4),
-                       lay(GEN, 2, 1, 1, 0, 1, -1, 1, 0, 0, 0, 2), tn, true);
+                       lay(GEN, 2, 1, 1, 0, 1, -1, 1, 0, 0, 0, 2), tn, 1);
             bad += run(spec(0, 2, 24, 4, 4, 8, 24, 50, 0, 1, 0, 0, 0, eb), lay(TR, 4, 2, 1, 0, -1, -1, 1, 0, 0, 64),
-                       lay(GEN, 2, 1, 1, 0, -1, -1, 1, 0, 0, 54), tn, true);
+                       lay(GEN, 2, 1, 1, 0, -1, -1, 1, 0, 0, 54), tn, 1);
         }
         // invalid requests must be refused, not crash
         // rows just under the 4 GiB pitch limit (64-bit offsets in every tile), and just over it
-        bad += run(spec(0, 1, 8, 2, 2, 8, (1 << 29) - 8, 8, 0, 1, 0, 0, 0, 8), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, true);
-        bad += run(spec(0, 1, 8, 2, 2, 8, 1 << 29, 8, 0, 1, 0, 0, 0, 8), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, false);
-        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, false);
-        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 3), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, false);
-        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 2, 1), tn, false);
-        bad += run(spec(1, 4, 64, 4, 4, 8, 0, 64, 0, 1, 512, 8, 0, 2), lay(TR, 1, 1, 512), lay(GEN, 1, 1, 1), tn, true);
-        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, 0), lay(GEN, 1, 1, 1), tn, false);
-        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, -1, -1, 1, 0, 0, 1000), lay(GEN, 1, 1, 1), tn, false);
-        bad += run(spec(1, 2, 32, 4, 4, 8, 0, 48, 0, 1, 4, 24, 1, 2), lay(TR, 4, 1, 2, 1, -1, -1, 1, 0, 0, 0, 2), lay(GEN, 2, 1, 1), tn, false);
-        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, -1, -1, 1, 0, 0, 1025), lay(GEN, 1, 1, 1), tn, false);
+        bad += run(spec(0, 1, 8, 2, 2, 8, (1 << 29) - 8, 8, 0, 1, 0, 0, 0, 8), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, 1);
+        bad += run(spec(0, 1, 8, 2, 2, 8, 1 << 29, 8, 0, 1, 0, 0, 0, 8), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, 0);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 3, 1, 1), lay(GEN, 1, 1, 1), tn, 0);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 3), lay(TR, 2, 1, 1), lay(GEN, 1, 1, 1), tn, 0);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1), lay(GEN, 1, 2, 1), tn, 0);
+        bad += run(spec(1, 4, 64, 4, 4, 8, 0, 64, 0, 1, 512, 8, 0, 2), lay(TR, 1, 1, 512), lay(GEN, 1, 1, 1), tn, 1);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, 0), lay(GEN, 1, 1, 1), tn, 0);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, -1, -1, 1, 0, 0, 1000), lay(GEN, 1, 1, 1), tn, 0);
+        bad += run(spec(1, 2, 32, 4, 4, 8, 0, 48, 0, 1, 4, 24, 1, 2), lay(TR, 4, 1, 2, 1, -1, -1, 1, 0, 0, 0, 2), lay(GEN, 2, 1, 1), tn, 0);
+        bad += run(spec(0, 2, 256, 4, 2, 64, 688, 1024, 0, 1, 0, 0, 0, 2), lay(TR, 2, 1, 1, 0, -1, -1, 1, 0, 0, 1025), lay(GEN, 1, 1, 1), tn, 0);
     }
     std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
     return bad ? 1 : 0;

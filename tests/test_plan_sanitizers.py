@@ -13,8 +13,19 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-@pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
-def test_plan_builder_is_clean_under_asan_and_ubsan(tmp_path):
+SPEC_FIELDS = ("family", "L", "H", "nq", "nkv", "d", "I", "V", "qkv_bias", "has_embeddings", "E", "Ie", "n_shared",
+               "q_lora", "kv_lora", "nope", "rope", "v_dim", "elem_bytes", "tied_embeddings")
+LAYOUT_FIELDS = ("kind", "tp", "pp", "ep", "expert_layout", "tp_filter", "ep_filter", "vpp", "first_stage_layers",
+                 "last_stage_layers", "vocab_padded", "etp")
+CODES = {"dense_gqa": 0, "moe_gqa": 1, "moe_mla": 2, "train": 0, "gen": 1, "per_expert": 0, "grouped": 1}
+
+
+def case_line(expect, spec, src, dst):
+    vals = [expect] + [spec[k] for k in SPEC_FIELDS] + [src[k] for k in LAYOUT_FIELDS] + [dst[k] for k in LAYOUT_FIELDS]
+    return " ".join(str(CODES.get(v, v)) for v in vals)
+
+
+def build(tmp_path):
     exe = str(tmp_path / "plan_sanitize")
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
            "-static-libasan", "-static-libubsan",  # no dependence on the order of preloaded libraries
@@ -24,6 +35,40 @@ def test_plan_builder_is_clean_under_asan_and_ubsan(tmp_path):
     subprocess.run(cmd, check=True, capture_output=True, text=True)
     env = dict(os.environ)
     env["ASAN_OPTIONS"] = "detect_leaks=1:abort_on_error=0"
+    return exe, env
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
+def test_random_and_mutated_cases_under_asan_and_ubsan(tmp_path):
+    """The random workloads (which must be accepted) and mutations of them (one field of the
+    shape or of a layout replaced by a random small, zero or negative value: accepted or refused,
+    never a crash, an overflow or a tile outside its buffer)."""
+    import random
+
+    from synth_inputs import random_case
+
+    lines = []
+    for seed in range(120):
+        w = random_case(seed, 1 if seed < 96 else 4)
+        lines.append(case_line(1, w["spec"], w["src"], w["dst"]))
+        r = random.Random(seed)
+        for _ in range(4):
+            spec, src, dst = dict(w["spec"]), dict(w["src"]), dict(w["dst"])
+            target = r.choice([spec, spec, src, dst])
+            key = r.choice([k for k in target if k not in ("family", "kind", "expert_layout")])
+            target[key] = r.choice([-1, 0, 1, 2, 3, 5, 7, 8, 12, 16, 33, 64])
+            lines.append(case_line(-1, spec, src, dst))
+    path = tmp_path / "cases.txt"
+    path.write_text("\n".join(lines) + "\n")
+    exe, env = build(tmp_path)
+    res = subprocess.run([exe, str(path)], capture_output=True, text=True, env=env, timeout=600)
+    assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
+    assert "600 cases from file" in res.stdout and res.stdout.strip().endswith("ok")
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
+def test_plan_builder_is_clean_under_asan_and_ubsan(tmp_path):
+    exe, env = build(tmp_path)
     res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert res.returncode == 0, res.stdout + res.stderr
     assert res.stdout.strip().endswith("ok")
