@@ -37,6 +37,8 @@ def parse():
                          "copies with shader kernels instead of the DMA engines, which starves the repack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-step timings on stderr")
+    ap.add_argument("--framework-baseline", action="store_true",
+                    help="also time the same plan as one torch strided copy per descriptor (a GPU-side comparison)")
     ap.add_argument("--streaming", action="store_true",
                     help="after the timed steps, also run the streaming flow once (one source buffer resident at a "
                          "time) and report its peak HBM")
@@ -211,6 +213,48 @@ def main():
         torch.cuda.synchronize()
         assert check == [None if s is None else int(s[::4099].to(torch.int64).sum()) for s in src], "swap round trip changed the weights"
 
+    framework = None
+    if a.framework_baseline:
+        # What "select and copy" looks like with framework tensor operations: one strided
+        # tensor copy per descriptor of the same plan (torch.as_strided views of the flat
+        # buffers, Tensor.copy_), on the same buffers.  A GPU-side comparison only: the
+        # product path never runs it.
+        eb = wl["spec"]["elem_bytes"]
+        assert eb == 2, "the framework baseline views the buffers as 16-bit words"
+        views = []
+        for d in plan.descs():
+            sb, db = src[d["src_buf"]], dst[d["dst_buf"]]
+            cols = d["row_bytes"] // 2
+            sv = torch.as_strided(sb, (d["rows"], cols), (d["src_stride"] // 2, 1), d["src_off"] // 2)
+            if d["kind"] == 0:
+                dv = torch.as_strided(db, (d["rows"], cols), (d["dst_stride"] // 2, 1), d["dst_off"] // 2)
+            else:  # transposing: element (i, k) lands at row k, column i
+                dv = torch.as_strided(db, (d["rows"], cols), (1, d["dst_stride"] // 2), d["dst_off"] // 2)
+            views.append((dv, sv))
+        ref = [None if t is None else t.clone() for t in dst]
+        for t in dst:
+            if t is not None:
+                t.zero_()
+
+        def run_views():
+            for dv, sv in views:
+                dv.copy_(sv)
+
+        run_views()
+        torch.cuda.synchronize()
+        same = all((x is None and y is None) or torch.equal(x, y) for x, y in zip(ref, dst))
+        del ref
+        times = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run_views()
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+        best = min(times)
+        framework = {"kind": "one torch strided copy_ per descriptor", "copies": len(views), "ms": round(best * 1e3, 3),
+                     "GBps": round(2 * info["bytes_moved"] / best / 1e9, 1), "same_bits_as_the_library": same}
+
     streaming = None
     if a.streaming:
         # the gathered shards "arrive" one buffer at a time: repack what reads it, swap it out, drop it
@@ -325,6 +369,8 @@ def main():
             out["swap"]["in_frac_of_link"] = round(src_bytes / si / 1e9 / link["h2d"], 3)
     if streaming:
         out["streaming"] = streaming
+    if framework:
+        out["framework_baseline"] = framework
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, plan, src)
     print(json.dumps(out))
