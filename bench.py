@@ -43,7 +43,7 @@ def parse():
                     help="after the timed steps, also run the streaming flow once (one source buffer resident at a "
                          "time) and report its peak HBM")
     ap.add_argument("--no-link-probe", action="store_true")
-    ap.add_argument("--tuning", default="", help="e.g. tile_bytes=65536,unroll=8")
+    ap.add_argument("--tuning", default="", help="e.g. tile_bytes=65536,unroll=8 (default 32768, 2)")
     return ap.parse_args()
 
 

@@ -210,10 +210,10 @@ typedef struct reshard_mem_stats_t {
 
 /* Knobs of the repack kernel; zero fields keep the built-in default. */
 typedef struct reshard_tuning {
-    int32_t tile_bytes;     /* bytes of work per tile (power of two, 4 KiB .. 512 KiB; default 64 KiB) */
+    int32_t tile_bytes;     /* bytes of work per tile (power of two, 4 KiB .. 512 KiB; default 32 KiB) */
     int32_t block_threads;  /* 64, 128, 256, 512 or 1024 (default 1024) */
     int32_t blocks_per_cu;  /* 0 (default): one tile per workgroup; n > 0: persistent grid of n per CU */
-    int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4, 8 or 16 (default 8) */
+    int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4, 8 or 16 (default 2) */
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
                                barrier between a tile's load burst and its store burst, bit 3: each XCD
                                walks a contiguous eighth of the tile table (default 15); -1 = none */

@@ -61,10 +61,10 @@ constexpr int kMaxLayoutBuffers = 16384;  // buffers of one layout, used or not 
 constexpr int kTransposeDim = 64;     // transposing tiles are at most 64 x 64 elements
 
 struct Tuning {
-    int tile_bytes = 64 * 1024;   // one half-filled round of block_threads * unroll * 16 bytes
+    int tile_bytes = 32 * 1024;   // one round of block_threads * unroll * 16 bytes
     int block_threads = 1024;
     int blocks_per_cu = 0;        // 0: one tile per workgroup; > 0: persistent grid
-    int unroll = 8;
+    int unroll = 2;               // 22 VGPRs: two 1024-lane workgroups fit a compute unit (8 takes 69: one)
     int flags = 15;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
                                   // bit 3: each XCD walks a contiguous eighth of the tile table
     int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;

@@ -437,15 +437,15 @@ def test_state_machine_errors_without_a_device():
 def test_tuning_is_validated():
     set_tuning()
     base = get_tuning()
-    assert base == dict(tile_bytes=65536, block_threads=1024, blocks_per_cu=0, unroll=8, flags=15, transpose_rows=0,
+    assert base == dict(tile_bytes=32768, block_threads=1024, blocks_per_cu=0, unroll=2, flags=15, transpose_rows=0,
                         transpose_cols=0)
-    set_tuning(tile_bytes=16384, unroll=4)
-    assert get_tuning()["tile_bytes"] == 16384 and get_tuning()["unroll"] == 4
+    set_tuning(tile_bytes=8192, unroll=4)
+    assert get_tuning()["tile_bytes"] == 8192 and get_tuning()["unroll"] == 4
     w = WORKLOADS["C1"]
-    n16 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
+    n8 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
     set_tuning()
-    n64 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
-    assert n16 > 3.5 * n64
+    n32 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
+    assert n8 > 3.5 * n32
     for bad in (dict(tile_bytes=1000), dict(block_threads=96), dict(unroll=3), dict(blocks_per_cu=100)):
         with pytest.raises(ReshardError):
             set_tuning(**bad)
