@@ -5,7 +5,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from oracle import fast, locate
+from oracle import fast
 from synth_inputs import BF16_ONE, fill_buffer
 
 SENT16 = -23131  # 0xA5A5 as int16

@@ -6,8 +6,8 @@ import pytest
 import torch
 
 import gpu_util as G
-from oracle import fast, locate
-from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, get_tuning, set_tuning
+from oracle import locate
+from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, set_tuning
 from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout, make_spec, random_case
 
 pytestmark = pytest.mark.gpu
