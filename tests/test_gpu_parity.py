@@ -564,6 +564,28 @@ def test_largest_shapes_whole_output_and_sampled_pairs(name):
     assert (plan.info()["num_transpose_tiles"] > 0) == (wl["src"]["expert_layout"] == "grouped")
 
 
+def test_a_table_too_long_for_one_launch_goes_out_in_slices():
+    """4 KiB tiles on the 26 GB plan: 6.4 million workgroups of 1024 lanes, more lanes than one
+    launch can have, so the copy class is launched in two slices; same bits as the default plan."""
+    wl = WORKLOADS["C4"]
+    print("case C4 sliced launches", flush=True)
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    src = G.device_sources(plan, wl, "raw16")
+    one = G.device_destinations(plan)
+    plan.execute(G.ptrs(src), G.ptrs(one), G.stream_handle())
+    try:
+        set_tuning(tile_bytes=4096)
+        small = Plan(wl["spec"], wl["src"], wl["dst"])
+    finally:
+        set_tuning()
+    assert small.info()["num_tiles"] * 1024 > 1 << 32
+    two = G.device_destinations(small)
+    small.execute(G.ptrs(src), G.ptrs(two), G.stream_handle())
+    torch.cuda.synchronize()
+    for a, b in zip(one, two):
+        assert (a is None and b is None) or torch.equal(a, b)
+
+
 def test_c4_deepseek_shape_share_whole_output():
     print("case C4 full", flush=True)
     plan, src, dst = run_case(WORKLOADS["C4"], "normal")
