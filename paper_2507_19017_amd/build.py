@@ -32,5 +32,26 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(ROOT, "tests", "c_abi_gpu_client.c")
+C_CLIENT = os.path.join(ROOT, "tests", "c_abi_gpu_client")
+
+
+def build_c_client() -> str:
+    """The plain-C GPU client used by the GPU tests (gcc, C99; links the library and the HIP runtime)."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    tmp = C_CLIENT + ".tmp%d" % os.getpid()
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(rocm, "include"),
+           C_CLIENT_SRC, "-o", tmp, "-L" + HERE, "-l:libreshard.so", "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_2507_19017_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+        raise RuntimeError("gcc failed building the C client")
+    os.replace(tmp, C_CLIENT)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_client())

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import gpu_util as G
-from oracle import locate
+from oracle import fast, locate
 from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, set_tuning
 from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout, make_spec, random_case
 
@@ -236,6 +236,33 @@ def test_execute_on_a_side_stream_and_inside_a_hip_graph():
         for a, b in zip(dst, eager):
             assert torch.equal(a, b), f"replay {replay}"
         G.assert_equal_buffers(dst, G.oracle_destinations(wl, G.to_host(src), 4), f"replay {replay}")
+
+
+def test_a_plain_c_program_drives_the_library_on_the_gpu(tmp_path):
+    """No Python and no tensor framework in the client: a C99 program allocates device memory with
+    the HIP runtime, reshards the toy workload, swaps the sources out, frees them, allocates new
+    ones and swaps back in.  Its destination buffer must equal the oracle's on the same inputs and
+    the sources must return bit for bit."""
+    import os
+    import subprocess
+
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi_gpu_client")
+    assert os.path.exists(exe), "tests/c_abi_gpu_client is missing: run __graft_entry__.build() first"
+    out = str(tmp_path / "c_client.bin")
+    res = subprocess.run([exe, out], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, res.stdout + res.stderr
+    wl = WORKLOADS["C0"]
+    sizes_s, sizes_d = fast.buffer_sizes(wl["spec"], wl["src"]), fast.buffer_sizes(wl["spec"], wl["dst"])
+    assert res.stdout.split() == ["ok", str(sizes_d[0]), str(sizes_s[0]), str(sizes_s[1])]
+    src = [(((np.arange(n // 2, dtype=np.uint64) * np.uint64(2654435761) + np.uint64(b * 40503)) >> np.uint64(9))
+            & np.uint64(0xFFFF)).astype(np.uint16).view(np.int16) for b, n in enumerate(sizes_s)]
+    want = [np.full(sizes_d[0] // 2, G.SENT16, dtype=np.int16)]
+    fast.reshard(wl["spec"], wl["src"], wl["dst"], src, want, threads=2)
+    got = np.fromfile(out, dtype=np.int16)
+    nd = sizes_d[0] // 2
+    assert got.size == nd + sum(sizes_s) // 2
+    assert np.array_equal(got[:nd], want[0])
+    assert np.array_equal(got[nd:nd + sizes_s[0] // 2], src[0]) and np.array_equal(got[nd + sizes_s[0] // 2:], src[1])
 
 
 # ------------------------------------------------------------- streaming ----
