@@ -189,9 +189,135 @@ static int flows(int eb) {
     return 0;
 }
 
+// Random sequences of calls against a model of the residency rules written from reshard.h: every
+// return code, every buffer state and the ledger must match the model after every call.
+static int random_calls(unsigned seed, int steps) {
+    const reshard_model_spec spec = moe_spec(2);
+    const reshard_layout src = lay(RESHARD_TRAIN, 2, 1, 2, 0), dst = lay(RESHARD_GEN, 1, 1, 1, 0);
+    reshard_plan *plan = nullptr;
+    REQUIRE(reshard_plan_create(&spec, &src, &dst, &plan) == RESHARD_OK);
+    const int ns = reshard_plan_num_bufs(plan, 0);
+    Buffers A, B, D;  // two device homes per source buffer, one destination set
+    A.make(plan, 0, -1);
+    B.make(plan, 0, 0);
+    D.make(plan, 1, 0xA5);
+    enum { UNB = RESHARD_SRC_UNBOUND, RES = RESHARD_SRC_RESIDENT, OUT = RESHARD_SRC_SWAPPING_OUT, HOST = RESHARD_SRC_ON_HOST,
+           REL = RESHARD_SRC_RELEASED, IN = RESHARD_SRC_SWAPPING_IN, MIX = RESHARD_SRC_MIXED };
+    std::vector<int> st(size_t(ns), UNB);
+    std::vector<const void *> ptr(size_t(ns), nullptr);
+    bool swapped_once = false;
+    unsigned r = seed * 2654435761u + 12345u;
+    auto rnd = [&](unsigned n) { r = r * 1664525u + 1013904223u; return (r >> 8) % n; };
+    auto plan_state = [&] {
+        int c = st[0];
+        for (int s_ : st) if (s_ != c) return int(MIX);
+        return c;
+    };
+    auto all = [&](int from, int to) { for (int &s_ : st) if (s_ == from) s_ = to; };
+    for (int step = 0; step < steps; ++step) {
+        const int op = int(rnd(13)), i = int(rnd(unsigned(ns)));
+        const Buffers &home = rnd(2) ? A : B;
+        std::vector<const void *> sp(home.p.begin(), home.p.end());
+        const int ps = plan_state();
+        int want = RESHARD_OK, got = RESHARD_OK;
+        switch (op) {
+            case 0: {  // execute
+                bool same = true;
+                for (int k = 0; k < ns; ++k) same = same && ptr[size_t(k)] == sp[size_t(k)];
+                if (!(ps == UNB || ps == RES || (ps == OUT && same))) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_execute(plan, sp.data(), D.p.data(), nullptr);
+                if (want == RESHARD_OK) {
+                    ptr = sp;
+                    if (ps != OUT) all(ps, RES);
+                }
+                break;
+            }
+            case 1:  // execute_source
+                if (st[size_t(i)] != UNB && st[size_t(i)] != RES) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_execute_source(plan, i, sp[size_t(i)], D.p.data(), nullptr);
+                if (want == RESHARD_OK) { ptr[size_t(i)] = sp[size_t(i)]; st[size_t(i)] = RES; }
+                break;
+            case 2:
+                if (ps != RES) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_swap_out(plan, nullptr);
+                if (want == RESHARD_OK) { all(RES, OUT); swapped_once = true; }
+                break;
+            case 3:
+                if (st[size_t(i)] != RES) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_swap_out_source(plan, i, nullptr);
+                if (want == RESHARD_OK) { st[size_t(i)] = OUT; swapped_once = true; }
+                break;
+            case 4:
+                got = reshard_swap_wait(plan);
+                all(OUT, HOST);
+                all(IN, RES);
+                break;
+            case 5:
+                if (!swapped_once) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_swap_wait_buffer(plan, i, nullptr, 1);
+                if (want == RESHARD_OK) st[size_t(i)] = st[size_t(i)] == OUT ? int(HOST) : st[size_t(i)] == IN ? int(RES) : st[size_t(i)];
+                break;
+            case 6:
+                if (ps != HOST) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_mark_src_released(plan);
+                if (want == RESHARD_OK) { all(HOST, REL); std::fill(ptr.begin(), ptr.end(), nullptr); }
+                break;
+            case 7:
+                if (st[size_t(i)] != HOST) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_mark_src_buffer_released(plan, i);
+                if (want == RESHARD_OK) { st[size_t(i)] = REL; ptr[size_t(i)] = nullptr; }
+                break;
+            case 8:
+                if (!(ps == UNB || ps == RES || ps == HOST || ps == REL)) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_bind_src(plan, sp.data());
+                if (want == RESHARD_OK) { ptr = sp; all(UNB, RES); all(REL, HOST); }
+                break;
+            case 9:
+                if (ps != HOST) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_swap_in(plan, nullptr);
+                if (want == RESHARD_OK) { all(HOST, IN); swapped_once = true; }
+                break;
+            case 10: {
+                const bool give = rnd(2) != 0;
+                void *to = give ? const_cast<void *>(sp[size_t(i)]) : nullptr;
+                if ((st[size_t(i)] != HOST && st[size_t(i)] != REL) || (!give && !ptr[size_t(i)])) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_swap_in_source(plan, i, to, nullptr);
+                if (want == RESHARD_OK) { if (give) ptr[size_t(i)] = to; st[size_t(i)] = IN; swapped_once = true; }
+                break;
+            }
+            case 11:
+                if (ps != UNB && ps != RES) want = RESHARD_ERR_BAD_STATE;
+                got = reshard_release_host(plan);
+                break;
+            default:
+                got = reshard_reserve_host(plan);
+                break;
+        }
+        if (got != want) { std::printf("seed %u step %d op %d buffer %d: returned %d, model says %d (%s)\n", seed, step, op, i, got, want, reshard_last_error()); return 1; }
+        reshard_mem_stats_t ms;
+        REQUIRE(reshard_mem_stats(plan, &ms) == RESHARD_OK);
+        int64_t live = 0, released = 0;
+        for (int k = 0; k < ns; ++k) {
+            if (reshard_src_buffer_state(plan, k) != st[size_t(k)]) { std::printf("seed %u step %d op %d: buffer %d is %d, model says %d\n", seed, step, op, k, reshard_src_buffer_state(plan, k), st[size_t(k)]); return 1; }
+            const bool is_live = st[size_t(k)] == RES || st[size_t(k)] == OUT || st[size_t(k)] == HOST || st[size_t(k)] == IN;
+            if (is_live && ptr[size_t(k)]) live += A.n[size_t(k)];
+            if (st[size_t(k)] == REL) released += A.n[size_t(k)];
+        }
+        if (ms.state != plan_state() || ms.src_live != live || ms.released != released) {
+            std::printf("seed %u step %d op %d: ledger state %d live %lld released %lld, model %d %lld %lld\n", seed, step, op, ms.state,
+                        (long long)ms.src_live, (long long)ms.released, plan_state(), (long long)live, (long long)released);
+            return 1;
+        }
+    }
+    REQUIRE(reshard_plan_destroy(plan) == RESHARD_OK);
+    REQUIRE(fake_hip_host_bytes == 0);
+    return 0;
+}
+
 int main() {
     int bad = 0;
     for (int eb : {1, 2, 4, 8}) bad += flows(eb);
+    for (unsigned seed = 1; seed <= 40 && !bad; ++seed) bad += random_calls(seed, 400);
     // NULL plans and bad indices on every entry point that takes them
     bad += reshard_plan_destroy(nullptr) != RESHARD_OK;
     bad += reshard_execute(nullptr, nullptr, nullptr, nullptr) != RESHARD_ERR_INVALID_ARG;
