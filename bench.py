@@ -67,9 +67,11 @@ def cpu_baseline(wl, plan, src):
     dst = [np.zeros(n // 2, dtype=np.int16) if u else None for n, u in zip(sizes, used)]
     threads = min(fast.max_threads(), 16)
     fast.reshard(wl["spec"], wl["src"], only, host_src, dst, threads=threads)  # warm the pages
-    t0 = time.perf_counter()
-    nbytes = fast.reshard(wl["spec"], wl["src"], only, host_src, dst, threads=threads)
-    dt = time.perf_counter() - t0
+    dt = None
+    for _ in range(3):  # best of three: the runs are short
+        t0 = time.perf_counter()
+        nbytes = fast.reshard(wl["spec"], wl["src"], only, host_src, dst, threads=threads)
+        dt = min(dt or 1e30, time.perf_counter() - t0)
     dt1 = None
     if dt * threads < 40.0:  # keep the default run short: skipped where one core would need longer
         t0 = time.perf_counter()
@@ -78,7 +80,7 @@ def cpu_baseline(wl, plan, src):
     return {
         "value": round(2 * nbytes / dt / 1e9, 3), "unit": "GB/s (read+write)", "cores": threads,
         "kind": "oracle", "one_core_value": round(2 * nbytes / dt1 / 1e9, 3) if dt1 else None,
-        "sample": "%s, destination rank 0 only: %.2f GB written, one run after a page-warming run" % (wl["name"], nbytes / 1e9),
+        "sample": "%s, destination rank 0 only: %.2f GB written, best of three runs after a page-warming run" % (wl["name"], nbytes / 1e9),
     }
 
 
