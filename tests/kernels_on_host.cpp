@@ -1,0 +1,129 @@
+// Host-only driver: the REAL kernels of repack.hip, compiled for the host against
+// tests/host_simt (one host thread per lane, real barriers) and run under AddressSanitizer, on
+// small workloads that reach every kernel, tile class, element size and launch shape.  Each
+// result is compared with an interpretation of the plan's descriptor table.  Built and run by
+// tests/test_plan_sanitizers.py; test infrastructure only.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "internal.h"
+
+long fake_hip_host_limit = -1, fake_hip_host_bytes = 0, fake_hip_copies = 0;
+thread_local uint3_ threadIdx;
+uint3_ blockIdx, blockDim, gridDim;
+namespace host_simt {
+long launches = 0, blocks_run = 0;
+Pool &pool() {
+    static Pool p;
+    return p;
+}
+}  // namespace host_simt
+
+#define REQUIRE(cond) do { if (!(cond)) { std::printf("line %d: %s is false (last error: %s)\n", __LINE__, #cond, reshard_last_error()); return 1; } } while (0)
+
+static reshard_layout lay(int kind, int tp, int pp, int ep, int grouped, int etp = 1) {
+    reshard_layout l{};
+    l.struct_size = sizeof l;
+    l.kind = kind; l.tp = tp; l.pp = pp; l.ep = ep; l.expert_layout = grouped; l.tp_rank_filter = l.ep_rank_filter = -1; l.etp = etp;
+    return l;
+}
+
+static int run(const reshard_model_spec &spec, const reshard_layout &src, const reshard_layout &dst, const reshard_tuning *tn,
+               bool by_source) {
+    REQUIRE(reshard_set_tuning(tn) == RESHARD_OK);
+    reshard_plan *plan = nullptr;
+    REQUIRE(reshard_plan_create(&spec, &src, &dst, &plan) == RESHARD_OK);
+    REQUIRE(reshard_set_tuning(nullptr) == RESHARD_OK);
+    const int ns = reshard_plan_num_bufs(plan, 0), nd = reshard_plan_num_bufs(plan, 1);
+    std::vector<void *> S(size_t(ns), nullptr), D(size_t(nd), nullptr), W(size_t(nd), nullptr);
+    for (int i = 0; i < ns; ++i) {
+        if (!reshard_plan_buf_used(plan, 0, i)) continue;
+        const size_t n = size_t(reshard_plan_buf_bytes(plan, 0, i));
+        S[size_t(i)] = std::aligned_alloc(256, n);  // exact extent: one byte too far is reported
+        unsigned char *c = static_cast<unsigned char *>(S[size_t(i)]);
+        for (size_t k = 0; k < n; ++k) c[k] = (unsigned char)((k * 2654435761u + unsigned(i) * 97u) >> 11);
+    }
+    for (int j = 0; j < nd; ++j) {
+        if (!reshard_plan_buf_used(plan, 1, j)) continue;
+        const size_t n = size_t(reshard_plan_buf_bytes(plan, 1, j));
+        D[size_t(j)] = std::aligned_alloc(256, n);
+        W[size_t(j)] = std::aligned_alloc(256, n);
+        std::memset(D[size_t(j)], 0xA5, n);
+        std::memset(W[size_t(j)], 0xA5, n);
+    }
+    if (by_source) {
+        for (int i = 0; i < ns; ++i)
+            if (S[size_t(i)]) REQUIRE(reshard_execute_source(plan, i, S[size_t(i)], D.data(), nullptr) == RESHARD_OK);
+    } else {
+        std::vector<const void *> sp(S.begin(), S.end());
+        REQUIRE(reshard_execute(plan, sp.data(), D.data(), nullptr) == RESHARD_OK);
+    }
+    // what the descriptor table says, byte by byte
+    reshard_plan_info info;
+    REQUIRE(reshard_plan_get_info(plan, &info) == RESHARD_OK);
+    for (int64_t q = 0; q < info.num_descs; ++q) {
+        reshard_desc d;
+        REQUIRE(reshard_plan_desc(plan, q, &d) == RESHARD_OK);
+        const char *s = static_cast<const char *>(S[size_t(d.src_buf)]) + d.src_off;
+        char *w = static_cast<char *>(W[size_t(d.dst_buf)]) + d.dst_off;
+        if (d.kind == 0) {
+            for (int64_t i = 0; i < d.rows; ++i) std::memcpy(w + i * d.dst_stride, s + i * d.src_stride, size_t(d.row_bytes));
+        } else {
+            const int64_t cols = d.row_bytes / d.elem_bytes;
+            for (int64_t i = 0; i < d.rows; ++i)
+                for (int64_t k = 0; k < cols; ++k)
+                    std::memcpy(w + k * d.dst_stride + i * d.elem_bytes, s + i * d.src_stride + k * d.elem_bytes, size_t(d.elem_bytes));
+        }
+    }
+    int bad = 0;
+    for (int j = 0; j < nd; ++j)
+        if (D[size_t(j)] && std::memcmp(D[size_t(j)], W[size_t(j)], size_t(reshard_plan_buf_bytes(plan, 1, j)))) {
+            std::printf("destination buffer %d differs from the descriptor table's result\n", j);
+            bad = 1;
+        }
+    REQUIRE(reshard_plan_destroy(plan) == RESHARD_OK);
+    for (void *p : S) std::free(p);
+    for (void *p : D) std::free(p);
+    for (void *p : W) std::free(p);
+    return bad;
+}
+
+int main() {
+    int bad = 0;
+    // dense: fused QKV, gate/up, row-parallel merges, bias vectors, two pipeline stages
+    reshard_model_spec dense{};
+    dense.struct_size = sizeof dense;
+    dense.family = RESHARD_DENSE_GQA; dense.L = 2; dense.H = 64; dense.nq = 4; dense.nkv = 2; dense.d = 16; dense.I = 88; dense.V = 96;
+    dense.has_embeddings = 1; dense.qkv_bias = 1;
+    // grouped experts whose matrices hold whole register-path tiles, smaller shapes on the strips and a ragged rest
+    reshard_model_spec moe{};
+    moe.struct_size = sizeof moe;
+    moe.family = RESHARD_MOE_GQA; moe.L = 1; moe.H = 336; moe.nq = 4; moe.nkv = 2; moe.d = 16; moe.V = 32; moe.has_embeddings = 1;
+    moe.E = 2; moe.Ie = 208; moe.n_shared = 0;
+    reshard_tuning small{}, odd{}, persistent{}, plain_order{};
+    small.tile_bytes = 4096; small.block_threads = 64; small.unroll = 1; small.transpose_rows = 64; small.transpose_cols = 64;
+    odd.tile_bytes = 8192; odd.block_threads = 256; odd.unroll = 4; odd.flags = 11; odd.transpose_rows = 128; odd.transpose_cols = 64;
+    persistent.blocks_per_cu = 2; persistent.block_threads = 128; persistent.tile_bytes = 4096;
+    plain_order.flags = 7; plain_order.tile_bytes = 16384; plain_order.unroll = 16;
+    for (int eb : {2, 1, 4, 8}) {
+        dense.elem_bytes = moe.elem_bytes = eb;
+        // every launch shape at 2 bytes; the default and the smallest shapes at the other sizes
+        std::vector<const reshard_tuning *> tunings{nullptr, &small};
+        if (eb == 2) tunings.insert(tunings.end(), {&odd, &persistent, &plain_order});
+        for (const reshard_tuning *tn : tunings) {
+            bad += run(dense, lay(RESHARD_TRAIN, 2, 2, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), tn, false);
+            bad += run(moe, lay(RESHARD_TRAIN, 1, 1, 2, 1), lay(RESHARD_GEN, 2, 1, 1, 0), tn, false);   // transposing
+            bad += run(moe, lay(RESHARD_GEN, 2, 1, 1, 0), lay(RESHARD_TRAIN, 1, 1, 2, 1), tn, tn == nullptr);  // and back
+            if (bad) break;
+        }
+        if (bad) break;
+        std::printf("element size %d done: %ld launches, %ld workgroups so far\n", eb, host_simt::launches, host_simt::blocks_run);
+        std::fflush(stdout);
+    }
+    std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
+    return bad ? 1 : 0;
+}

@@ -93,3 +93,25 @@ def test_c_abi_flows_are_clean_under_asan_and_ubsan(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert res.returncode == 0, res.stdout + res.stderr
     assert res.stdout.strip().endswith("ok")
+
+
+@pytest.mark.skipif(not os.path.exists("/opt/rocm/llvm/bin/clang++"), reason="ROCm clang++ not available")
+def test_the_real_kernels_run_on_the_host_under_asan(tmp_path):
+    """repack.hip itself, compiled for the host against tests/host_simt (a host thread per lane, real
+    barriers, __shared__ as statics) and run under AddressSanitizer on small workloads that reach
+    the copy kernels (one tile per workgroup and persistent), the register-transpose kernel at
+    every element size and the generic transpose: every global and LDS access of the kernels' own
+    index arithmetic is checked against the exact extents of the buffers, and every result against
+    the descriptor table."""
+    exe = str(tmp_path / "kernels_on_host")
+    csrc = os.path.join(ROOT, "paper_2507_19017_amd", "csrc")
+    cmd = ["/opt/rocm/llvm/bin/clang++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-pthread", "-I" + os.path.join(ROOT, "tests", "host_simt"), "-I" + os.path.join(ROOT, "include"), "-I" + csrc,
+           os.path.join(csrc, "plan.cpp"), os.path.join(csrc, "api.cpp"), "-x", "c++", os.path.join(csrc, "repack.hip"),
+           os.path.join(ROOT, "tests", "kernels_on_host.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    env = dict(os.environ)
+    env["ASAN_OPTIONS"] = "detect_leaks=1:abort_on_error=0"
+    res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=900)
+    assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
+    assert res.stdout.strip().endswith("ok") and "element size 8 done" in res.stdout
