@@ -25,8 +25,15 @@ def case_line(expect, spec, src, dst):
     return " ".join(str(CODES.get(v, v)) for v in vals)
 
 
+_BUILT = {}
+
+
 def build(tmp_path):
-    exe = str(tmp_path / "plan_sanitize")
+    if "plan_sanitize" in _BUILT:  # both tests of this module run the same binary
+        return _BUILT["plan_sanitize"]
+    import tempfile
+
+    exe = os.path.join(tempfile.mkdtemp(prefix="plan_sanitize_"), "plan_sanitize")
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
            "-static-libasan", "-static-libubsan",  # no dependence on the order of preloaded libraries
            "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(ROOT, "paper_2507_19017_amd", "csrc"),
@@ -35,6 +42,7 @@ def build(tmp_path):
     subprocess.run(cmd, check=True, capture_output=True, text=True)
     env = dict(os.environ)
     env["ASAN_OPTIONS"] = "detect_leaks=1:abort_on_error=0"
+    _BUILT["plan_sanitize"] = (exe, env)
     return exe, env
 
 
