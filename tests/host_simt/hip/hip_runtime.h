@@ -31,25 +31,24 @@ extern uint3_ blockIdx, blockDim, gridDim;
 static inline uint32_t __umulhi(uint32_t a, uint32_t b) { return uint32_t((uint64_t(a) * b) >> 32); }
 
 namespace host_simt {
-constexpr int kMaxLanes = 1024;
+// A pool of host threads, one per lane of a workgroup of `n` lanes; the workgroups of a launch
+// run one after another on it (they share the statics that stand for LDS).
 struct Pool {
     pthread_barrier_t start, done, sync;
     std::vector<std::thread> lanes;
     std::function<void()> job;
-    uint32_t active = 0;
-    bool quit = false, sync_made = false;
-    Pool() {
-        pthread_barrier_init(&start, nullptr, kMaxLanes + 1);
-        pthread_barrier_init(&done, nullptr, kMaxLanes + 1);
-        for (int t = 0; t < kMaxLanes; ++t)
+    bool quit = false;
+    explicit Pool(uint32_t n) {
+        pthread_barrier_init(&start, nullptr, n + 1);
+        pthread_barrier_init(&done, nullptr, n + 1);
+        pthread_barrier_init(&sync, nullptr, n);
+        for (uint32_t t = 0; t < n; ++t)
             lanes.emplace_back([this, t] {
                 for (;;) {
                     pthread_barrier_wait(&start);
                     if (quit) return;
-                    if (uint32_t(t) < active) {
-                        threadIdx = {uint32_t(t), 0, 0};
-                        job();
-                    }
+                    threadIdx = {t, 0, 0};
+                    job();
                     pthread_barrier_wait(&done);
                 }
             });
@@ -60,34 +59,33 @@ struct Pool {
         for (std::thread &l : lanes) l.join();
         pthread_barrier_destroy(&start);
         pthread_barrier_destroy(&done);
-        if (sync_made) pthread_barrier_destroy(&sync);
+        pthread_barrier_destroy(&sync);
     }
-    void run_block(uint32_t nlanes, const std::function<void()> &f) {
-        if (sync_made) pthread_barrier_destroy(&sync);
-        pthread_barrier_init(&sync, nullptr, nlanes);
-        sync_made = true;
-        active = nlanes;
+    void run_block(const std::function<void()> &f) {
         job = f;
         pthread_barrier_wait(&start);
         pthread_barrier_wait(&done);
     }
 };
-Pool &pool();
+Pool &pool(uint32_t lanes);
+extern pthread_barrier_t *current_sync;
 extern long launches, blocks_run;
 inline void launch(dim3 grid, dim3 block, const std::function<void()> &body) {
     ++launches;
     gridDim = {grid.x, 1, 1};
     blockDim = {block.x, 1, 1};
+    Pool &p = pool(block.x);
+    current_sync = &p.sync;
     for (uint32_t b = 0; b < grid.x; ++b) {
         blockIdx = {b, 0, 0};
-        pool().run_block(block.x, body);
+        p.run_block(body);
         ++blocks_run;
     }
 }
 }  // namespace host_simt
 
 // every lane of the workgroup must reach it, as on the device (a lane that returned early would hang here)
-#define __syncthreads() pthread_barrier_wait(&host_simt::pool().sync)
+#define __syncthreads() pthread_barrier_wait(host_simt::current_sync)
 #define hipLaunchKernelGGL(kernel, grid, block, shmem, stream, ...) \
     host_simt::launch(grid, block, [=] { kernel(__VA_ARGS__); })
 

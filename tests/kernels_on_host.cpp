@@ -8,6 +8,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
+#include <memory>
 #include <vector>
 
 #include "internal.h"
@@ -17,10 +19,13 @@ thread_local uint3_ threadIdx;
 uint3_ blockIdx, blockDim, gridDim;
 namespace host_simt {
 long launches = 0, blocks_run = 0;
-Pool &pool() {
-    static Pool p;
-    return p;
+Pool &pool(uint32_t lanes) {
+    static std::map<uint32_t, std::unique_ptr<Pool>> pools;  // one pool per workgroup size in use
+    std::unique_ptr<Pool> &p = pools[lanes];
+    if (!p) p.reset(new Pool(lanes));
+    return *p;
 }
+pthread_barrier_t *current_sync = nullptr;
 }  // namespace host_simt
 
 #define REQUIRE(cond) do { if (!(cond)) { std::printf("line %d: %s is false (last error: %s)\n", __LINE__, #cond, reshard_last_error()); return 1; } } while (0)
@@ -92,8 +97,44 @@ static int run(const reshard_model_spec &spec, const reshard_layout &src, const 
     return bad;
 }
 
-int main() {
+// Cases from a file, one per line, in the format of tests/plan_sanitize.cpp (the leading
+// "expect" field is ignored: every case in the file is a valid one).
+static int run_file(const char *path, const reshard_tuning *tn) {
+    std::FILE *f = std::fopen(path, "r");
+    if (!f) { std::printf("cannot open %s\n", path); return 1; }
+    int bad = 0, n = 0, v[45];
+    for (;;) {
+        int got = 0;
+        while (got < 45 && std::fscanf(f, "%d", &v[got]) == 1) ++got;
+        if (got < 45) break;
+        reshard_model_spec s{};
+        s.struct_size = sizeof s;
+        int32_t *sp = &s.family;
+        for (int k = 0; k < 20; ++k) sp[k] = v[1 + k];
+        reshard_layout l[2]{};
+        for (int side = 0; side < 2; ++side) {
+            l[side].struct_size = sizeof(reshard_layout);
+            int32_t *lp = &l[side].kind;
+            for (int k = 0; k < 12; ++k) lp[k] = v[21 + 12 * side + k];
+        }
+        bad += run(s, l[0], l[1], tn, n % 3 == 2);
+        ++n;
+    }
+    std::fclose(f);
+    std::printf("%d cases from file\n", n);
+    return bad;
+}
+static_assert(sizeof(reshard_model_spec) == 21 * 4 && sizeof(reshard_layout) == 13 * 4, "field counts used by run_file");
+
+int main(int argc, char **argv) {
     int bad = 0;
+    if (argc > 1) {
+        reshard_tuning tiny{};
+        tiny.tile_bytes = 4096; tiny.block_threads = 128; tiny.unroll = 1;
+        bad = run_file(argv[1], &tiny);  // 128-lane workgroups: cheap to emulate
+        std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
+        return bad ? 1 : 0;
+    }
     // dense: fused QKV, gate/up, row-parallel merges, bias vectors, two pipeline stages
     reshard_model_spec dense{};
     dense.struct_size = sizeof dense;

@@ -123,3 +123,11 @@ def test_the_real_kernels_run_on_the_host_under_asan(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=900)
     assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
     assert res.stdout.strip().endswith("ok") and "element size 8 done" in res.stdout
+    # the random small workloads as well: every layout option, odd widths, narrow vector units
+    from synth_inputs import random_case
+
+    path = tmp_path / "cases.txt"
+    path.write_text("\n".join(case_line(1, w["spec"], w["src"], w["dst"]) for w in (random_case(seed) for seed in range(24))) + "\n")
+    res = subprocess.run([exe, str(path)], capture_output=True, text=True, env=env, timeout=900)
+    assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
+    assert "24 cases from file" in res.stdout and res.stdout.strip().endswith("ok")
