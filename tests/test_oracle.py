@@ -95,7 +95,7 @@ def test_tiny_random_payload_other_element_sizes(name, eb):
 
 
 def test_toy_config_against_numpy_layouts():
-    """BASELINE config 0 (toy dense TP2 -> TP1), bf16-sized payload."""
+    """The smallest task workload (toy dense TP2 -> TP1), bf16-sized payload."""
     w = WORKLOADS["C0"]
     spec = w["spec"]
     rng = np.random.default_rng(w["seed"])
