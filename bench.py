@@ -217,7 +217,7 @@ def main():
 
     framework = None
     if a.framework_baseline:
-        # What "select and copy" looks like with framework tensor operations: one strided
+        # What the slice selection and copy looks like with framework tensor operations: one strided
         # tensor copy per descriptor of the same plan (torch.as_strided views of the flat
         # buffers, Tensor.copy_), on the same buffers.  A GPU-side comparison only: the
         # product path never runs it.

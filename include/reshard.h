@@ -5,8 +5,8 @@
  * sections "Allgather-Swap Technique" and "Problem Statement", redundant-memory
  * example).  After an actor update the training-layout weight shards (already
  * gathered in HBM: step 1 of the technique) are repacked into the generation
- * engine's layout at a different tensor/expert-parallel degree (step 2: "select
- * and copy"), the training-side buffers are swapped to pinned host memory so
+ * engine's layout at a different tensor/expert-parallel degree (step 2: slice
+ * selection and copy), the training-side buffers are swapped to pinned host memory so
  * their HBM can be released for generation (step 3, device-to-host), and swapped
  * back before the next update (host-to-device) instead of resharding again.
  *
@@ -235,7 +235,7 @@ int reshard_set_tuning(const reshard_tuning *t);
 int reshard_get_tuning(reshard_tuning *out);
 
 /*
- * Step "select and copy", compile time (host only, no GPU needed): validates the
+ * Step 2 (slice selection and copy), compile time (host only, no GPU needed): validates the
  * shape against both layouts and compiles the src -> dst mapping into a flat
  * table of copy descriptors, cut into equal-work tiles.  Any (kind, degrees)
  * pair is allowed, so TRAIN -> GEN is the resharding, TRAIN -> TRAIN with equal
@@ -287,7 +287,7 @@ int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshard_desc *out
 int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshard_tile *out);
 
 /*
- * Step "select and copy", run time: asynchronous kernel launches on `stream` (one for the
+ * Step 2 (slice selection and copy), run time: asynchronous kernel launches on `stream` (one for the
  * strided copies, one per transposing tile shape in use; three or fewer for most plans, a
  * dozen at most) that fill every used destination buffer from the source buffers.
  * src_ptrs[num_src_bufs], dst_ptrs[num_dst_bufs]: device pointers, each aligned to

@@ -1,7 +1,7 @@
 // Host-side plan builder: compiles (model shape, source layout, destination
 // layout) into a flat table of copy descriptors and equal-work tiles.
 //
-// This is the "select" half of step 2 of the allgather-swap technique (paper
+// This is the selection half of step 2 of the allgather-swap technique (paper
 // section "Allgather-Swap Technique": each device selects and copies the weight
 // slices it needs for generation), done once per layout pair instead of per
 // iteration.  Formulation: each layout is described as a list of FRAGMENTS

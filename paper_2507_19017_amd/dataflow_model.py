@@ -31,7 +31,7 @@ def td_tcv_gb(G: int, N: int, B: int, PL: int, n: int, SL: int, M: int, C: int, 
 
 def dispatch_seconds(volume_gb: float, link_mb_per_s: float) -> float:
     """Time to move `volume_gb` (2^30-byte GB) over a link of `link_mb_per_s` (2^20-byte MB/s);
-    Table 1's "1 GB/s" column is 1024 MB/s."""
+    Table 1's 1 GB/s column is 1024 MB/s."""
     return volume_gb * 1024.0 / link_mb_per_s
 
 

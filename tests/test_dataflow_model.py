@@ -26,7 +26,7 @@ def test_eq2_reproduces_table_1(row):
     v = m.tcv_gb(G, N, B, PL, n, SL, M)
     assert printed_close(v, tcv)
     assert printed_close(m.dispatch_seconds(v, 100), t100)
-    assert printed_close(m.dispatch_seconds(v, 1024), t1k)  # the "1 GB/s" column
+    assert printed_close(m.dispatch_seconds(v, 1024), t1k)  # the 1 GB/s column
 
 
 def test_eq1_eq4_reduce_to_each_other():
