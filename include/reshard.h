@@ -216,7 +216,8 @@ typedef struct reshard_tuning {
     int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4, 8 or 16 (default 2) */
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
                                barrier between a tile's load burst and its store burst, bit 3: each XCD
-                               walks a contiguous eighth of the tile table (default 15); -1 = none */
+                               walks a contiguous eighth of the tile table, bit 4: the copy kernel issues its
+                               loads at raised wave priority (with bits 0-2 all set; default 31); -1 = none */
     int32_t transpose_rows; /* shape of a register-transposed tile in elements: source rows ... */
     int32_t transpose_cols; /* ... and source columns; each 64, 128, 256 or 512.  0, or a shape the plan's
                              * element size does not allow (the tile must fit 128 KiB): the default for

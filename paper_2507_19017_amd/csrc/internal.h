@@ -65,8 +65,9 @@ struct Tuning {
     int block_threads = 1024;
     int blocks_per_cu = 0;        // 0: one tile per workgroup; > 0: persistent grid
     int unroll = 2;               // 22 VGPRs: two 1024-lane workgroups fit a compute unit (8 takes 69: one)
-    int flags = 15;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
-                                  // bit 3: each XCD walks a contiguous eighth of the tile table
+    int flags = 31;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
+                                  // bit 3: each XCD walks a contiguous eighth of the tile table,
+                                  // bit 4: the copy kernel's load bursts run at raised wave priority
     int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;
     int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size
 };

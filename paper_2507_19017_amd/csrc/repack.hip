@@ -62,6 +62,7 @@ __device__ __forceinline__ void copy_tile(const char *__restrict__ s, char *__re
         const uint32_t base = first + tid;
         V v[UNROLL];
         uint64_t doff[UNROLL];
+        if (NT & 8) __builtin_amdgcn_s_setprio(3);  // waves that issue loads go first
 #pragma unroll
         for (int k = 0; k < UNROLL; ++k) {
             const uint32_t u = base + k * nthreads;
@@ -72,6 +73,7 @@ __device__ __forceinline__ void copy_tile(const char *__restrict__ s, char *__re
                 doff[k] = uint64_t(row) * dstride + uint64_t(col) * sizeof(V);
             }
         }
+        if (NT & 8) __builtin_amdgcn_s_setprio(0);
         if (NT & 4) __syncthreads();
 #pragma unroll
         for (int k = 0; k < UNROLL; ++k) {
@@ -315,6 +317,10 @@ template <int U>
 void launch_copy_u(int flags, dim3 grid, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n,
                    const PtrTable &pt) {
     const int x = (flags & 8) ? 1 : 0;
+    if ((flags & 16) && (flags & 7) == 7) {  // load bursts at raised wave priority (built for the full set of hints only)
+        launch_copy_u_nt<U, 15>(grid, block, st, tiles, n, pt, x);
+        return;
+    }
     switch (flags & 7) {
         case 0: launch_copy_u_nt<U, 0>(grid, block, st, tiles, n, pt, x); break;
         case 1: launch_copy_u_nt<U, 1>(grid, block, st, tiles, n, pt, x); break;
@@ -570,7 +576,7 @@ extern "C" int reshard_set_tuning(const reshard_tuning *t) {
                 return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 256 or 512");
         if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
         if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
-        if (t->flags < -1 || t->flags > 15) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 15]");
+        if (t->flags < -1 || t->flags > 31) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 31]");
         // 0 keeps the default like every other field; -1 asks for plain loads and stores, no barrier
         if (t->flags > 0) n.flags = t->flags;
         if (t->flags == -1) n.flags = 0;

@@ -28,6 +28,7 @@ extern uint3_ blockIdx, blockDim, gridDim;
 #define __forceinline__ inline
 #define __shared__ static
 #define __launch_bounds__(...)
+#define __builtin_amdgcn_s_setprio(level) ((void)0)  // wave priority means nothing on the host
 static inline uint32_t __umulhi(uint32_t a, uint32_t b) { return uint32_t((uint64_t(a) * b) >> 32); }
 
 namespace host_simt {

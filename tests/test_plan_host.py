@@ -437,7 +437,7 @@ def test_state_machine_errors_without_a_device():
 def test_tuning_is_validated():
     set_tuning()
     base = get_tuning()
-    assert base == dict(tile_bytes=32768, block_threads=1024, blocks_per_cu=0, unroll=2, flags=15, transpose_rows=0,
+    assert base == dict(tile_bytes=32768, block_threads=1024, blocks_per_cu=0, unroll=2, flags=31, transpose_rows=0,
                         transpose_cols=0)
     set_tuning(tile_bytes=8192, unroll=4)
     assert get_tuning()["tile_bytes"] == 8192 and get_tuning()["unroll"] == 4
