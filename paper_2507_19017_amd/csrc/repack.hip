@@ -252,6 +252,7 @@ void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, 
     char *d = ptrs.p[t.dst_buf] + t.dst_off;
     const uint32_t tid = threadIdx.x;
     u32x4 r[ROUNDS][VE];
+    __builtin_amdgcn_s_setprio(3);  // like the copy kernel: waves that issue loads go first
 #pragma unroll
     for (int q = 0; q < ROUNDS; ++q) {
         const uint32_t b = tid + q * THREADS, kb = b % KB, ib = b / KB;
@@ -259,6 +260,7 @@ void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, 
         for (int j = 0; j < VE; ++j)
             r[q][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(s + uint64_t(ib * VE + j) * t.src_stride + kb * 16));
     }
+    __builtin_amdgcn_s_setprio(0);
 #pragma unroll
     for (int q = 0; q < ROUNDS; ++q) {
         const uint32_t b = tid + q * THREADS, kb = b % KB, ib = b / KB;
