@@ -219,7 +219,7 @@ typedef struct reshard_tuning {
                                walks a contiguous eighth of the tile table, bit 4: the copy kernel issues its
                                loads at raised wave priority (with bits 0-2 all set; default 31); -1 = none */
     int32_t transpose_rows; /* shape of a register-transposed tile in elements: source rows ... */
-    int32_t transpose_cols; /* ... and source columns; each 64, 128, 256 or 512.  0, or a shape the plan's
+    int32_t transpose_cols; /* ... and source columns; each 64, 128, 192, 256 or 512.  0, or a shape the plan's
                              * element size does not allow (the tile must fit 128 KiB): the default for
                              * that size (1 byte 512 x 256, 2 bytes 256 x 256, 4 bytes 128 x 256, 8 bytes 128 x 128) */
 } reshard_tuning;

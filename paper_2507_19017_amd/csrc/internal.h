@@ -76,12 +76,22 @@ Tuning current_tuning();
 // Shapes the register-transpose kernel is built for: E-byte elements, ti x tk elements per tile.
 // (16 / E) x (16 / E) blocks, one per lane and round; at least eight 16-byte chunks per
 // destination row (the LDS swizzle needs them); whole waves; at most 128 KiB of LDS.
-constexpr bool transpose_shape_ok(int E, int ti, int tk) {
-    auto listed = [](int v) { return v == 64 || v == 128 || v == 256 || v == 512; };
-    if (!listed(ti) || !listed(tk) || (E != 1 && E != 2 && E != 4 && E != 8)) return false;
+// Lanes of the workgroup that handles a ti x tk tile: the largest whole number of waves, at most
+// 1024 lanes, that divides the tile's blocks (0 if there is none).
+constexpr int transpose_threads(int E, int ti, int tk) {
     const int ve = 16 / E, blocks = (ti / ve) * (tk / ve);
+    for (int t = 1024; t >= 64; t -= 64)
+        if (blocks % t == 0) return t;
+    return 0;
+}
+constexpr bool transpose_shape_ok(int E, int ti, int tk) {
+    // 192 (2-byte elements, with 256 or 192 on the other side) serves experts of width 768 split four ways
+    auto listed = [](int v) { return v == 64 || v == 128 || v == 192 || v == 256 || v == 512; };
+    if (!listed(ti) || !listed(tk) || (E != 1 && E != 2 && E != 4 && E != 8)) return false;
+    if ((ti == 192 || tk == 192) && (E != 2 || ti < 192 || tk < 192)) return false;
+    const int ve = 16 / E;
     if (E == 1 ? tk < 128 : (ti > 256 || tk > 256)) return false;  // shapes nobody needs are not built
-    return ti / ve >= 8 && blocks >= 64 && ti * tk * E <= 128 * 1024;
+    return ti / ve >= 8 && (ti / ve) % 8 == 0 && transpose_threads(E, ti, tk) > 0 && ti * tk * E <= 128 * 1024;
 }
 // Shape used when the tuning names none (or one the element size does not allow).
 inline void transpose_default_shape(int E, int &ti, int &tk) {

@@ -515,8 +515,8 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
                     return true;
                 }
                 int64_t best = 0;
-                for (int a : {512, 256, 128, 64})
-                    for (int b : {512, 256, 128, 64})
+                for (int a : {512, 256, 192, 128, 64})
+                    for (int b : {512, 256, 192, 128, 64})
                         if (a <= R && b <= C && transpose_shape_ok(E, a, b) && int64_t(a) * b > best) {
                             best = int64_t(a) * b;
                             ti = a;

@@ -236,14 +236,14 @@ __device__ __forceinline__ u32x4 transposed_row(const u32x4 *r, int c) {
 // 16-byte chunks of a row XOR-swizzled by (k / VE) so that neither the writes (lanes
 // VE rows apart) nor the reads (lanes along a row) pile onto one bank group.
 template <int E, int TI, int TK>
-__global__ __launch_bounds__((TI * TK * E * E / 256) < 1024 ? (TI * TK * E * E / 256) : 1024)
+__global__ __launch_bounds__(transpose_threads(E, TI, TK))
 void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, PtrTable ptrs, int by_xcd) {
     constexpr int VE = 16 / E;
     constexpr int BLOCKS = TI / VE * (TK / VE);    // VE x VE blocks in a tile
-    constexpr int THREADS = BLOCKS < 1024 ? BLOCKS : 1024;
+    constexpr int THREADS = transpose_threads(E, TI, TK);
     constexpr int ROUNDS = BLOCKS / THREADS;
     constexpr int KB = TK / VE, IC = TI / VE;      // blocks along k; 16-byte chunks per LDS row
-    static_assert(BLOCKS % THREADS == 0 && THREADS % 64 == 0 && IC >= 8 && TI * TK * E <= 128 * 1024, "tile shape");
+    static_assert(BLOCKS % THREADS == 0 && THREADS % 64 == 0 && IC % 8 == 0 && TI * TK * E <= 128 * 1024, "tile shape");
     __shared__ u32x4 lds[TK * IC];
     const uint32_t ti = tile_of_workgroup(blockIdx.x, ntiles, by_xcd != 0);
     if (ti >= ntiles) return;  // uniform for the workgroup: nobody reaches the barrier below
@@ -433,7 +433,7 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc
         const int E = plan->spec.elem_bytes;
         if (!transpose_shape_ok(E, rows, cols)) return fail(RESHARD_ERR_INVALID_ARG, "unsupported transposing tile shape");
         const int shape = (E * 1000 + rows) * 1000 + cols;
-        const uint32_t threads = uint32_t(std::min(rows * cols * E * E / 256, 1024));
+        const uint32_t threads = uint32_t(transpose_threads(E, rows, cols));
         const uint32_t per_launch = (0xFFFFFFFFu / threads) & ~7u;
         for (uint32_t first = 0; first < n; first += per_launch) {
             const Tile *ft = t + first;
@@ -451,6 +451,7 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc
                 RESHARD_T16(2, 64, 64) RESHARD_T16(2, 64, 128) RESHARD_T16(2, 64, 256)
                 RESHARD_T16(2, 128, 64) RESHARD_T16(2, 128, 128) RESHARD_T16(2, 128, 256)
                 RESHARD_T16(2, 256, 64) RESHARD_T16(2, 256, 128) RESHARD_T16(2, 256, 256)
+                RESHARD_T16(2, 256, 192) RESHARD_T16(2, 192, 256) RESHARD_T16(2, 192, 192)
                 RESHARD_T16(4, 64, 64) RESHARD_T16(4, 64, 128) RESHARD_T16(4, 64, 256)
                 RESHARD_T16(4, 128, 64) RESHARD_T16(4, 128, 128) RESHARD_T16(4, 128, 256)
                 RESHARD_T16(4, 256, 64) RESHARD_T16(4, 256, 128)
@@ -574,8 +575,8 @@ extern "C" int reshard_set_tuning(const reshard_tuning *t) {
             n.unroll = u;
         }
         for (int v : {t->transpose_rows, t->transpose_cols})
-            if (v != 0 && v != 64 && v != 128 && v != 256 && v != 512)
-                return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 256 or 512");
+            if (v != 0 && v != 64 && v != 128 && v != 192 && v != 256 && v != 512)
+                return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 192, 256 or 512");
         if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
         if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
         if (t->flags < -1 || t->flags > 31) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 31]");

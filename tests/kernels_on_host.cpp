@@ -145,7 +145,8 @@ int main(int argc, char **argv) {
     moe.struct_size = sizeof moe;
     moe.family = RESHARD_MOE_GQA; moe.L = 1; moe.H = 336; moe.nq = 4; moe.nkv = 2; moe.d = 16; moe.V = 32; moe.has_embeddings = 1;
     moe.E = 2; moe.Ie = 208; moe.n_shared = 0;
-    reshard_tuning small{}, odd{}, persistent{}, plain_order{};
+    reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{};
+    wide192.transpose_rows = 192; wide192.transpose_cols = 192;
     small.tile_bytes = 4096; small.block_threads = 64; small.unroll = 1; small.transpose_rows = 64; small.transpose_cols = 64;
     odd.tile_bytes = 8192; odd.block_threads = 256; odd.unroll = 4; odd.flags = 11; odd.transpose_rows = 128; odd.transpose_cols = 64;
     persistent.blocks_per_cu = 2; persistent.block_threads = 128; persistent.tile_bytes = 4096;
@@ -154,7 +155,7 @@ int main(int argc, char **argv) {
         dense.elem_bytes = moe.elem_bytes = eb;
         // every launch shape at 2 bytes; the default and the smallest shapes at the other sizes
         std::vector<const reshard_tuning *> tunings{nullptr, &small};
-        if (eb == 2) tunings.insert(tunings.end(), {&odd, &persistent, &plain_order});
+        if (eb == 2) tunings.insert(tunings.end(), {&odd, &persistent, &plain_order, &wide192});
         for (const reshard_tuning *tn : tunings) {
             bad += run(dense, lay(RESHARD_TRAIN, 2, 2, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), tn, false);
             bad += run(moe, lay(RESHARD_TRAIN, 1, 1, 2, 1), lay(RESHARD_GEN, 2, 1, 1, 0), tn, false);   // transposing

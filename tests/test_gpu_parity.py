@@ -131,7 +131,7 @@ def _transpose_shapes():
                 fits = ti * tk * eb <= 131072
                 if fits and ((ti >= 128 and tk >= 128) if eb == 1 else max(ti, tk) <= 256):
                     out.append((eb, ti, tk))
-    return out
+    return out + [(2, 256, 192), (2, 192, 256), (2, 192, 192)]
 
 
 @pytest.mark.parametrize("eb,ti,tk", _transpose_shapes())

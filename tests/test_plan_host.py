@@ -85,6 +85,8 @@ def transpose_shape(eb, tuning):
     default = {1: (512, 256), 2: (256, 256), 4: (128, 256), 8: (128, 128)}[eb]
     ti, tk = tuning.get("transpose_rows", 0), tuning.get("transpose_cols", 0)
     ok = ti and tk and ti * tk * eb <= 131072 and (ti >= 128 and tk >= 128 if eb == 1 else max(ti, tk) <= 256)
+    if 192 in (ti, tk):  # built for 2-byte elements only, with 192 or 256 on the other side
+        ok = ok and eb == 2 and min(ti, tk) >= 192
     return (ti, tk) if ok else default
 
 
