@@ -109,7 +109,7 @@ def main():
         sys.exit(2)
     import torch
 
-    from paper_2507_19017_amd import Plan, copy_baseline, get_tuning, set_tuning
+    from paper_2507_19017_amd import Plan, copy_baseline, get_tuning, read_baseline, set_tuning, write_baseline
     from synth_inputs import BF16_ONE, WORKLOADS, fill_buffer
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -329,6 +329,21 @@ def main():
         evs.append((e0, e1))
     torch.cuda.synchronize()
     plain_gbps = 2 * cp_n / (min(x.elapsed_time(y) for x, y in evs[1:]) / 1e3) / 1e9
+    # one-way rates of the same buffers with the same tile shape: a copy moves equal bytes both ways
+    # over the same memory, so 2 / (1/R + 1/W) bounds it (the destination is rewritten by every repack)
+    one_way = {}
+    pr_n = cp_n // 32768 * 32768
+    for key, fn in (("read", lambda: read_baseline(big_s.data_ptr(), pr_n, h)), ("write", lambda: write_baseline(big_d.data_ptr(), pr_n, h))):
+        evs = []
+        for _ in range(6):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        one_way[key] = pr_n / (min(x.elapsed_time(y) for x, y in evs[1:]) / 1e3) / 1e9
+    mixed_bound = 2.0 / (1.0 / one_way["read"] + 1.0 / one_way["write"])
 
     traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "repack_hbm_traffic.json")  # from rocprofv3 --pmc runs
@@ -354,7 +369,9 @@ def main():
                      "frac": round(repack_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes": 2 * moved, "traffic_detail": traffic_detail,
                      "kernel_ms_avg": round(k_avg * 1e3, 4), "kernel_ms_min": round(min(kernel_ms), 4),
-                     "plain_copy_GBps": round(plain_gbps, 1)},
+                     "plain_copy_GBps": round(plain_gbps, 1), "read_only_GBps": round(one_way["read"], 1),
+                     "write_only_GBps": round(one_way["write"], 1), "mixed_bound_GBps": round(mixed_bound, 1),
+                     "frac_of_mixed_bound": round(2 * moved / k_avg / 1e9 / mixed_bound, 4)},
         "pct_hbm_peak": round(100 * repack_gbps / HBM_PEAK_GBPS, 2),
         "peak_hbm_bytes": {"ledger": stats["peak_device"], "torch_max_allocated": peak_torch,
                            "freed_after_swap_out": (sum(freed) // len(freed)) if freed else None,

@@ -419,6 +419,17 @@ int reshard_mem_stats(const reshard_plan *plan, reshard_mem_stats_t *out);
  */
 int reshard_copy_baseline(void *dst, const void *src, int64_t bytes, void *stream);
 
+/*
+ * One-way bandwidth probes with the copy kernel's tile shape, launch shape and access hints:
+ * reshard_read_baseline only loads `bytes` from `src` (the data is folded into a checksum that
+ * is never stored), reshard_write_baseline only stores `bytes` of a fixed pattern to `dst`
+ * (the buffer's contents are lost).  `bytes` a multiple of 32 KiB, pointers 16-byte aligned,
+ * one launch on `stream`.  With R and W the two rates, a copy that moves equal bytes both ways
+ * over the same memory is bounded by 2 / (1/R + 1/W).
+ */
+int reshard_read_baseline(const void *src, int64_t bytes, void *stream);
+int reshard_write_baseline(void *dst, int64_t bytes, void *stream);
+
 /* Library build tag, e.g. "reshard 0.1 gfx950". */
 const char *reshard_version(void);
 

@@ -4,6 +4,8 @@ from .binding import (  # noqa: F401
     Plan,
     ReshardError,
     copy_baseline,
+    read_baseline,
+    write_baseline,
     get_tuning,
     last_error,
     redundant_memory_bytes,

@@ -123,6 +123,8 @@ def lib():
             "reshard_set_host_limit": (None, [C.c_int64]),
             "reshard_mem_stats": (C.c_int, [P, C.POINTER(MemStats)]),
             "reshard_copy_baseline": (C.c_int, [P, P, C.c_int64, P]),
+            "reshard_read_baseline": (C.c_int, [P, C.c_int64, P]),
+            "reshard_write_baseline": (C.c_int, [P, C.c_int64, P]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
@@ -140,6 +142,7 @@ EXPORTS = (
     "reshard_swap_out_source", "reshard_mark_src_buffer_released", "reshard_src_buffer_state", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
     "reshard_swap_wait", "reshard_swap_wait_buffer", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_swap_in_source", "reshard_reserve_host", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
+    "reshard_read_baseline", "reshard_write_baseline",
 )
 
 
@@ -174,6 +177,14 @@ def get_tuning() -> dict:
 
 def set_host_limit(limit: int) -> None:
     lib().reshard_set_host_limit(int(limit))
+
+
+def read_baseline(src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib().reshard_read_baseline(C.c_void_p(src_ptr), int(nbytes), C.c_void_p(stream)))
+
+
+def write_baseline(dst_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib().reshard_write_baseline(C.c_void_p(dst_ptr), int(nbytes), C.c_void_p(stream)))
 
 
 def copy_baseline(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:

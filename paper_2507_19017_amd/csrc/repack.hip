@@ -307,6 +307,32 @@ __global__ __launch_bounds__(1024) void plain_copy_kernel(const char *__restrict
     }
 }
 
+// One-way probes: 32 KiB per 1024-lane workgroup, two 16-byte non-temporal accesses per lane, the
+// XCD-contiguous order of the repack.  The read probe folds what it loads into a value and
+// stores it to a private sink when it equals one particular number, which keeps the compiler
+// from dropping (or sinking) the loads and happens for about one lane in four billion.
+__device__ uint32_t g_probe_sink[64];
+__global__ __launch_bounds__(1024) void read_probe_kernel(const char *__restrict__ src, uint32_t ntiles) {
+    const uint32_t ti = tile_of_workgroup(blockIdx.x, ntiles, true);
+    if (ti >= ntiles) return;
+    const char *s = src + uint64_t(ti) * 32768;
+    __builtin_amdgcn_s_setprio(3);
+    const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(s + uint64_t(threadIdx.x) * 16));
+    const u32x4 b = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(s + uint64_t(threadIdx.x + 1024) * 16));
+    __builtin_amdgcn_s_setprio(0);
+    const uint32_t fold = a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3];
+    // one lane in four billion; the volatile store cannot be dropped, so neither can the loads
+    if (fold == 0x9E3779B9u) *const_cast<volatile uint32_t *>(&g_probe_sink[threadIdx.x & 63]) = fold;
+}
+__global__ __launch_bounds__(1024) void write_probe_kernel(char *__restrict__ dst, uint32_t ntiles) {
+    const uint32_t ti = tile_of_workgroup(blockIdx.x, ntiles, true);
+    if (ti >= ntiles) return;
+    char *d = dst + uint64_t(ti) * 32768;
+    const u32x4 v = {ti, threadIdx.x, 0x9E3779B9u, ~ti};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d + uint64_t(threadIdx.x) * 16));
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d + uint64_t(threadIdx.x + 1024) * 16));
+}
+
 template <int U, int NT>
 void launch_copy_u_nt(dim3 grid, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n,
                       const PtrTable &pt, int by_xcd) {
@@ -601,6 +627,26 @@ extern "C" int reshard_get_tuning(reshard_tuning *out) {
     out->transpose_cols = t.transpose_cols;
     return RESHARD_OK;
 }
+
+namespace {
+int probe(const void *src, void *dst, int64_t bytes, void *stream) {
+    const void *p = src ? src : dst;
+    if (!p || bytes <= 0 || bytes % 32768 || (reinterpret_cast<uintptr_t>(p) % 16))
+        return fail(RESHARD_ERR_INVALID_ARG, "a bandwidth probe needs a 16-byte aligned pointer and a positive multiple of 32 KiB");
+    const int64_t tiles = bytes / 32768;
+    if (tiles > 0x3FFFFFll) return fail(RESHARD_ERR_INVALID_ARG, "a bandwidth probe takes at most 128 GiB");  // 2^32 lanes per launch
+    const uint32_t n = uint32_t(tiles);
+    const dim3 grid((n + 7) / 8 * 8), block(1024);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (src) hipLaunchKernelGGL(read_probe_kernel, grid, block, 0, st, static_cast<const char *>(src), n);
+    else hipLaunchKernelGGL(write_probe_kernel, grid, block, 0, st, static_cast<char *>(dst), n);
+    if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of a bandwidth probe");
+    return RESHARD_OK;
+}
+}  // namespace
+
+extern "C" int reshard_read_baseline(const void *src, int64_t bytes, void *stream) { return probe(src, nullptr, bytes, stream); }
+extern "C" int reshard_write_baseline(void *dst, int64_t bytes, void *stream) { return probe(nullptr, dst, bytes, stream); }
 
 extern "C" int reshard_copy_baseline(void *dst, const void *src, int64_t bytes, void *stream) {
     if (!dst || !src || bytes <= 0 || bytes % 16 || (reinterpret_cast<uintptr_t>(dst) % 16) ||

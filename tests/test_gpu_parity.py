@@ -7,7 +7,7 @@ import torch
 
 import gpu_util as G
 from oracle import fast, locate
-from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, set_tuning
+from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, read_baseline, set_tuning, write_baseline
 from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout, make_spec, random_case
 
 pytestmark = pytest.mark.gpu
@@ -236,6 +236,32 @@ def test_execute_on_a_side_stream_and_inside_a_hip_graph():
         for a, b in zip(dst, eager):
             assert torch.equal(a, b), f"replay {replay}"
         G.assert_equal_buffers(dst, G.oracle_destinations(wl, G.to_host(src), 4), f"replay {replay}")
+
+
+def test_one_way_bandwidth_probes():
+    """The read probe leaves its buffer alone, the write probe fills exactly the bytes it was given
+    (each 16-byte unit holds its tile, its lane, a constant and the tile's complement), and both
+    refuse sizes that are not whole tiles."""
+    n = 5 * 32768
+    buf = torch.arange(n // 2 + 64, dtype=torch.int16, device="cuda")
+    keep = buf.clone()
+    read_baseline(buf.data_ptr(), n, G.stream_handle())
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep)
+    write_baseline(buf.data_ptr(), n, G.stream_handle())
+    torch.cuda.synchronize()
+    got = buf[:n // 2].view(torch.int32).view(-1, 4).cpu().numpy().view(np.uint32).reshape(5, 2, 1024, 4)
+    tile = np.arange(5, dtype=np.uint32)[:, None, None]
+    lane = np.arange(1024, dtype=np.uint32)[None, None, :]
+    assert np.array_equal(got[..., 0], np.broadcast_to(tile, (5, 2, 1024)))
+    assert np.array_equal(got[..., 1], np.broadcast_to(lane, (5, 2, 1024)))
+    assert np.all(got[..., 2] == 0x9E3779B9) and np.array_equal(got[..., 3], np.broadcast_to(~tile, (5, 2, 1024)))
+    assert torch.equal(buf[n // 2:], keep[n // 2:])  # nothing past the end
+    for bad in (n + 16, 0):
+        with pytest.raises(ReshardError):
+            write_baseline(buf.data_ptr(), bad, G.stream_handle())
+        with pytest.raises(ReshardError):
+            read_baseline(buf.data_ptr(), bad, G.stream_handle())
 
 
 def test_a_plain_c_program_drives_the_library_on_the_gpu(tmp_path):
