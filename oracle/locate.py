@@ -21,9 +21,11 @@ The result has a plain definition, written out here literally:
 
 `Layout.place` answers "where does logical element (tensor, layer, expert,
 row, col) live", by explicit index arithmetic, for ints or numpy arrays.
-Parity status: pinned by brute-force tracing, counting, closed-form byte totals
-and numpy reshape/concatenate constructions in tests/; there is no worked
-example in the paper, so against the authors' own code it is parity unpinned.
+Parity status: pinned, by brute-force tracing, per-element write counts,
+closed-form byte totals, the per-device bytes the paper's ablation prints and
+numpy reshape/concatenate constructions in tests/.  The paper prints no worked
+example of the mapping itself, so none of the pins is an element-level value
+from the authors; the layout conventions are the public Megatron ones.
 """
 
 from __future__ import annotations

@@ -20,9 +20,11 @@
  * No blocking, fusion or reordering beyond that.  A second, independent
  * statement of the same mapping lives in locate.py; tests compare the two.
  *
- * Parity status: pinned by element tracing, counting, closed-form byte totals
- * and numpy constructions in tests/; the paper has no worked example of the
- * mapping, so against the authors' code it is parity unpinned.
+ * Parity status: pinned, by element tracing, per-element write counts,
+ * closed-form byte totals, the per-device bytes the paper's ablation prints
+ * and numpy constructions in tests/.  The paper prints no worked example of
+ * the mapping itself, so none of the pins is an element-level value from the
+ * authors; the layout conventions are the public Megatron ones.
  */
 #include <stdint.h>
 #include <stdlib.h>
