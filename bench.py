@@ -109,6 +109,9 @@ def main():
         sys.exit(2)
     import torch
 
+    from paper_2507_19017_amd.build import ensure_built
+
+    ensure_built()  # compiles only if no library is there
     from paper_2507_19017_amd import Plan, copy_baseline, get_tuning, read_baseline, set_tuning, write_baseline
     from synth_inputs import BF16_ONE, WORKLOADS, fill_buffer
 

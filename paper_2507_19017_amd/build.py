@@ -52,6 +52,15 @@ def build_c_client() -> str:
     return C_CLIENT
 
 
+def ensure_built() -> None:
+    """For tests, smoke() and bench.py: build what is missing, leave what is there alone.
+    The binding never calls this: without a built library the product refuses to load."""
+    if not os.path.exists(LIB):
+        build_library()
+    if not os.path.exists(C_CLIENT):
+        build_c_client()
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_c_client())

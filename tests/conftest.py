@@ -11,6 +11,9 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    from paper_2507_19017_amd.build import ensure_built
+
+    ensure_built()  # loads what is built; compiles only if nothing is
 
 
 def _gpu_present() -> bool:

@@ -577,3 +577,21 @@ def test_plans_can_be_built_from_several_threads_at_once():
         t.join()
     for k in range(8):
         assert out[k] == ([(binding.ERR_UNSUPPORTED, True)] * 6 if k % 2 else [True] * 6), (k, out[k])
+
+
+def test_without_a_built_library_the_binding_refuses_to_load(monkeypatch, tmp_path):
+    """No fallback of any kind: with the shared library absent every call raises, and nothing
+    under oracle/ is touched by the product package."""
+    import sys
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libreshard.so"))
+    with pytest.raises(ImportError, match="not built"):
+        binding.version()
+    with pytest.raises(ImportError, match="not built"):
+        Plan(TINY["tiny_dense"]["spec"], TINY["tiny_dense"]["src"], TINY["tiny_dense"]["dst"])
+    pkg = os.path.dirname(os.path.abspath(binding.__file__))
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            text = open(os.path.join(pkg, name)).read()
+            assert "oracle" not in text, name + " mentions the oracle"
