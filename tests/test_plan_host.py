@@ -595,3 +595,14 @@ def test_without_a_built_library_the_binding_refuses_to_load(monkeypatch, tmp_pa
         if name.endswith(".py"):
             text = open(os.path.join(pkg, name)).read()
             assert "oracle" not in text, name + " mentions the oracle"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build is for one GPU: asked for more, the bench says so and exits before touching a device."""
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2", "--steps", "1", "--warmup", "0"],
+                         capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
