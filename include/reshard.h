@@ -208,16 +208,21 @@ typedef struct reshard_mem_stats_t {
     int32_t state;        /* RESHARD_SRC_* */
 } reshard_mem_stats_t;
 
-/* Knobs of the repack kernel; zero fields keep the built-in default. */
+/* Knobs of the repack kernels; zero fields keep the built-in default.  Every plan holds its own
+ * copy: tile_bytes and the transposing tile shape decide how the plan's tiles are cut and are fixed
+ * at creation, the other fields are the launch shape and may be changed between executes. */
 typedef struct reshard_tuning {
     int32_t tile_bytes;     /* bytes of work per tile (power of two, 4 KiB .. 512 KiB; default 32 KiB) */
     int32_t block_threads;  /* 64, 128, 256, 512 or 1024 (default 1024) */
     int32_t blocks_per_cu;  /* 0 (default): one tile per workgroup; n > 0: persistent grid of n per CU */
-    int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4, 8 or 16 (default 2) */
+    int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4 or 8 (default 2) */
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
                                barrier between a tile's load burst and its store burst, bit 3: each XCD
                                walks a contiguous eighth of the tile table, bit 4: the copy kernel issues its
-                               loads at raised wave priority (with bits 0-2 all set; default 31); -1 = none */
+                               loads at raised wave priority (with bits 0-2 all set; default 31); -1 = none.
+                               With unroll 1, 4 or 8 bits 0-2 must be all set or all clear.  A persistent
+                               grid has no barrier and no raised priority, and its accesses are
+                               non-temporal when bits 0 and 1 are both set */
     int32_t transpose_rows; /* shape of a register-transposed tile in elements: source rows ... */
     int32_t transpose_cols; /* ... and source columns; each 64, 128, 192, 256 or 512.  0, or a shape the plan's
                              * element size does not allow (the tile must fit 128 KiB): the default for
@@ -228,8 +233,8 @@ typedef struct reshard_tuning {
 const char *reshard_last_error(void);
 
 /*
- * Process-wide tuning used by plans created afterwards (tile_bytes) and by
- * executes issued afterwards (the launch shape).  NULL restores the defaults.
+ * The process-wide default tuning: plans created afterwards by reshard_plan_create start from a
+ * copy of it; existing plans are not affected.  NULL restores the built-in defaults.
  * Returns INVALID_ARG for a value outside the ranges above.
  */
 int reshard_set_tuning(const reshard_tuning *t);
@@ -250,6 +255,23 @@ int reshard_get_tuning(reshard_tuning *out);
 #define RESHARD_MAX_BUFFERS 384
 int reshard_plan_create(const reshard_model_spec *spec, const reshard_layout *src,
                         const reshard_layout *dst, reshard_plan **out);
+
+/*
+ * The same with the plan's tuning given explicitly (NULL: the process-wide default; otherwise the
+ * non-zero fields of *tuning over the built-in defaults), so that plans with different tile sizes
+ * and launch shapes live side by side in one process.
+ */
+int reshard_plan_create_tuned(const reshard_model_spec *spec, const reshard_layout *src,
+                              const reshard_layout *dst, const reshard_tuning *tuning, reshard_plan **out);
+
+/*
+ * Changes the launch shape of an existing plan (block_threads, blocks_per_cu, unroll, flags) for the
+ * executes issued afterwards; NULL or zero fields select the built-in defaults.  tile_bytes and
+ * transpose_rows / transpose_cols must be zero or what the plan was created with (INVALID_ARG
+ * otherwise): the tiles are already cut.  reshard_plan_get_tuning reads the plan's copy.
+ */
+int reshard_plan_set_tuning(reshard_plan *plan, const reshard_tuning *tuning);
+int reshard_plan_get_tuning(const reshard_plan *plan, reshard_tuning *out);
 
 /* Frees the plan, its device tile table and its pinned host memory.  Waits for
  * swap copies still in flight.  NULL is allowed. */
@@ -359,12 +381,17 @@ int reshard_bind_src(reshard_plan *plan, const void *const *src_ptrs);
  * first and reshard_execute second (or use two streams) and the copies overlap
  * the repack, which only reads the sources.
  * State RESIDENT -> SWAPPING_OUT.  Call reshard_swap_wait before freeing the
- * device buffers.  Errors: BAD_STATE, HOST_OOM (state unchanged), HIP.
+ * device buffers: it returns once the copies are done AND every reshard_execute
+ * issued on this plan while they were in flight has finished reading the sources.
+ * Errors: BAD_STATE, HOST_OOM (state unchanged), HIP.
  */
 int reshard_swap_out(reshard_plan *plan, void *stream);
 
 /*
- * Before the next update, host-to-device: copies the pinned host copy back into
+ * Step 3, second half (section "Allgather-Swap Technique": before the next update stage the
+ * update weights are swapped from the host back to the device instead of being resharded
+ * again; the paper notes that this copy can be issued ahead of time and hidden under the
+ * inference stage): copies the pinned host copy back into
  * the currently bound source pointers on the side stream and makes `stream` wait
  * for it, so work queued on `stream` afterwards sees the weights.
  * State ON_HOST -> SWAPPING_IN.  Errors: BAD_STATE (not swapped out, or the
@@ -383,22 +410,28 @@ int reshard_swap_in(reshard_plan *plan, void *stream);
  */
 int reshard_swap_wait_buffer(reshard_plan *plan, int index, void *stream, int host_wait);
 
-/* Blocks the host until the swap copies in flight are done and completes the
- * state change (SWAPPING_OUT -> ON_HOST, SWAPPING_IN -> RESIDENT).  A no-op in
+/* Blocks the host until the swap copies in flight are done (and, for a swap-out, until every
+ * repack launched on this plan meanwhile has finished: only then may the sources go) and
+ * completes the state change (SWAPPING_OUT -> ON_HOST, SWAPPING_IN -> RESIDENT).  A no-op in
  * any other state. */
 int reshard_swap_wait(reshard_plan *plan);
 
-/* Ledger: the caller has freed the device copy of the sources (allowed in
- * ON_HOST) / of the destinations.  The source pointers are forgotten. */
+/* Ledger of step 3's release (section "Allgather-Swap Technique": once the update weights are on
+ * the host their device buffer is released completely, so generation gets that memory; step 4
+ * releases the temporary gather buffer, which on one device is the same memory): the caller has
+ * freed the device copy of the sources (allowed in ON_HOST) / of the destinations.  The source
+ * pointers are forgotten. */
 int reshard_mark_src_released(reshard_plan *plan);
 int reshard_mark_dst_released(reshard_plan *plan);
 
-/* Allocates the pinned host copies now (all or nothing) instead of inside the first swap-out,
+/* Host side of step 3 (the host buffer the update weights are swapped into).
+ * Allocates the pinned host copies now (all or nothing) instead of inside the first swap-out,
  * which otherwise pays for pinning the pages (about one second for 65 GB).  Allowed in any state.
  * Errors: HOST_OOM. */
 int reshard_reserve_host(reshard_plan *plan);
 
-/* Frees the pinned host copy (allowed in UNBOUND, RESIDENT). */
+/* Frees the pinned host copy of step 3 once the weights are back on the device (allowed in
+ * UNBOUND, RESIDENT: in every other state the host copy is the only one, or a copy is in flight). */
 int reshard_release_host(reshard_plan *plan);
 
 /* Host pointer of the pinned copy of source buffer `index` (NULL before the first
@@ -409,6 +442,10 @@ const void *reshard_host_copy(const reshard_plan *plan, int index);
  * pinned bytes (negative = no limit).  Process-wide. */
 void reshard_set_host_limit(int64_t limit);
 
+/* The byte ledger (section "Allgather-Swap Technique", steps 3 and 4, and the memory-profiling
+ * ablation, which reports about 8 GB released per device for the 32B dense model going from TP8 to
+ * TP4): src_live + dst_live is the peak while both copies exist, and `released` is what the swap-out
+ * gave back.  Pure host bookkeeping of what the caller told the plan. */
 int reshard_mem_stats(const reshard_plan *plan, reshard_mem_stats_t *out);
 
 /*

@@ -92,6 +92,9 @@ def lib():
             "reshard_set_tuning": (C.c_int, [C.POINTER(Tuning)]),
             "reshard_get_tuning": (C.c_int, [C.POINTER(Tuning)]),
             "reshard_plan_create": (C.c_int, [C.POINTER(ModelSpec), C.POINTER(Layout), C.POINTER(Layout), C.POINTER(P)]),
+            "reshard_plan_create_tuned": (C.c_int, [C.POINTER(ModelSpec), C.POINTER(Layout), C.POINTER(Layout), C.POINTER(Tuning), C.POINTER(P)]),
+            "reshard_plan_set_tuning": (C.c_int, [P, C.POINTER(Tuning)]),
+            "reshard_plan_get_tuning": (C.c_int, [P, C.POINTER(Tuning)]),
             "reshard_plan_destroy": (C.c_int, [P]),
             "reshard_plan_num_bufs": (C.c_int, [P, C.c_int]),
             "reshard_plan_buf_bytes": (C.c_int64, [P, C.c_int, C.c_int]),
@@ -135,7 +138,7 @@ def lib():
 
 EXPORTS = (
     "reshard_last_error", "reshard_version", "reshard_set_tuning", "reshard_get_tuning",
-    "reshard_plan_create", "reshard_plan_destroy", "reshard_plan_num_bufs", "reshard_plan_buf_bytes",
+    "reshard_plan_create", "reshard_plan_create_tuned", "reshard_plan_set_tuning", "reshard_plan_get_tuning", "reshard_plan_destroy", "reshard_plan_num_bufs", "reshard_plan_buf_bytes",
     "reshard_plan_buf_used", "reshard_plan_num_tensors", "reshard_plan_tensor", "reshard_plan_get_info",
     "reshard_plan_class_bytes", "reshard_redundant_memory_bytes",
     "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_execute_source",
@@ -228,10 +231,25 @@ def _ptr_array(ptrs):
 class Plan:
     """Thin owner of a reshard_plan*; methods mirror the C entry points one to one."""
 
-    def __init__(self, spec: dict, src: dict, dst: dict):
+    def __init__(self, spec: dict, src: dict, dst: dict, tuning: dict | None = None):
+        """tuning: fields of reshard_tuning for this plan alone (None: the process-wide default)."""
         self._h = C.c_void_p()
         s, a, b = make_spec(spec), make_layout(src), make_layout(dst)
-        _check(lib().reshard_plan_create(C.byref(s), C.byref(a), C.byref(b), C.byref(self._h)))
+        if tuning is None:
+            _check(lib().reshard_plan_create(C.byref(s), C.byref(a), C.byref(b), C.byref(self._h)))
+        else:
+            t = Tuning(**{k: int(v) for k, v in tuning.items()})
+            _check(lib().reshard_plan_create_tuned(C.byref(s), C.byref(a), C.byref(b), C.byref(t), C.byref(self._h)))
+
+    def set_tuning(self, **kw) -> None:
+        """Launch shape of this plan's later executes (block_threads, blocks_per_cu, unroll, flags)."""
+        t = Tuning(**{k: int(v) for k, v in kw.items()})
+        _check(lib().reshard_plan_set_tuning(self._h, C.byref(t)))
+
+    def get_tuning(self) -> dict:
+        t = Tuning()
+        _check(lib().reshard_plan_get_tuning(self._h, C.byref(t)))
+        return {k: getattr(t, k) for k, _ in Tuning._fields_}
 
     def destroy(self) -> None:
         if self._h:

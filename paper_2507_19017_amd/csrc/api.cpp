@@ -76,6 +76,9 @@ void recompute(reshard_plan *p) {
         if (st == RESHARD_SRC_RELEASED) released += p->src.buf_bytes[i];
     }
     p->state = common < 0 ? RESHARD_SRC_UNBOUND : mixed ? RESHARD_SRC_MIXED : common;
+    bool any_out = false;
+    for (size_t i = 0; i < p->buf_state.size(); ++i) any_out = any_out || (p->src.used[i] && p->buf_state[i] == RESHARD_SRC_SWAPPING_OUT);
+    if (!any_out) p->exec_during_swap = false;
     p->src_live = live;
     p->released = released;
     p->touch_peak();
@@ -93,10 +96,11 @@ int ensure_swap_objects(reshard_plan *p) {
         if (hipError_t e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking)) return hip_fail(e, "hipStreamCreate");
         p->side_stream = s;
     }
-    if (!p->ev_ready) {
+    for (void **slot : {&p->ev_ready, &p->ev_exec}) {
+        if (*slot) continue;
         hipEvent_t ev;
         if (hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) return hip_fail(e, "hipEventCreate");
-        p->ev_ready = ev;
+        *slot = ev;
     }
     if (p->ev_buf.empty()) p->ev_buf.assign(p->src.buf_bytes.size(), nullptr);
     for (size_t i = 0; i < p->ev_buf.size(); ++i) {
@@ -152,6 +156,10 @@ int finish_buffer(reshard_plan *p, size_t i) {
     const int st = p->buf_state[i];
     if (st != RESHARD_SRC_SWAPPING_OUT && st != RESHARD_SRC_SWAPPING_IN) return RESHARD_OK;
     if (hipError_t e = hipEventSynchronize(static_cast<hipEvent_t>(p->ev_buf[i]))) return hip_fail(e, "hipEventSynchronize");
+    // ON_HOST tells the caller the device copy may go: a repack launched while the copies were in
+    // flight reads the same buffers on the caller's stream and must have finished as well
+    if (st == RESHARD_SRC_SWAPPING_OUT && p->exec_during_swap)
+        if (hipError_t e = hipEventSynchronize(static_cast<hipEvent_t>(p->ev_exec))) return hip_fail(e, "hipEventSynchronize");
     p->buf_state[i] = st == RESHARD_SRC_SWAPPING_OUT ? RESHARD_SRC_ON_HOST : RESHARD_SRC_RESIDENT;
     return RESHARD_OK;
 }
@@ -198,10 +206,9 @@ extern "C" const char *reshard_version(void) { return "reshard 0.1 gfx950"; }
 
 extern "C" void reshard_set_host_limit(int64_t limit) { g_host_limit.store(limit); }
 
-extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard_layout *src,
-                                   const reshard_layout *dst, reshard_plan **out) {
-    if (!spec || !src || !dst || !out) return fail(RESHARD_ERR_INVALID_ARG, "NULL argument");
-    *out = nullptr;
+namespace {
+int create_plan(const reshard_model_spec *spec, const reshard_layout *src, const reshard_layout *dst,
+                const Tuning &tuning, reshard_plan **out) {
     if (spec->struct_size != sizeof(reshard_model_spec) || src->struct_size != sizeof(reshard_layout) ||
         dst->struct_size != sizeof(reshard_layout))
         return fail(RESHARD_ERR_INVALID_ARG, "struct_size does not match this library's headers");
@@ -213,7 +220,7 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
         if (int rc = build_side(*spec, *dst, false, p->dst)) { delete p; return rc; }
         const int ns = int(p->src.buf_bytes.size()), nd = int(p->dst.buf_bytes.size());
         if (int rc = compile_descriptors(*spec, p->src, p->dst, p->descs)) { delete p; return rc; }
-        const Tuning tuning = current_tuning();
+        p->tuning = tuning;
         p->fast_rows = tuning.transpose_rows;
         p->fast_cols = tuning.transpose_cols;
         if (!transpose_shape_ok(spec->elem_bytes, p->fast_rows, p->fast_cols))
@@ -272,6 +279,57 @@ extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard
     *out = p;
     return RESHARD_OK;
 }
+}  // namespace
+
+extern "C" int reshard_plan_create(const reshard_model_spec *spec, const reshard_layout *src,
+                                   const reshard_layout *dst, reshard_plan **out) {
+    return reshard_plan_create_tuned(spec, src, dst, nullptr, out);
+}
+
+extern "C" int reshard_plan_create_tuned(const reshard_model_spec *spec, const reshard_layout *src,
+                                         const reshard_layout *dst, const reshard_tuning *tuning, reshard_plan **out) {
+    if (!spec || !src || !dst || !out) return fail(RESHARD_ERR_INVALID_ARG, "NULL argument");
+    *out = nullptr;
+    Tuning tn = current_tuning();
+    if (tuning)
+        if (int rc = tuning_from_abi(tuning, tn)) return rc;
+    return create_plan(spec, src, dst, tn, out);
+}
+
+extern "C" int reshard_set_tuning(const reshard_tuning *t) {
+    Tuning n;
+    if (int rc = tuning_from_abi(t, n)) return rc;
+    set_default_tuning(n);
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_get_tuning(reshard_tuning *out) {
+    if (!out) return fail(RESHARD_ERR_INVALID_ARG, "out is NULL");
+    tuning_to_abi(current_tuning(), out);
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_plan_set_tuning(reshard_plan *p, const reshard_tuning *t) {
+    if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    Tuning n;
+    if (int rc = tuning_from_abi(t, n)) return rc;
+    // the tiles are cut: what shaped them stays (a zero field means "as the plan has it" here)
+    if ((t && t->tile_bytes && t->tile_bytes != p->tuning.tile_bytes) ||
+        (t && t->transpose_rows && t->transpose_rows != p->tuning.transpose_rows) ||
+        (t && t->transpose_cols && t->transpose_cols != p->tuning.transpose_cols))
+        return fail(RESHARD_ERR_INVALID_ARG, "tile_bytes and the transposing tile shape are fixed when the plan is created");
+    n.tile_bytes = p->tuning.tile_bytes;
+    n.transpose_rows = p->tuning.transpose_rows;
+    n.transpose_cols = p->tuning.transpose_cols;
+    p->tuning = n;
+    return RESHARD_OK;
+}
+
+extern "C" int reshard_plan_get_tuning(const reshard_plan *p, reshard_tuning *out) {
+    if (!p || !out) return fail(RESHARD_ERR_INVALID_ARG, "NULL argument");
+    tuning_to_abi(p->tuning, out);
+    return RESHARD_OK;
+}
 
 extern "C" int reshard_plan_destroy(reshard_plan *p) {
     if (!p) return RESHARD_OK;
@@ -281,6 +339,7 @@ extern "C" int reshard_plan_destroy(reshard_plan *p) {
     free_host_copies(p);
     if (p->side_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(p->side_stream));
     if (p->ev_ready) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev_ready));
+    if (p->ev_exec) (void)hipEventDestroy(static_cast<hipEvent_t>(p->ev_exec));
     for (void *ev : p->ev_buf)
         if (ev) (void)hipEventDestroy(static_cast<hipEvent_t>(ev));
     if (p->d_tiles) (void)hipFree(p->d_tiles);
@@ -403,10 +462,23 @@ extern "C" int reshard_execute(reshard_plan *p, const void *const *src_ptrs, voi
             if (p->dst.used[j] && overlaps(src_ptrs[i], p->src.buf_bytes[i], dst_ptrs[j], p->dst.buf_bytes[j]))
                 return fail(RESHARD_ERR_INVALID_ARG, "a source and a destination buffer overlap");
     }
+    if (swapping_out) {
+        // the event recorded below is waited for on the host later, which a captured record cannot serve
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipError_t e = hipStreamIsCapturing(static_cast<hipStream_t>(stream), &cap)) return hip_fail(e, "hipStreamIsCapturing");
+        if (cap != hipStreamCaptureStatusNone)
+            return fail(RESHARD_ERR_BAD_STATE, "an execute cannot be captured into a graph while a swap-out is in flight");
+    }
     if (int rc = ensure_device_table(p)) return rc;
     for (size_t i = 0; i < p->src_ptrs.size(); ++i) p->src_ptrs[i] = p->src.used[i] ? src_ptrs[i] : nullptr;
     for (size_t j = 0; j < p->dst_ptrs.size(); ++j) p->dst_ptrs[j] = p->dst.used[j] ? dst_ptrs[j] : nullptr;
     if (int rc = launch_repack(p, static_cast<hipStream_t>(stream))) return rc;
+    if (swapping_out) {
+        // reshard_swap_wait must not report the sources free to go before this repack has read them
+        p->exec_during_swap = true;
+        if (hipError_t e = hipEventRecord(static_cast<hipEvent_t>(p->ev_exec), static_cast<hipStream_t>(stream)))
+            return hip_fail(e, "hipEventRecord");
+    }
     p->dst_bound = true;
     p->dst_live = used_bytes(p->dst);
     if (swapping_out) recompute(p);

@@ -71,7 +71,13 @@ struct Tuning {
     int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;
     int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size
 };
+// The process-wide default that new plans copy (every plan then keeps its own).
 Tuning current_tuning();
+void set_default_tuning(const Tuning &t);
+// Validates the ABI struct and overlays its non-zero fields on the built-in defaults
+// (t == nullptr: the built-in defaults).  Returns RESHARD_OK or INVALID_ARG.
+int tuning_from_abi(const reshard_tuning *t, Tuning &out);
+void tuning_to_abi(const Tuning &t, reshard_tuning *out);
 
 // Shapes the register-transpose kernel is built for: E-byte elements, ti x tk elements per tile.
 // (16 / E) x (16 / E) blocks, one per lane and round; at least eight 16-byte chunks per
@@ -98,6 +104,15 @@ inline void transpose_default_shape(int E, int &ti, int &tk) {
     ti = E == 8 ? 128 : E == 4 ? 128 : E == 1 ? 512 : 256;
     tk = E == 8 ? 128 : 256;
 }
+
+// Workgroups (of 256 lanes) for `n` generic transposing tiles: the kernel strides over the table, so
+// the grid only has to stay within the 2^32 - 1 lanes of one launch.
+constexpr uint32_t generic_transpose_grid(uint32_t n, uint32_t wanted) {
+    const uint32_t cap = 0xFFFFFFFFu / 256u;
+    return (n < wanted ? n : wanted) < cap ? (n < wanted ? n : wanted) : cap;
+}
+static_assert(uint64_t(generic_transpose_grid(0x7FFFFFF0u, 0xFFFFFFFFu)) * 256 <= 0xFFFFFFFFull &&
+              generic_transpose_grid(1000, 0xFFFFFFFFu) == 1000 && generic_transpose_grid(1000, 512) == 512, "launch limit");
 
 // Tiles of one kind that go out in one launch.
 struct TileClass {
@@ -127,6 +142,8 @@ struct reshard_plan {
     // copy tiles; register-transposed tiles by shape (the preferred shape first); generic transposes
     std::vector<reshard::TileClass> classes;
     int fast_rows = 0, fast_cols = 0;  // preferred shape of the register-transposed tiles
+    reshard::Tuning tuning;            // this plan's own knobs: tile_bytes and the transposing shape are fixed
+                                       // once the tiles are cut, the launch shape may change between executes
     // Tile records index a pointer table of the USED buffers only (used sources first, then used
     // destinations; at most RESHARD_MAX_BUFFERS): slot of every buffer (-1 unused) and the way back.
     std::vector<int> src_slot, dst_slot, slot_buf;
@@ -154,6 +171,8 @@ struct reshard_plan {
     int64_t host_pinned = 0;
     void *side_stream = nullptr;
     void *ev_ready = nullptr;  // recorded on the caller's stream
+    void *ev_exec = nullptr;   // recorded on the caller's stream behind a repack launched during a swap-out
+    bool exec_during_swap = false;  // such a repack is (or may be) still reading the sources
     std::vector<void *> ev_buf; // per source buffer: recorded on the side stream after that buffer's copy
     std::vector<int> buf_state; // per source buffer: RESHARD_SRC_*; `state` is their common value or MIXED
     bool swapped_once = false;

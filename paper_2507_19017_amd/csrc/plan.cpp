@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "internal.h"
@@ -167,6 +168,73 @@ int fail(int code, const std::string &msg) {
     return code;
 }
 const char *last_error_cstr() { return g_error.c_str(); }
+
+namespace {
+std::mutex g_tuning_mutex;
+Tuning g_tuning;
+}  // namespace
+
+Tuning current_tuning() {
+    std::lock_guard<std::mutex> g(g_tuning_mutex);
+    return g_tuning;
+}
+
+void set_default_tuning(const Tuning &t) {
+    std::lock_guard<std::mutex> g(g_tuning_mutex);
+    g_tuning = t;
+}
+
+int tuning_from_abi(const reshard_tuning *t, Tuning &out) {
+    Tuning n;  // built-in defaults
+    if (t) {
+        if (t->tile_bytes) {
+            if (t->tile_bytes < 4096 || t->tile_bytes > 512 * 1024 || (t->tile_bytes & (t->tile_bytes - 1)))
+                return fail(RESHARD_ERR_INVALID_ARG, "tile_bytes must be a power of two in [4 KiB, 512 KiB]");
+            n.tile_bytes = t->tile_bytes;
+        }
+        if (t->block_threads) {
+            const int b = t->block_threads;
+            if (b != 64 && b != 128 && b != 256 && b != 512 && b != 1024)
+                return fail(RESHARD_ERR_INVALID_ARG, "block_threads must be 64, 128, 256, 512 or 1024");
+            n.block_threads = b;
+        }
+        if (t->blocks_per_cu) {
+            if (t->blocks_per_cu < 1 || t->blocks_per_cu > 64)
+                return fail(RESHARD_ERR_INVALID_ARG, "blocks_per_cu must be in [0, 64]");
+            n.blocks_per_cu = t->blocks_per_cu;
+        }
+        if (t->unroll) {
+            const int u = t->unroll;
+            if (u != 1 && u != 2 && u != 4 && u != 8) return fail(RESHARD_ERR_INVALID_ARG, "unroll must be 1, 2, 4 or 8");
+            n.unroll = u;
+        }
+        for (int v : {t->transpose_rows, t->transpose_cols})
+            if (v != 0 && v != 64 && v != 128 && v != 192 && v != 256 && v != 512)
+                return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 192, 256 or 512");
+        if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
+        if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
+        if (t->flags < -1 || t->flags > 31) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 31]");
+        // 0 keeps the default like every other field; -1 asks for plain loads and stores, no barrier
+        if (t->flags > 0) n.flags = t->flags;
+        if (t->flags == -1) n.flags = 0;
+        // the one-tile copy kernel is built for every hint set at unroll 2, for none or all at the others
+        const int hints = n.flags & 7;
+        if (n.blocks_per_cu == 0 && n.unroll != 2 && hints != 0 && hints != 7)
+            return fail(RESHARD_ERR_INVALID_ARG, "with unroll 1, 4 or 8 the hint bits 0-2 must be all set or all clear");
+    }
+    out = n;
+    return RESHARD_OK;
+}
+
+void tuning_to_abi(const Tuning &t, reshard_tuning *out) {
+    out->tile_bytes = t.tile_bytes;
+    out->block_threads = t.block_threads;
+    out->blocks_per_cu = t.blocks_per_cu;
+    out->unroll = t.unroll;
+    out->flags = t.flags;
+    out->transpose_rows = t.transpose_rows;
+    out->transpose_cols = t.transpose_cols;
+}
 
 int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_source, Side &out) {
     if (int rc = check_shape(s, l)) return rc;
@@ -380,7 +448,8 @@ void append_merged(std::vector<reshard_desc> &out, reshard_desc d) {
                 const bool p_multi = p.rows > 1, d_multi = d.rows > 1;
                 int64_t ss = p_multi ? p.src_stride : d_multi ? d.src_stride : d.src_off - p.src_off;
                 int64_t ds = p_multi ? p.dst_stride : d_multi ? d.dst_stride : d.dst_off - p.dst_off;
-                const bool pitch_ok = ss >= p.row_bytes && ds >= p.row_bytes &&
+                // a tile record holds 32-bit pitches: rows further apart stay separate descriptors
+                const bool pitch_ok = ss >= p.row_bytes && ds >= p.row_bytes && ss <= 0xFFFFFFFFll && ds <= 0xFFFFFFFFll &&
                                       (!p_multi || (p.src_stride == ss && p.dst_stride == ds)) &&
                                       (!d_multi || (d.src_stride == ss && d.dst_stride == ds));
                 if (pitch_ok && d.src_off == p.src_off + p.rows * ss && d.dst_off == p.dst_off + p.rows * ds &&

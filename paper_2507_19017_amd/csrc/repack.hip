@@ -16,7 +16,6 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
-#include <mutex>
 #include <new>
 #include <string>
 
@@ -25,9 +24,6 @@
 namespace reshard {
 
 namespace {
-
-std::mutex g_tuning_mutex;
-Tuning g_tuning;
 
 struct PtrTable {
     char *p[RESHARD_MAX_BUFFERS];  // the used buffers: sources first, then destinations
@@ -333,71 +329,68 @@ __global__ __launch_bounds__(1024) void write_probe_kernel(char *__restrict__ ds
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d + uint64_t(threadIdx.x + 1024) * 16));
 }
 
+// The copy kernel is built for: every hint set (bits 0-2, and bit 4 on top of all three) at
+// 2 loads per lane, the default; none or all of them at 1, 4 and 8 loads per lane.  The persistent
+// grid has no barrier and no priority; its accesses are non-temporal when bits 0 and 1 are both set.
 template <int U, int NT>
-void launch_copy_u_nt(dim3 grid, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n,
-                      const PtrTable &pt, int by_xcd) {
-    if (grid.x == n)
-        hipLaunchKernelGGL((repack_copy_kernel<U, NT>), dim3(by_xcd ? (n + 7) / 8 * 8 : n), block, 0, st, tiles, n, pt, by_xcd);
-    else
-        hipLaunchKernelGGL((repack_copy_persistent_kernel<U, (NT & 3)>), grid, block, 0, st, tiles, n, pt);
+void launch_one_tile(dim3 block, hipStream_t st, const Tile *tiles, uint32_t n, const PtrTable &pt, int by_xcd) {
+    hipLaunchKernelGGL((repack_copy_kernel<U, NT>), dim3(by_xcd ? (n + 7) / 8 * 8 : n), block, 0, st, tiles, n, pt, by_xcd);
 }
 template <int U>
-void launch_copy_u(int flags, dim3 grid, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n,
-                   const PtrTable &pt) {
-    const int x = (flags & 8) ? 1 : 0;
-    if ((flags & 16) && (flags & 7) == 7) {  // load bursts at raised wave priority (built for the full set of hints only)
-        launch_copy_u_nt<U, 15>(grid, block, st, tiles, n, pt, x);
-        return;
-    }
-    switch (flags & 7) {
-        case 0: launch_copy_u_nt<U, 0>(grid, block, st, tiles, n, pt, x); break;
-        case 1: launch_copy_u_nt<U, 1>(grid, block, st, tiles, n, pt, x); break;
-        case 2: launch_copy_u_nt<U, 2>(grid, block, st, tiles, n, pt, x); break;
-        case 3: launch_copy_u_nt<U, 3>(grid, block, st, tiles, n, pt, x); break;
-        case 4: launch_copy_u_nt<U, 4>(grid, block, st, tiles, n, pt, x); break;
-        case 5: launch_copy_u_nt<U, 5>(grid, block, st, tiles, n, pt, x); break;
-        case 6: launch_copy_u_nt<U, 6>(grid, block, st, tiles, n, pt, x); break;
-        default: launch_copy_u_nt<U, 7>(grid, block, st, tiles, n, pt, x); break;
-    }
+void launch_one_tile_few(int hints, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n, const PtrTable &pt, int by_xcd) {
+    if (hints == 15) launch_one_tile<U, 15>(block, st, tiles, n, pt, by_xcd);
+    else if (hints == 7) launch_one_tile<U, 7>(block, st, tiles, n, pt, by_xcd);
+    else launch_one_tile<U, 0>(block, st, tiles, n, pt, by_xcd);
+}
+template <int U>
+void launch_persistent(bool nt, dim3 grid, dim3 block, hipStream_t st, const Tile *tiles, uint32_t n, const PtrTable &pt) {
+    if (nt) hipLaunchKernelGGL((repack_copy_persistent_kernel<U, 3>), grid, block, 0, st, tiles, n, pt);
+    else hipLaunchKernelGGL((repack_copy_persistent_kernel<U, 0>), grid, block, 0, st, tiles, n, pt);
 }
 void launch_copy(const Tuning &tn, dim3 grid, dim3 block, hipStream_t st, const Tile *tiles,
                  uint32_t n, const PtrTable &pt) {
+    const int by_xcd = (tn.flags & 8) ? 1 : 0;
+    if (grid.x != n) {  // persistent grid
+        const bool nt = (tn.flags & 3) == 3;
+        switch (tn.unroll) {
+            case 1: launch_persistent<1>(nt, grid, block, st, tiles, n, pt); break;
+            case 2: launch_persistent<2>(nt, grid, block, st, tiles, n, pt); break;
+            case 4: launch_persistent<4>(nt, grid, block, st, tiles, n, pt); break;
+            default: launch_persistent<8>(nt, grid, block, st, tiles, n, pt); break;
+        }
+        return;
+    }
+    // raised load priority exists on top of the full set of hints only
+    const int hints = ((tn.flags & 16) && (tn.flags & 7) == 7) ? 15 : (tn.flags & 7);
     switch (tn.unroll) {
-        case 1: launch_copy_u<1>(tn.flags, grid, block, st, tiles, n, pt); break;
-        case 2: launch_copy_u<2>(tn.flags, grid, block, st, tiles, n, pt); break;
-        case 8: launch_copy_u<8>(tn.flags, grid, block, st, tiles, n, pt); break;
-        case 16: launch_copy_u<16>(tn.flags, grid, block, st, tiles, n, pt); break;
-        default: launch_copy_u<4>(tn.flags, grid, block, st, tiles, n, pt); break;
+        case 1: launch_one_tile_few<1>(hints, block, st, tiles, n, pt, by_xcd); break;
+        case 4: launch_one_tile_few<4>(hints, block, st, tiles, n, pt, by_xcd); break;
+        case 8: launch_one_tile_few<8>(hints, block, st, tiles, n, pt, by_xcd); break;
+        default:
+            switch (hints) {
+                case 0: launch_one_tile<2, 0>(block, st, tiles, n, pt, by_xcd); break;
+                case 1: launch_one_tile<2, 1>(block, st, tiles, n, pt, by_xcd); break;
+                case 2: launch_one_tile<2, 2>(block, st, tiles, n, pt, by_xcd); break;
+                case 3: launch_one_tile<2, 3>(block, st, tiles, n, pt, by_xcd); break;
+                case 4: launch_one_tile<2, 4>(block, st, tiles, n, pt, by_xcd); break;
+                case 5: launch_one_tile<2, 5>(block, st, tiles, n, pt, by_xcd); break;
+                case 6: launch_one_tile<2, 6>(block, st, tiles, n, pt, by_xcd); break;
+                case 7: launch_one_tile<2, 7>(block, st, tiles, n, pt, by_xcd); break;
+                default: launch_one_tile<2, 15>(block, st, tiles, n, pt, by_xcd); break;
+            }
     }
 }
 
-template <int U, int NT>
-void launch_plain_u_nt(dim3 grid, dim3 block, hipStream_t st, const char *s, char *d, uint64_t units, int by_xcd) {
-    hipLaunchKernelGGL((plain_copy_kernel<U, NT>), grid, block, 0, st, s, d, units, by_xcd);
-}
 template <int U>
 void launch_plain_u(int flags, dim3 grid, dim3 block, hipStream_t st, const char *s, char *d, uint64_t units) {
     const int x = (flags & 8) ? 1 : 0;
-    switch (flags & 3) {
-        case 0: launch_plain_u_nt<U, 0>(grid, block, st, s, d, units, x); break;
-        case 1: launch_plain_u_nt<U, 1>(grid, block, st, s, d, units, x); break;
-        case 2: launch_plain_u_nt<U, 2>(grid, block, st, s, d, units, x); break;
-        default: launch_plain_u_nt<U, 3>(grid, block, st, s, d, units, x); break;
-    }
+    if ((flags & 3) == 3) hipLaunchKernelGGL((plain_copy_kernel<U, 3>), grid, block, 0, st, s, d, units, x);
+    else hipLaunchKernelGGL((plain_copy_kernel<U, 0>), grid, block, 0, st, s, d, units, x);
 }
 
 int hip_fail(hipError_t e, const char *what) {
     return fail(RESHARD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }
-
-}  // namespace
-
-Tuning current_tuning() {
-    std::lock_guard<std::mutex> g(g_tuning_mutex);
-    return g_tuning;
-}
-
-namespace {
 
 int query_device(reshard_plan *plan) {
     int dev = 0, cus = 0;
@@ -489,7 +482,9 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc
             if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the register-transpose kernel");
         }
     } else {
-        dim3 grid(std::min(n, wanted)), block(256);
+        // the kernel strides over the table, so the grid is capped where n workgroups of 256 lanes
+        // would exceed the 2^32 - 1 lanes one launch may have
+        dim3 grid(generic_transpose_grid(n, wanted)), block(256);
         switch (plan->spec.elem_bytes) {
             case 1: hipLaunchKernelGGL(repack_transpose_kernel<uint8_t>, grid, block, 0, stream, t, n, pt); break;
             case 2: hipLaunchKernelGGL(repack_transpose_kernel<uint16_t>, grid, block, 0, stream, t, n, pt); break;
@@ -522,7 +517,7 @@ int ensure_device_table(reshard_plan *plan) {
 }
 
 int launch_repack(reshard_plan *plan, hipStream_t stream) {
-    const Tuning tn = current_tuning();
+    const Tuning &tn = plan->tuning;
     PtrTable pt;
     fill_ptrs(plan, pt);
     const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
@@ -562,7 +557,7 @@ int ensure_by_source_table(reshard_plan *plan) {
 }
 
 int launch_source(reshard_plan *plan, int src_index, hipStream_t stream) {
-    const Tuning tn = current_tuning();
+    const Tuning &tn = plan->tuning;
     PtrTable pt;
     fill_ptrs(plan, pt);
     const Tile *base = static_cast<const Tile *>(plan->d_by_src);
@@ -575,58 +570,6 @@ int launch_source(reshard_plan *plan, int src_index, hipStream_t stream) {
 }  // namespace reshard
 
 using namespace reshard;
-
-extern "C" int reshard_set_tuning(const reshard_tuning *t) {
-    Tuning n;  // defaults
-    if (t) {
-        if (t->tile_bytes) {
-            if (t->tile_bytes < 4096 || t->tile_bytes > 512 * 1024 || (t->tile_bytes & (t->tile_bytes - 1)))
-                return fail(RESHARD_ERR_INVALID_ARG, "tile_bytes must be a power of two in [4 KiB, 512 KiB]");
-            n.tile_bytes = t->tile_bytes;
-        }
-        if (t->block_threads) {
-            const int b = t->block_threads;
-            if (b != 64 && b != 128 && b != 256 && b != 512 && b != 1024)
-                return fail(RESHARD_ERR_INVALID_ARG, "block_threads must be 64, 128, 256, 512 or 1024");
-            n.block_threads = b;
-        }
-        if (t->blocks_per_cu) {
-            if (t->blocks_per_cu < 1 || t->blocks_per_cu > 64)
-                return fail(RESHARD_ERR_INVALID_ARG, "blocks_per_cu must be in [0, 64]");
-            n.blocks_per_cu = t->blocks_per_cu;
-        }
-        if (t->unroll) {
-            const int u = t->unroll;
-            if (u != 1 && u != 2 && u != 4 && u != 8 && u != 16) return fail(RESHARD_ERR_INVALID_ARG, "unroll must be 1, 2, 4, 8 or 16");
-            n.unroll = u;
-        }
-        for (int v : {t->transpose_rows, t->transpose_cols})
-            if (v != 0 && v != 64 && v != 128 && v != 192 && v != 256 && v != 512)
-                return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 192, 256 or 512");
-        if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
-        if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
-        if (t->flags < -1 || t->flags > 31) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 31]");
-        // 0 keeps the default like every other field; -1 asks for plain loads and stores, no barrier
-        if (t->flags > 0) n.flags = t->flags;
-        if (t->flags == -1) n.flags = 0;
-    }
-    std::lock_guard<std::mutex> g(g_tuning_mutex);
-    g_tuning = n;
-    return RESHARD_OK;
-}
-
-extern "C" int reshard_get_tuning(reshard_tuning *out) {
-    if (!out) return fail(RESHARD_ERR_INVALID_ARG, "out is NULL");
-    const Tuning t = current_tuning();
-    out->tile_bytes = t.tile_bytes;
-    out->block_threads = t.block_threads;
-    out->blocks_per_cu = t.blocks_per_cu;
-    out->unroll = t.unroll;
-    out->flags = t.flags;
-    out->transpose_rows = t.transpose_rows;
-    out->transpose_cols = t.transpose_cols;
-    return RESHARD_OK;
-}
 
 namespace {
 int probe(const void *src, void *dst, int64_t bytes, void *stream) {
@@ -671,7 +614,6 @@ extern "C" int reshard_copy_baseline(void *dst, const void *src, int64_t bytes, 
         case 1: launch_plain_u<1>(tn.flags, grid, block, st, s, d, units); break;
         case 2: launch_plain_u<2>(tn.flags, grid, block, st, s, d, units); break;
         case 8: launch_plain_u<8>(tn.flags, grid, block, st, s, d, units); break;
-        case 16: launch_plain_u<16>(tn.flags, grid, block, st, s, d, units); break;
         default: launch_plain_u<4>(tn.flags, grid, block, st, s, d, units); break;
     }
     if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the plain copy kernel");

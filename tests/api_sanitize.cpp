@@ -16,8 +16,6 @@
 long fake_hip_host_limit = -1, fake_hip_host_bytes = 0, fake_hip_copies = 0;
 
 namespace reshard {
-Tuning current_tuning() { return Tuning{}; }
-
 static void run_tile(const reshard_plan *p, const Tile &t) {
     const char *s = static_cast<const char *>(p->src_ptrs[size_t(p->slot_buf[t.src_buf])]) + t.src_off;
     char *d = static_cast<char *>(p->dst_ptrs[size_t(p->slot_buf[t.dst_buf])]) + t.dst_off;

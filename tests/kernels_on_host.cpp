@@ -39,10 +39,8 @@ static reshard_layout lay(int kind, int tp, int pp, int ep, int grouped, int etp
 
 static int run(const reshard_model_spec &spec, const reshard_layout &src, const reshard_layout &dst, const reshard_tuning *tn,
                bool by_source) {
-    REQUIRE(reshard_set_tuning(tn) == RESHARD_OK);
     reshard_plan *plan = nullptr;
-    REQUIRE(reshard_plan_create(&spec, &src, &dst, &plan) == RESHARD_OK);
-    REQUIRE(reshard_set_tuning(nullptr) == RESHARD_OK);
+    REQUIRE(reshard_plan_create_tuned(&spec, &src, &dst, tn, &plan) == RESHARD_OK);
     const int ns = reshard_plan_num_bufs(plan, 0), nd = reshard_plan_num_bufs(plan, 1);
     std::vector<void *> S(size_t(ns), nullptr), D(size_t(nd), nullptr), W(size_t(nd), nullptr);
     for (int i = 0; i < ns; ++i) {
@@ -148,9 +146,9 @@ int main(int argc, char **argv) {
     reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{};
     wide192.transpose_rows = 192; wide192.transpose_cols = 192;
     small.tile_bytes = 4096; small.block_threads = 64; small.unroll = 1; small.transpose_rows = 64; small.transpose_cols = 64;
-    odd.tile_bytes = 8192; odd.block_threads = 256; odd.unroll = 4; odd.flags = 11; odd.transpose_rows = 128; odd.transpose_cols = 64;
+    odd.tile_bytes = 8192; odd.block_threads = 256; odd.unroll = 2; odd.flags = 11; odd.transpose_rows = 128; odd.transpose_cols = 64;
     persistent.blocks_per_cu = 2; persistent.block_threads = 128; persistent.tile_bytes = 4096;
-    plain_order.flags = 7; plain_order.tile_bytes = 16384; plain_order.unroll = 16;
+    plain_order.flags = 7; plain_order.tile_bytes = 16384; plain_order.unroll = 8;
     for (int eb : {2, 1, 4, 8}) {
         dense.elem_bytes = moe.elem_bytes = eb;
         // every launch shape at 2 bytes; the default and the smallest shapes at the other sizes

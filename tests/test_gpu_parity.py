@@ -19,10 +19,10 @@ def with_eb(wl, eb):
     return w
 
 
-def run_case(wl, mode="normal", src_lay=None, dst_lay=None, threads=16, via_swap=False):
+def run_case(wl, mode="normal", src_lay=None, dst_lay=None, threads=16, via_swap=False, tuning=None):
     src_lay = src_lay or wl["src"]
     dst_lay = dst_lay or wl["dst"]
-    plan = Plan(wl["spec"], src_lay, dst_lay)
+    plan = Plan(wl["spec"], src_lay, dst_lay, tuning=tuning)
     src = G.device_sources(plan, wl, mode)
     dst = G.device_destinations(plan)
     plan.execute(G.ptrs(src), G.ptrs(dst), G.stream_handle())
@@ -100,12 +100,21 @@ def test_identity_and_round_trip_on_device(name):
 TUNINGS = [
     dict(tile_bytes=4096, block_threads=64, unroll=1, flags=-1),
     dict(tile_bytes=8192, block_threads=128, unroll=2, flags=1),
-    dict(tile_bytes=32768, block_threads=512, unroll=8, flags=2),
-    dict(tile_bytes=16384, block_threads=256, unroll=16, flags=4),
+    dict(tile_bytes=32768, block_threads=512, unroll=2, flags=2),
+    dict(tile_bytes=16384, block_threads=256, unroll=2, flags=4),
+    dict(tile_bytes=16384, block_threads=256, unroll=2, flags=5),
+    dict(tile_bytes=16384, block_threads=1024, unroll=2, flags=6),
     dict(tile_bytes=524288, block_threads=1024, unroll=4, blocks_per_cu=1),
     dict(tile_bytes=65536, block_threads=256, unroll=8, blocks_per_cu=16, flags=7),
-    dict(tile_bytes=131072, block_threads=1024, unroll=16, flags=7),
-    dict(tile_bytes=262144, block_threads=1024, unroll=8, flags=11),
+    dict(tile_bytes=65536, block_threads=1024, unroll=2, blocks_per_cu=2, flags=4),
+    dict(tile_bytes=131072, block_threads=1024, unroll=8, flags=7),
+    dict(tile_bytes=262144, block_threads=1024, unroll=2, flags=11),
+    dict(tile_bytes=65536, block_threads=1024, unroll=8, flags=31),
+    dict(tile_bytes=32768, block_threads=1024, unroll=2, flags=23),
+    dict(tile_bytes=32768, block_threads=1024, unroll=2, flags=27),
+    dict(tile_bytes=32768, block_threads=1024, unroll=2, flags=28),
+    dict(tile_bytes=16384, block_threads=1024, unroll=1, flags=31),
+    dict(tile_bytes=65536, block_threads=1024, unroll=4, flags=15),
     dict(tile_bytes=4096, block_threads=256, unroll=2, flags=8),
 ]
 
@@ -113,13 +122,34 @@ TUNINGS = [
 @pytest.mark.parametrize("tuning", TUNINGS)
 def test_every_launch_shape_gives_the_same_bits(tuning):
     print("tuning", tuning, flush=True)
-    try:
-        set_tuning(**tuning)
-        for name in ("tiny_dense", "tiny_moe_grouped"):
-            run_case(TINY[name], "raw16")
-        run_case(WORKLOADS["C0"], "raw16")
-    finally:
-        set_tuning()
+    for name in ("tiny_dense", "tiny_moe_grouped"):
+        run_case(TINY[name], "raw16", tuning=tuning)
+    run_case(WORKLOADS["C0"], "raw16", tuning=tuning)
+
+
+def test_two_plans_with_different_tunings_interleave():
+    """Tuning belongs to the plan: two plans of one workload cut into different tile sizes and launched
+    with different shapes run alternately on one stream, one of them changes its launch shape in
+    between, and every result equals the oracle's."""
+    wl = WORKLOADS["C0"]
+    print("case two tunings", flush=True)
+    small = Plan(wl["spec"], wl["src"], wl["dst"], tuning=dict(tile_bytes=4096, unroll=1, block_threads=256, flags=7))
+    big = Plan(wl["spec"], wl["src"], wl["dst"], tuning=dict(tile_bytes=131072, unroll=8))
+    assert small.info()["num_tiles"] > 8 * big.info()["num_tiles"]
+    src = G.device_sources(small, wl, "raw16")
+    want = G.oracle_destinations(wl, G.to_host(src), 4)
+    h = G.stream_handle()
+    outs = []
+    for round_ in range(3):
+        for plan in (small, big):
+            dst = G.device_destinations(plan)
+            plan.execute(G.ptrs(src), G.ptrs(dst), h)
+            outs.append(dst)
+        small.set_tuning(unroll=2, flags=(23, 31)[round_ % 2], blocks_per_cu=round_)
+        assert small.get_tuning()["tile_bytes"] == 4096 and big.get_tuning()["tile_bytes"] == 131072
+    torch.cuda.synchronize()
+    for dst in outs:
+        G.assert_equal_buffers(dst, want, "two tunings")
 
 
 def _transpose_shapes():
@@ -141,20 +171,17 @@ def test_register_transpose_tile_shapes(eb, ti, tk):
     print("transpose shape", eb, ti, tk, flush=True)
     exact = dict(TINY["mid_moe_grouped"])
     exact["spec"] = dict(exact["spec"], H=512, Ie=256)
-    try:
-        set_tuning(transpose_rows=ti, transpose_cols=tk)
-        for wl in (TINY["mid_moe_grouped"], TINY["big_moe_grouped"], exact):
-            wl = with_eb(wl, eb)
-            plan, _, _ = run_case(wl, "raw16")
-            # way back: generation [out][in] -> grouped [in][out] is a transpose as well
-            gen = dict(wl["dst"])
-            run_case(wl, "raw16", gen, wl["src"])
-            classes = {t["tile_class"] for t in plan.tiles()}
-            if wl["name"] == "big_moe_grouped":
-                assert 1 in classes and 3 in classes, "full tiles and ragged strips both present"
-        assert plan.info()["num_transpose_tiles"] > 0
-    finally:
-        set_tuning()
+    shape = dict(transpose_rows=ti, transpose_cols=tk)
+    for wl in (TINY["mid_moe_grouped"], TINY["big_moe_grouped"], exact):
+        wl = with_eb(wl, eb)
+        plan, _, _ = run_case(wl, "raw16", tuning=shape)
+        # way back: generation [out][in] -> grouped [in][out] is a transpose as well
+        gen = dict(wl["dst"])
+        run_case(wl, "raw16", gen, wl["src"], tuning=shape)
+        classes = {t["tile_class"] for t in plan.tiles()}
+        if wl["name"] == "big_moe_grouped":
+            assert 1 in classes and 3 in classes, "full tiles and ragged strips both present"
+    assert plan.info()["num_transpose_tiles"] > 0
 
 
 DEGENERATE = [
@@ -626,11 +653,7 @@ def test_a_table_too_long_for_one_launch_goes_out_in_slices():
     src = G.device_sources(plan, wl, "raw16")
     one = G.device_destinations(plan)
     plan.execute(G.ptrs(src), G.ptrs(one), G.stream_handle())
-    try:
-        set_tuning(tile_bytes=4096)
-        small = Plan(wl["spec"], wl["src"], wl["dst"])
-    finally:
-        set_tuning()
+    small = Plan(wl["spec"], wl["src"], wl["dst"], tuning=dict(tile_bytes=4096))
     assert small.info()["num_tiles"] * 1024 > 1 << 32
     two = G.device_destinations(small)
     small.execute(G.ptrs(src), G.ptrs(two), G.stream_handle())

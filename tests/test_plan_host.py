@@ -448,10 +448,44 @@ def test_tuning_is_validated():
     set_tuning()
     n32 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
     assert n8 > 3.5 * n32
-    for bad in (dict(tile_bytes=1000), dict(block_threads=96), dict(unroll=3), dict(blocks_per_cu=100)):
+    for bad in (dict(tile_bytes=1000), dict(block_threads=96), dict(unroll=3), dict(unroll=16), dict(blocks_per_cu=100),
+                dict(unroll=8, flags=5), dict(flags=32)):
         with pytest.raises(ReshardError):
             set_tuning(**bad)
     assert get_tuning() == base
+
+
+def test_every_plan_keeps_its_own_tuning():
+    """The process-wide tuning is only what new plans start from: a plan keeps the tile size it was
+    cut with and its own launch shape whatever is set afterwards, and two plans may differ."""
+    w = WORKLOADS["C0"]
+    set_tuning()
+    a = Plan(w["spec"], w["src"], w["dst"], tuning=dict(tile_bytes=4096, unroll=1, block_threads=256))
+    b = Plan(w["spec"], w["src"], w["dst"])
+    try:
+        set_tuning(tile_bytes=8192, unroll=4, flags=7)
+        c = Plan(w["spec"], w["src"], w["dst"])
+    finally:
+        set_tuning()
+    assert a.get_tuning() == dict(tile_bytes=4096, block_threads=256, blocks_per_cu=0, unroll=1, flags=31,
+                                  transpose_rows=0, transpose_cols=0)
+    assert b.get_tuning()["tile_bytes"] == 32768 and b.get_tuning()["unroll"] == 2
+    assert c.get_tuning()["tile_bytes"] == 8192 and c.get_tuning()["unroll"] == 4 and c.get_tuning()["flags"] == 7
+    assert a.info()["num_tiles"] > c.info()["num_tiles"] >= b.info()["num_tiles"]
+    # the launch shape of an existing plan may change, what cut its tiles may not
+    a.set_tuning(unroll=2, flags=23, blocks_per_cu=2)
+    t = a.get_tuning()
+    assert (t["tile_bytes"], t["unroll"], t["flags"], t["blocks_per_cu"], t["block_threads"]) == (4096, 2, 23, 2, 1024)
+    a.set_tuning(tile_bytes=4096, block_threads=128)  # naming the plan's own tile size is fine
+    assert a.get_tuning()["block_threads"] == 128 and a.get_tuning()["unroll"] == 2
+    for bad in (dict(tile_bytes=8192), dict(transpose_rows=64), dict(unroll=3)):
+        with pytest.raises(ReshardError) as e:
+            a.set_tuning(**bad)
+        assert e.value.code == binding.ERR_INVALID_ARG
+    assert a.get_tuning()["block_threads"] == 128
+    with pytest.raises(ReshardError):
+        Plan(w["spec"], w["src"], w["dst"], tuning=dict(tile_bytes=5000))
+    assert b.get_tuning()["tile_bytes"] == 32768 and get_tuning()["tile_bytes"] == 32768
 
 
 def test_library_exports_every_symbol_the_header_declares():
@@ -606,3 +640,20 @@ def test_bench_refuses_more_than_one_gpu():
                          capture_output=True, text=True, timeout=120)
     assert res.returncode != 0
     assert "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_rows_more_than_4_gib_apart_stay_separate_descriptors():
+    """Two equal single rows of one buffer pair are stacked into one pitched descriptor only when the
+    pitch fits the 32 bits a tile record holds; further apart they stay two runs (and the plan is
+    accepted instead of refused for its pitch).  Heads of 2 GiB: Q1 sits 6 GiB behind Q0 in the
+    fused training tensor."""
+    spec = make_spec(family="dense_gqa", L=1, H=65536, nq=2, nkv=2, d=16384, I=8, V=8)
+    plan = Plan(spec, make_layout(kind="train"), make_layout(kind="gen"), tuning=dict(tile_bytes=524288))
+    descs = plan.descs()
+    assert all(d["rows"] == 1 for d in descs)  # nothing was stacked across the 4 GiB limit
+    spans = sorted((d["dst_off"], d["dst_off"] + d["row_bytes"]) for d in descs)
+    assert all(a[1] <= b[0] for a, b in zip(spans, spans[1:]))  # written once
+    assert sum(b - a for a, b in spans) == plan.info()["bytes_moved"] == sum(t["bytes"] for t in plan.tensors(1))
+    # the same shape with heads a sixteenth the size stacks the rows as before
+    small = make_spec(family="dense_gqa", L=1, H=4096, nq=2, nkv=2, d=16384, I=8, V=8)
+    assert any(d["rows"] == 2 for d in Plan(small, make_layout(kind="train"), make_layout(kind="gen")).descs())
