@@ -642,6 +642,101 @@ def test_largest_shapes_whole_output_and_sampled_pairs(name):
     print(name, "sampled pairs", n, flush=True)
     pads_untouched(plan, dst)
     assert (plan.info()["num_transpose_tiles"] > 0) == (wl["src"]["expert_layout"] == "grouped")
+    if name != "C2":
+        return
+    # "... and back": the device copy is dropped, the caller allocates new buffers, and the swap-in
+    # returns every source byte (compared with the pinned copies and with the seeded fill made again)
+    print(name, "swap-in at full size", flush=True)
+    del dst
+    nsrc = sum(b for b, u in zip(plan.buf_bytes(0), plan.buf_used(0)) if u)
+    assert plan.mem_stats()["state"] == "on_host"
+    plan.mark_src_released()
+    before = torch.cuda.memory_allocated()
+    del src
+    assert before - torch.cuda.memory_allocated() == nsrc == plan.mem_stats()["released"]
+    fresh = [torch.zeros(b // 2, dtype=torch.int16, device="cuda") if u else None
+             for b, u in zip(plan.buf_bytes(0), plan.buf_used(0))]
+    plan.bind_src(G.ptrs(fresh))
+    plan.swap_in(G.stream_handle())
+    plan.swap_wait()
+    torch.cuda.synchronize()
+    assert plan.mem_stats()["state"] == "resident" and plan.mem_stats()["src_live"] == nsrc
+    for i, f in enumerate(fresh):
+        if f is not None:
+            assert np.array_equal(f.cpu().numpy(), G.host_copy_view(plan, i)), f"source buffer {i} differs from its pinned copy"
+    again = G.device_sources(plan, wl, "normal")
+    for i, (f, g) in enumerate(zip(fresh, again)):
+        assert (f is None and g is None) or torch.equal(f, g), f"source buffer {i} differs from the seeded fill"
+
+
+@pytest.mark.parametrize("name", ["C1", "C4"])
+def test_repack_while_the_swap_out_is_in_flight_at_full_size(name):
+    """The overlapped order: the swap-out is queued first, the repack is launched while the
+    device-to-host copies run (both only read the sources).  The destination must equal the loop
+    oracle's, the pinned copies must equal the device sources, and once reshard_swap_wait has
+    returned the repack has finished reading them, so they may be dropped at once."""
+    wl = WORKLOADS[name]
+    print("case", name, "overlapped swap-out and repack", flush=True)
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    plan.prepare()
+    plan.reserve_host()
+    src = G.device_sources(plan, wl, "raw16")
+    dst = G.device_destinations(plan)
+    h = G.stream_handle()
+    plan.bind_src(G.ptrs(src))
+    torch.cuda.synchronize()
+    plan.swap_out(h)
+    assert plan.mem_stats()["state"] == "swapping_out"
+    plan.execute(G.ptrs(src), G.ptrs(dst), h)
+    first = plan.buf_used(0).index(True)
+    assert plan.src_buffer_state(first) == "swapping_out"
+    plan.swap_wait()
+    assert plan.mem_stats()["state"] == "on_host"
+    # no synchronisation of the caller's stream here: swap_wait vouches for the repack as well
+    plan.mark_src_released()
+    keep = [None if s is None else G.host_copy_view(plan, i) for i, s in enumerate(src)]
+    for i, s in enumerate(src):
+        if s is not None:
+            assert np.array_equal(s.cpu().numpy(), keep[i]), f"pinned copy of source buffer {i} differs"
+    del src
+    torch.cuda.synchronize()
+    want = G.oracle_destinations(wl, keep, 16)
+    G.assert_equal_buffers(dst, want, name + " overlapped")
+    pads_untouched(plan, dst)
+
+
+def test_swap_wait_also_waits_for_a_repack_launched_during_the_swap_out():
+    """On a small plan the copies end before the kernel does.  reshard_swap_wait must not return
+    (and the sources must not count as free to go) before a repack launched during the swap-out has
+    read them: right after it returns another stream overwrites the sources, and the destination
+    must still hold the original weights' repack."""
+    wl = WORKLOADS["C0"]
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    plan.prepare()
+    plan.reserve_host()
+    h = G.stream_handle()
+    other = torch.cuda.Stream()
+    for rep in range(20):
+        src = G.device_sources(plan, wl, "raw16")
+        keep = G.to_host(src)
+        dst = G.device_destinations(plan)
+        plan.bind_src(G.ptrs(src))
+        torch.cuda.synchronize()
+        plan.swap_out(h)
+        plan.execute(G.ptrs(src), G.ptrs(dst), h)
+        plan.swap_wait()
+        with torch.cuda.stream(other):  # not ordered after the caller's stream in any way
+            for s_ in src:
+                s_.fill_(0x5A5A)
+        torch.cuda.synchronize()
+        G.assert_equal_buffers(dst, G.oracle_destinations(wl, keep, 2), f"rep {rep}")
+        plan.mark_src_released()
+        plan.bind_src(G.ptrs(src))
+        plan.swap_in(h)
+        plan.swap_wait()
+        torch.cuda.synchronize()
+        for s_, k in zip(src, keep):
+            assert np.array_equal(s_.cpu().numpy(), k)
 
 
 def test_a_table_too_long_for_one_launch_goes_out_in_slices():
