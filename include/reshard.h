@@ -328,6 +328,28 @@ int reshard_execute(reshard_plan *plan, const void *const *src_ptrs, void *const
                     void *stream);
 
 /*
+ * For callers that cannot allocate device memory (set-up code of a HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): reshard_execute with the kernels' tile table in a
+ * static device array of RESHARD_STATIC_TABLE_BYTES (32 MiB = 699,050 tiles; each GPU the library
+ * runs on holds that array until the process ends) instead of device memory owned by the plan.
+ * The call, and everything it calls, allocates and frees nothing: no hipMalloc, no hipFree, no
+ * pinned memory.  Arguments, checks, launches, state changes and results are those of
+ * reshard_execute; inputs and outputs stay caller-owned.
+ * The array is shared by every plan on that GPU and keeps the last call's table: when it does not
+ * already hold this plan's table (the first call for the plan, or another plan has used it since),
+ * the table is copied there from the plan's host memory with hipMemcpyAsync on `stream`, ahead of
+ * the kernels; later calls for the same plan are kernel launches only.  Calls for DIFFERENT plans
+ * that overlap on one GPU (other streams, other threads) race for the array: serialise them, e.g. by
+ * issuing them on one stream.
+ * Errors: those of reshard_execute, and UNSUPPORTED when the plan's table_bytes (reshard_plan_info)
+ * exceed RESHARD_STATIC_TABLE_BYTES: cut the plan into larger tiles (tile_bytes of
+ * reshard_plan_create_tuned) or use reshard_execute.
+ */
+#define RESHARD_STATIC_TABLE_BYTES (32u << 20)
+int reshard_execute_noalloc(reshard_plan *plan, const void *const *src_ptrs, void *const *dst_ptrs,
+                            void *stream);
+
+/*
  * Optional: uploads the tile table to the current device now (hipMalloc + a
  * synchronous copy) instead of inside the first reshard_execute.  After it, an
  * execute is kernel launches only: no allocation, no copy, no synchronisation, so

@@ -108,6 +108,7 @@ def lib():
             "reshard_plan_tile": (C.c_int, [P, C.c_int64, C.POINTER(TileView)]),
             "reshard_plan_prepare": (C.c_int, [P]),
             "reshard_execute": (C.c_int, [P, C.POINTER(P), C.POINTER(P), P]),
+            "reshard_execute_noalloc": (C.c_int, [P, C.POINTER(P), C.POINTER(P), P]),
             "reshard_execute_source": (C.c_int, [P, C.c_int, P, C.POINTER(P), P]),
             "reshard_swap_out_source": (C.c_int, [P, C.c_int, P]),
             "reshard_mark_src_buffer_released": (C.c_int, [P, C.c_int]),
@@ -141,7 +142,7 @@ EXPORTS = (
     "reshard_plan_create", "reshard_plan_create_tuned", "reshard_plan_set_tuning", "reshard_plan_get_tuning", "reshard_plan_destroy", "reshard_plan_num_bufs", "reshard_plan_buf_bytes",
     "reshard_plan_buf_used", "reshard_plan_num_tensors", "reshard_plan_tensor", "reshard_plan_get_info",
     "reshard_plan_class_bytes", "reshard_redundant_memory_bytes",
-    "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_execute_source",
+    "reshard_plan_desc", "reshard_plan_tile", "reshard_plan_prepare", "reshard_execute", "reshard_execute_noalloc", "reshard_execute_source",
     "reshard_swap_out_source", "reshard_mark_src_buffer_released", "reshard_src_buffer_state", "reshard_bind_src", "reshard_swap_out", "reshard_swap_in",
     "reshard_swap_wait", "reshard_swap_wait_buffer", "reshard_mark_src_released", "reshard_mark_dst_released", "reshard_swap_in_source", "reshard_reserve_host", "reshard_release_host",
     "reshard_host_copy", "reshard_set_host_limit", "reshard_mem_stats", "reshard_copy_baseline",
@@ -314,6 +315,9 @@ class Plan:
 
     def execute(self, src_ptrs, dst_ptrs, stream: int = 0) -> None:
         _check(lib().reshard_execute(self._h, _ptr_array(src_ptrs), _ptr_array(dst_ptrs), C.c_void_p(stream)))
+
+    def execute_noalloc(self, src_ptrs, dst_ptrs, stream: int = 0) -> None:
+        _check(lib().reshard_execute_noalloc(self._h, _ptr_array(src_ptrs), _ptr_array(dst_ptrs), C.c_void_p(stream)))
 
     def execute_source(self, src_index: int, src_ptr: int, dst_ptrs, stream: int = 0) -> None:
         _check(lib().reshard_execute_source(self._h, src_index, C.c_void_p(src_ptr), _ptr_array(dst_ptrs), C.c_void_p(stream)))

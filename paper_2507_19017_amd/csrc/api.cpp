@@ -15,6 +15,7 @@ const char *last_error_cstr();
 int ensure_device_table(reshard_plan *plan);
 int ensure_by_source_table(reshard_plan *plan);
 int launch_repack(reshard_plan *plan, hipStream_t stream);
+int launch_repack_static(reshard_plan *plan, hipStream_t stream);
 int launch_source(reshard_plan *plan, int src_index, hipStream_t stream);
 }  // namespace reshard
 
@@ -23,6 +24,7 @@ using namespace reshard;
 namespace {
 
 std::atomic<int64_t> g_host_limit{-1};
+std::atomic<uint64_t> g_plan_serial{0};
 
 int hip_fail(hipError_t e, const char *what) {
     return fail(RESHARD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
@@ -215,6 +217,7 @@ int create_plan(const reshard_model_spec *spec, const reshard_layout *src, const
     reshard_plan *p = nullptr;
     try {
         p = new reshard_plan();
+        p->serial = ++g_plan_serial;
         p->spec = *spec;
         if (int rc = build_side(*spec, *src, true, p->src)) { delete p; return rc; }
         if (int rc = build_side(*spec, *dst, false, p->dst)) { delete p; return rc; }
@@ -444,8 +447,15 @@ extern "C" int reshard_bind_src(reshard_plan *p, const void *const *src_ptrs) {
     return RESHARD_OK;
 }
 
-extern "C" int reshard_execute(reshard_plan *p, const void *const *src_ptrs, void *const *dst_ptrs, void *stream) {
+namespace {
+// reshard_execute and reshard_execute_noalloc: the same checks, binding and ledger; they differ in
+// where the kernels read the tile table from (plan-owned device memory / the static device array).
+int execute_common(reshard_plan *p, const void *const *src_ptrs, void *const *dst_ptrs, void *stream, bool static_table) {
     if (!p) return fail(RESHARD_ERR_INVALID_ARG, "plan is NULL");
+    if (static_table && p->info.table_bytes > int64_t(RESHARD_STATIC_TABLE_BYTES))
+        return fail(RESHARD_ERR_UNSUPPORTED, "the plan's tile table (" + std::to_string(p->info.table_bytes) +
+                    " bytes) does not fit the static device array of " + std::to_string(RESHARD_STATIC_TABLE_BYTES) +
+                    " bytes: create the plan with a larger tile_bytes, or use reshard_execute");
     // while a swap-out is in flight the sources are still valid in HBM and only read
     const bool swapping_out = p->state == RESHARD_SRC_SWAPPING_OUT;
     if (p->state != RESHARD_SRC_UNBOUND && p->state != RESHARD_SRC_RESIDENT && !swapping_out)
@@ -469,10 +479,13 @@ extern "C" int reshard_execute(reshard_plan *p, const void *const *src_ptrs, voi
         if (cap != hipStreamCaptureStatusNone)
             return fail(RESHARD_ERR_BAD_STATE, "an execute cannot be captured into a graph while a swap-out is in flight");
     }
-    if (int rc = ensure_device_table(p)) return rc;
+    if (!static_table)
+        if (int rc = ensure_device_table(p)) return rc;
     for (size_t i = 0; i < p->src_ptrs.size(); ++i) p->src_ptrs[i] = p->src.used[i] ? src_ptrs[i] : nullptr;
     for (size_t j = 0; j < p->dst_ptrs.size(); ++j) p->dst_ptrs[j] = p->dst.used[j] ? dst_ptrs[j] : nullptr;
-    if (int rc = launch_repack(p, static_cast<hipStream_t>(stream))) return rc;
+    if (int rc = static_table ? launch_repack_static(p, static_cast<hipStream_t>(stream))
+                              : launch_repack(p, static_cast<hipStream_t>(stream)))
+        return rc;
     if (swapping_out) {
         // reshard_swap_wait must not report the sources free to go before this repack has read them
         p->exec_during_swap = true;
@@ -484,6 +497,15 @@ extern "C" int reshard_execute(reshard_plan *p, const void *const *src_ptrs, voi
     if (swapping_out) recompute(p);
     else set_all(p, RESHARD_SRC_RESIDENT);
     return RESHARD_OK;
+}
+}  // namespace
+
+extern "C" int reshard_execute(reshard_plan *p, const void *const *src_ptrs, void *const *dst_ptrs, void *stream) {
+    return execute_common(p, src_ptrs, dst_ptrs, stream, false);
+}
+
+extern "C" int reshard_execute_noalloc(reshard_plan *p, const void *const *src_ptrs, void *const *dst_ptrs, void *stream) {
+    return execute_common(p, src_ptrs, dst_ptrs, stream, true);
 }
 
 extern "C" int reshard_execute_source(reshard_plan *p, int src_index, const void *src_ptr, void *const *dst_ptrs,

@@ -149,6 +149,7 @@ struct reshard_plan {
     std::vector<int> src_slot, dst_slot, slot_buf;
     int num_src_slots = 0;
     reshard_plan_info info{};
+    uint64_t serial = 0;  // unique per plan in this process (tells whose table a shared device array holds)
 
     // device side (created lazily by the first execute)
     int device = -1;

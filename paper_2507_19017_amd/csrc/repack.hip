@@ -16,10 +16,18 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
 #include "internal.h"
+
+// The tile table of reshard_execute_noalloc: a static device array instead of plan-owned device
+// memory, for callers that cannot allocate.  Every GPU the library runs on holds its own copy at
+// its own address until the process ends.  The name is a host-side stand-in, not a device address:
+// host code reaches the memory only through the pointer hipGetSymbolAddress returns for the
+// current device (static_table_address below).
+static __device__ __align__(256) unsigned char scratch[RESHARD_STATIC_TABLE_BYTES];
 
 namespace reshard {
 
@@ -521,6 +529,62 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     PtrTable pt;
     fill_ptrs(plan, pt);
     const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
+    for (const TileClass &c : plan->classes) {
+        const uint32_t n = uint32_t(c.tiles.size());
+        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream)) return rc;
+        tiles += n;
+    }
+    return RESHARD_OK;
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char *g_static_ptr[kMaxDevices];  // device address of `scratch` on each device (set on first use there)
+uint64_t g_static_owner[kMaxDevices];      // serial of the plan whose table the array holds on that device (0: none)
+
+// Address of the static array on the current device `dev`; asked of the runtime once per device,
+// with that device current.
+int static_table_address(int dev, unsigned char **out) {
+    if (dev < 0 || dev >= kMaxDevices) return fail(RESHARD_ERR_UNSUPPORTED, "device index beyond the static table's bookkeeping");
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) return hip_fail(e, "hipGetSymbolAddress");
+        if (!ptr) return fail(RESHARD_ERR_HIP, "hipGetSymbolAddress returned no address");
+        g_static_ptr[dev] = static_cast<unsigned char *>(ptr);
+    }
+    *out = g_static_ptr[dev];
+    return RESHARD_OK;
+}
+}  // namespace
+
+// reshard_execute_noalloc: the launches of launch_repack with the tile table read from the static
+// device array.  No allocation anywhere: when the array does not hold this plan's table already
+// (first call, or another plan used it since) the table is copied there from the plan's host
+// memory with hipMemcpyAsync on `stream`, ahead of the kernels.
+int launch_repack_static(reshard_plan *plan, hipStream_t stream) {
+    if (int rc = query_device(plan)) return rc;
+    if (plan->info.table_bytes > int64_t(RESHARD_STATIC_TABLE_BYTES))
+        return fail(RESHARD_ERR_UNSUPPORTED, "the plan's tile table does not fit the static device array");
+    std::lock_guard<std::mutex> g(g_static_mutex);
+    unsigned char *base = nullptr;
+    if (int rc = static_table_address(plan->device, &base)) return rc;
+    if (g_static_owner[plan->device] != plan->serial) {
+        g_static_owner[plan->device] = 0;  // half a table belongs to nobody
+        size_t at = 0;
+        for (const TileClass &c : plan->classes) {
+            const size_t n = c.tiles.size() * sizeof(Tile);
+            if (!n) continue;
+            if (hipError_t e = hipMemcpyAsync(base + at, c.tiles.data(), n, hipMemcpyHostToDevice, stream))
+                return hip_fail(e, "hipMemcpyAsync of the tile table into the static array");
+            at += n;
+        }
+        g_static_owner[plan->device] = plan->serial;
+    }
+    const Tuning &tn = plan->tuning;
+    PtrTable pt;
+    fill_ptrs(plan, pt);
+    const Tile *tiles = reinterpret_cast<const Tile *>(base);
     for (const TileClass &c : plan->classes) {
         const uint32_t n = uint32_t(c.tiles.size());
         if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream)) return rc;

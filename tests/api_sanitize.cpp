@@ -38,6 +38,7 @@ int launch_repack(reshard_plan *p, hipStream_t) {
         for (const Tile &t : c.tiles) run_tile(p, t);
     return RESHARD_OK;
 }
+int launch_repack_static(reshard_plan *p, hipStream_t s) { return launch_repack(p, s); }
 int launch_source(reshard_plan *p, int src_index, hipStream_t) {
     for (const TileClass &c : p->classes)
         for (const Tile &t : c.tiles)
@@ -128,7 +129,7 @@ static int flows(int eb) {
     REQUIRE(reshard_swap_out(plan, nullptr) == RESHARD_ERR_HOST_OOM && fake_hip_host_bytes == 0);
     fake_hip_host_limit = -1;
     REQUIRE(reshard_swap_out(plan, nullptr) == RESHARD_OK && fake_hip_host_bytes == sbytes);
-    REQUIRE(reshard_execute(plan, sp.data(), D2.p.data(), nullptr) == RESHARD_OK);  // allowed while swapping out
+    REQUIRE(reshard_execute_noalloc(plan, sp.data(), D2.p.data(), nullptr) == RESHARD_OK);  // allowed while swapping out
     REQUIRE(D.same(D2));
     REQUIRE(reshard_mark_src_released(plan) == RESHARD_ERR_BAD_STATE);  // copies not waited for
     REQUIRE(reshard_swap_wait(plan) == RESHARD_OK);

@@ -28,6 +28,8 @@ extern uint3_ blockIdx, blockDim, gridDim;
 #define __forceinline__ inline
 #define __shared__ static
 #define __launch_bounds__(...)
+#define __align__(n) __attribute__((aligned(n)))
+#define HIP_SYMBOL(x) (&(x))
 #define __builtin_amdgcn_s_setprio(level) ((void)0)  // wave priority means nothing on the host
 static inline uint32_t __umulhi(uint32_t a, uint32_t b) { return uint32_t((uint64_t(a) * b) >> 32); }
 
@@ -93,5 +95,6 @@ inline void launch(dim3 grid, dim3 block, const std::function<void()> &body) {
 enum { hipDeviceAttributeMultiprocessorCount = 1 };
 inline hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }
 inline hipError_t hipDeviceGetAttribute(int *v, int, int) { *v = 4; return hipSuccess; }
+template <typename T> inline hipError_t hipGetSymbolAddress(void **p, T *symbol) { *p = const_cast<void *>(static_cast<const void *>(symbol)); return hipSuccess; }
 inline hipError_t hipMalloc(void **p, size_t n) { *p = std::malloc(n ? n : 1); return *p ? hipSuccess : hipErrorOutOfMemory; }
 inline hipError_t hipMemcpy(void *d, const void *s, size_t n, hipMemcpyKind) { std::memcpy(d, s, n); return hipSuccess; }

@@ -62,8 +62,11 @@ static int run(const reshard_model_spec &spec, const reshard_layout &src, const 
         for (int i = 0; i < ns; ++i)
             if (S[size_t(i)]) REQUIRE(reshard_execute_source(plan, i, S[size_t(i)], D.data(), nullptr) == RESHARD_OK);
     } else {
+        // alternately through the plan's own table and through the static array (which the
+        // previous case's table still fills: a new table must replace it)
+        static int flip = 0;
         std::vector<const void *> sp(S.begin(), S.end());
-        REQUIRE(reshard_execute(plan, sp.data(), D.data(), nullptr) == RESHARD_OK);
+        REQUIRE(((flip++ & 1) ? reshard_execute_noalloc : reshard_execute)(plan, sp.data(), D.data(), nullptr) == RESHARD_OK);
     }
     // what the descriptor table says, byte by byte
     reshard_plan_info info;
