@@ -227,6 +227,10 @@ typedef struct reshard_tuning {
     int32_t transpose_cols; /* ... and source columns; each 64, 128, 192, 256 or 512.  0, or a shape the plan's
                              * element size does not allow (the tile must fit 128 KiB): the default for
                              * that size (1 byte 512 x 256, 2 bytes 256 x 256, 4 bytes 128 x 256, 8 bytes 128 x 128) */
+    int32_t tail_pool_percent; /* 0 (default): every XCD walks its whole eighth of the copy tiles.  1..50: that share of
+                                  every eighth goes to a pool that the last workgroups of the grid drain in chunks, so
+                                  XCDs that finish early take over work of the slower ones (default launch shape only) */
+    int32_t tail_chunk_tiles;  /* tiles a pool workgroup takes per fetch, 1..1024 (default 16) */
 } reshard_tuning;
 
 /* Thread-local message of the last failing call on this thread ("" if none). */

@@ -70,6 +70,8 @@ struct Tuning {
                                   // bit 4: the copy kernel's load bursts run at raised wave priority
     int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;
     int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size
+    int tail_pool_percent = 0;    // copy kernel: share of every XCD's eighth of the table left to the shared tail pool
+    int tail_chunk_tiles = 16;    // tiles a pool workgroup takes per fetch
 };
 // The process-wide default that new plans copy (every plan then keeps its own).
 Tuning current_tuning();

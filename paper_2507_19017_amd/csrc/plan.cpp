@@ -217,6 +217,14 @@ int tuning_from_abi(const reshard_tuning *t, Tuning &out) {
         // 0 keeps the default like every other field; -1 asks for plain loads and stores, no barrier
         if (t->flags > 0) n.flags = t->flags;
         if (t->flags == -1) n.flags = 0;
+        if (t->tail_pool_percent < 0 || t->tail_pool_percent > 50)
+            return fail(RESHARD_ERR_INVALID_ARG, "tail_pool_percent must be in [0, 50]");
+        n.tail_pool_percent = t->tail_pool_percent;
+        if (t->tail_chunk_tiles) {
+            if (t->tail_chunk_tiles < 1 || t->tail_chunk_tiles > 1024)
+                return fail(RESHARD_ERR_INVALID_ARG, "tail_chunk_tiles must be in [1, 1024]");
+            n.tail_chunk_tiles = t->tail_chunk_tiles;
+        }
         // the one-tile copy kernel is built for every hint set at unroll 2, for none or all at the others
         const int hints = n.flags & 7;
         if (n.blocks_per_cu == 0 && n.unroll != 2 && hints != 0 && hints != 7)
@@ -234,6 +242,8 @@ void tuning_to_abi(const Tuning &t, reshard_tuning *out) {
     out->flags = t.flags;
     out->transpose_rows = t.transpose_rows;
     out->transpose_cols = t.transpose_cols;
+    out->tail_pool_percent = t.tail_pool_percent;
+    out->tail_chunk_tiles = t.tail_chunk_tiles;
 }
 
 int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_source, Side &out) {

@@ -131,6 +131,51 @@ __global__ __launch_bounds__(1024) void repack_copy_kernel(const Tile *__restric
     run_copy_tile<UNROLL, NT>(t, ptrs, threadIdx.x, blockDim.x);
 }
 
+// One tile per workgroup for the first part of every XCD's eighth of the table, and a shared pool
+// for the rest: the last `tail_blocks` workgroups of the grid (two per compute unit) are handed out
+// by the dispatcher once an XCD has started all its one-tile workgroups, and they take chunks of
+// `ct` tiles from per-XCD counters, their own XCD's pool first, then the others'.  An XCD that
+// moves bytes faster than its neighbours therefore ends up doing more of the pooled tiles instead
+// of idling until the slowest one has finished its fixed share.  `counters` (8 words) must be zero
+// when the kernel starts.  Every loop ends: a counter only grows, and a workgroup leaves a pool at
+// the first chunk index at or beyond that pool's chunk count.
+template <int UNROLL, int NT>
+__global__ __launch_bounds__(1024) void repack_copy_pool_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, PtrTable ptrs,
+                                                                uint32_t stat, uint32_t ct, uint32_t *__restrict__ counters) {
+    const uint32_t per = (ntiles + 7) >> 3;  // tiles in an XCD's eighth
+    const uint32_t b = blockIdx.x, x = b & 7;
+    if (b < stat * 8) {
+        const uint32_t ti = x * per + (b >> 3);
+        if (ti >= ntiles) return;
+        const Tile t = tiles[ti];
+        run_copy_tile<UNROLL, NT>(t, ptrs, threadIdx.x, blockDim.x);
+        return;
+    }
+    __shared__ uint32_t next;
+    for (uint32_t r = 0; r < 8; ++r) {
+        const uint32_t y = (x + r) & 7;
+        const uint32_t lo = y * per + stat, hi = min((y + 1) * per, ntiles);
+        if (lo >= hi) continue;  // the same for every lane
+        const uint32_t nchunks = (hi - lo + ct - 1) / ct;
+        for (;;) {
+            __syncthreads();  // every lane has read `next` of the round before
+            if (threadIdx.x == 0) next = atomicAdd(&counters[y], 1u);
+            __syncthreads();
+            const uint32_t c = __builtin_amdgcn_readfirstlane(next);
+            if (c >= nchunks) break;
+            const uint32_t first = lo + c * ct, last = min(first + ct, hi);
+            for (uint32_t ti = first; ti < last; ++ti) {
+                const Tile t = tiles[ti];
+                run_copy_tile<UNROLL, NT>(t, ptrs, threadIdx.x, blockDim.x);
+            }
+        }
+    }
+}
+
+__global__ void zero_words_kernel(uint32_t *p, uint32_t n) {
+    if (threadIdx.x < n) p[threadIdx.x] = 0;
+}
+
 // Persistent variant (a fixed number of workgroups per compute unit walking the
 // table with a static stride), kept selectable for comparison.
 template <int UNROLL, int NT>
@@ -418,7 +463,8 @@ int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
     size_t total = 0;
     for (auto *l : lists) total += l->size();
     void *mem = nullptr;
-    if (hipError_t e = hipMalloc(&mem, std::max<size_t>(total, 1) * sizeof(Tile))) {
+    // 256 bytes behind the table hold the counters of the copy kernel's shared tail pool
+    if (hipError_t e = hipMalloc(&mem, total * sizeof(Tile) + 256)) {
         (void)hipGetLastError();
         return fail(RESHARD_ERR_OOM, std::string("hipMalloc of the tile table: ") + hipGetErrorString(e));
     }
@@ -438,7 +484,7 @@ int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
 // Launches `n` tiles of class `tc` (copy, register transpose of one shape, generic transpose)
 // starting at device address `t`.
 int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc, const Tile *t, uint32_t n,
-                 const PtrTable &pt, hipStream_t stream) {
+                 const PtrTable &pt, hipStream_t stream, uint32_t *pool_counters = nullptr) {
     if (!n) return RESHARD_OK;
     const int cls = tc.kind;
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
@@ -447,6 +493,17 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc
     if (cls == 0 && tn.blocks_per_cu) {
         launch_copy(tn, dim3(std::min(n, wanted)), dim3(tn.block_threads), stream, t, n, pt);
         if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
+    } else if (cls == 0 && pool_counters && tn.tail_pool_percent > 0 && by_xcd && tn.unroll == 2 && (tn.flags & 23) == 23 &&
+               tn.block_threads == 1024 && uint64_t(n) * 1024 < 0xF0000000ull && n >= 64u * uint32_t(tn.tail_chunk_tiles)) {
+        // the shared tail pool (default hints, one launch, tables long enough to have a tail worth sharing)
+        const uint32_t per = (n + 7) >> 3, ct = uint32_t(tn.tail_chunk_tiles);
+        uint32_t pool = uint32_t(uint64_t(per) * uint32_t(tn.tail_pool_percent) / 100);
+        pool = std::min(per, (pool + ct - 1) / ct * ct);
+        const uint32_t stat = per - pool, tail_blocks = 8u * 2u * uint32_t(std::max(1, plan->num_cus / 8));
+        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, stream, pool_counters, 8u);
+        hipLaunchKernelGGL((repack_copy_pool_kernel<2, 15>), dim3(stat * 8 + tail_blocks), dim3(1024), 0, stream, t, n, pt, stat, ct,
+                           pool_counters);
+        if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel with a tail pool");
     } else if (cls == 0) {
         // a launch may not exceed 2^32 - 1 lanes in x, so very long tables go out in slices
         const uint32_t per_launch = (0xFFFFFFFFu / uint32_t(tn.block_threads)) & ~7u;
@@ -529,9 +586,10 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     PtrTable pt;
     fill_ptrs(plan, pt);
     const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
+    uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<char *>(plan->d_tiles) + size_t(plan->info.num_tiles) * sizeof(Tile));
     for (const TileClass &c : plan->classes) {
         const uint32_t n = uint32_t(c.tiles.size());
-        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream)) return rc;
+        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream, counters)) return rc;
         tiles += n;
     }
     return RESHARD_OK;

@@ -10,6 +10,7 @@
 
 #include <pthread.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <functional>
 #include <thread>
@@ -31,6 +32,9 @@ extern uint3_ blockIdx, blockDim, gridDim;
 #define __align__(n) __attribute__((aligned(n)))
 #define HIP_SYMBOL(x) (&(x))
 #define __builtin_amdgcn_s_setprio(level) ((void)0)  // wave priority means nothing on the host
+#define __builtin_amdgcn_readfirstlane(x) (x)
+static inline uint32_t atomicAdd(uint32_t *p, uint32_t v) { return __atomic_fetch_add(p, v, __ATOMIC_RELAXED); }
+using std::min;
 static inline uint32_t __umulhi(uint32_t a, uint32_t b) { return uint32_t((uint64_t(a) * b) >> 32); }
 
 namespace host_simt {

@@ -146,7 +146,8 @@ int main(int argc, char **argv) {
     moe.struct_size = sizeof moe;
     moe.family = RESHARD_MOE_GQA; moe.L = 1; moe.H = 336; moe.nq = 4; moe.nkv = 2; moe.d = 16; moe.V = 32; moe.has_embeddings = 1;
     moe.E = 2; moe.Ie = 208; moe.n_shared = 0;
-    reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{};
+    reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{}, pooled{};
+    pooled.tile_bytes = 4096; pooled.tail_pool_percent = 30; pooled.tail_chunk_tiles = 1;  // 1024-lane workgroups, a shared tail
     wide192.transpose_rows = 192; wide192.transpose_cols = 192;
     small.tile_bytes = 4096; small.block_threads = 64; small.unroll = 1; small.transpose_rows = 64; small.transpose_cols = 64;
     odd.tile_bytes = 8192; odd.block_threads = 256; odd.unroll = 2; odd.flags = 11; odd.transpose_rows = 128; odd.transpose_cols = 64;
@@ -156,7 +157,7 @@ int main(int argc, char **argv) {
         dense.elem_bytes = moe.elem_bytes = eb;
         // every launch shape at 2 bytes; the default and the smallest shapes at the other sizes
         std::vector<const reshard_tuning *> tunings{nullptr, &small};
-        if (eb == 2) tunings.insert(tunings.end(), {&odd, &persistent, &plain_order, &wide192});
+        if (eb == 2) tunings.insert(tunings.end(), {&odd, &persistent, &plain_order, &wide192, &pooled});
         for (const reshard_tuning *tn : tunings) {
             bad += run(dense, lay(RESHARD_TRAIN, 2, 2, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), tn, false);
             bad += run(moe, lay(RESHARD_TRAIN, 1, 1, 2, 1), lay(RESHARD_GEN, 2, 1, 1, 0), tn, false);   // transposing
@@ -166,6 +167,15 @@ int main(int argc, char **argv) {
         if (bad) break;
         std::printf("element size %d done: %ld launches, %ld workgroups so far\n", eb, host_simt::launches, host_simt::blocks_run);
         std::fflush(stdout);
+    }
+    if (!bad) {
+        // a table long enough for the copy kernel's shared tail pool: a zeroing launch and the pooled launch
+        reshard_model_spec wide = dense;
+        wide.elem_bytes = 2; wide.H = 256; wide.d = 64; wide.I = 688; wide.V = 1024;
+        const long before = host_simt::launches;
+        for (int twice = 0; twice < 2; ++twice)  // once through the plan's own table (pooled), once through the static array (not)
+            bad += run(wide, lay(RESHARD_TRAIN, 2, 1, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), &pooled, false);
+        if (host_simt::launches - before != 3) { std::printf("the tail pool was not used (%ld launches)\n", host_simt::launches - before); bad += 1; }
     }
     std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
     return bad ? 1 : 0;

@@ -116,6 +116,9 @@ TUNINGS = [
     dict(tile_bytes=16384, block_threads=1024, unroll=1, flags=31),
     dict(tile_bytes=65536, block_threads=1024, unroll=4, flags=15),
     dict(tile_bytes=4096, block_threads=256, unroll=2, flags=8),
+    dict(tile_bytes=4096, tail_pool_percent=25, tail_chunk_tiles=3),   # the shared tail pool: ragged last chunks
+    dict(tile_bytes=8192, tail_pool_percent=50, tail_chunk_tiles=1),
+    dict(tail_pool_percent=10),
 ]
 
 
@@ -737,6 +740,26 @@ def test_swap_wait_also_waits_for_a_repack_launched_during_the_swap_out():
         torch.cuda.synchronize()
         for s_, k in zip(src, keep):
             assert np.array_equal(s_.cpu().numpy(), k)
+
+
+def test_shared_tail_pool_at_full_size():
+    """The copy kernel's optional tail pool (the end of every XCD's share of the table is handed out
+    in chunks to whichever workgroups get there first) on the 15 GB plan: same bits as the default
+    launch, also on the second execute (the pool's counters are cleared by every launch)."""
+    wl = WORKLOADS["C1"]
+    print("case C1 tail pool", flush=True)
+    plan = Plan(wl["spec"], wl["src"], wl["dst"])
+    src = G.device_sources(plan, wl, "raw16")
+    one = G.device_destinations(plan)
+    plan.execute(G.ptrs(src), G.ptrs(one), G.stream_handle())
+    for pct, chunk in ((6, 16), (6, 16), (33, 5)):
+        plan.set_tuning(tail_pool_percent=pct, tail_chunk_tiles=chunk)
+        two = G.device_destinations(plan)
+        plan.execute(G.ptrs(src), G.ptrs(two), G.stream_handle())
+        torch.cuda.synchronize()
+        for a, b in zip(one, two):
+            assert torch.equal(a, b), (pct, chunk)
+        del two
 
 
 def test_a_table_too_long_for_one_launch_goes_out_in_slices():

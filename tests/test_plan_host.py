@@ -440,7 +440,7 @@ def test_tuning_is_validated():
     set_tuning()
     base = get_tuning()
     assert base == dict(tile_bytes=32768, block_threads=1024, blocks_per_cu=0, unroll=2, flags=31, transpose_rows=0,
-                        transpose_cols=0)
+                        transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16)
     set_tuning(tile_bytes=8192, unroll=4)
     assert get_tuning()["tile_bytes"] == 8192 and get_tuning()["unroll"] == 4
     w = WORKLOADS["C1"]
@@ -468,7 +468,7 @@ def test_every_plan_keeps_its_own_tuning():
     finally:
         set_tuning()
     assert a.get_tuning() == dict(tile_bytes=4096, block_threads=256, blocks_per_cu=0, unroll=1, flags=31,
-                                  transpose_rows=0, transpose_cols=0)
+                                  transpose_rows=0, transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16)
     assert b.get_tuning()["tile_bytes"] == 32768 and b.get_tuning()["unroll"] == 2
     assert c.get_tuning()["tile_bytes"] == 8192 and c.get_tuning()["unroll"] == 4 and c.get_tuning()["flags"] == 7
     assert a.info()["num_tiles"] > c.info()["num_tiles"] >= b.info()["num_tiles"]
