@@ -57,11 +57,18 @@ def parse():
                          "time) and report its peak HBM")
     ap.add_argument("--no-link-probe", action="store_true")
     ap.add_argument("--tuning", default="", help="e.g. tile_bytes=65536,unroll=8 (default 32768, 2)")
+    ap.add_argument("--ablate", default="",
+                    help="design ablation instead of the benchmark: tunings separated by ';' (e.g. "
+                         "'flags=31;flags=23;tile_bytes=65536,unroll=8'), one plan each on the SAME buffers, executed in "
+                         "turn for --ablate-rounds rounds (so that all variants see the same physical placement); "
+                         "prints one JSON line with the event-timed kernel time of each")
+    ap.add_argument("--ablate-rounds", type=int, default=10)
     return ap.parse_args()
 
 
-def say(a, *msg):
-    if a.verbose:
+def say(a, *msg, detail=False):
+    """Progress on stderr: one line per phase always, per-step lines with --verbose."""
+    if a.verbose or not detail:
         print("[bench %.1fs]" % (clock() - T_START), *msg, file=sys.stderr, flush=True)
 
 
@@ -120,15 +127,18 @@ def cpu_baseline(wl, host_src, whole):
         sizes, used = fast.buffer_sizes(wl["spec"], dst_lay), fast.buffers_used(wl["spec"], dst_lay)
     dst = [np.empty(n // 2, dtype=np.int16) if u else None for n, u in zip(sizes, used)]
     threads = fast.max_threads()
+    t0 = clock()
     fast.reshard(wl["spec"], wl["src"], dst_lay, host_src, dst, threads=threads)  # touches the destination pages
-    runs = 3 if whole else 1
+    first = clock() - t0
+    # bounded: about half a minute of wall time at most (element-wise transposes run at a tenth of the copies' rate)
+    runs = (3 if first < 4.0 else 1) if whole else 1
     dt = None
     for _ in range(runs):
         t0 = clock()
         nbytes = fast.reshard(wl["spec"], wl["src"], dst_lay, host_src, dst, threads=threads)
         dt = min(dt or 1e30, clock() - t0)
     dt1 = None
-    if whole and 2 * nbytes / 20e9 < 40.0:  # one core moves some tens of GB/s: skipped where it would take too long
+    if whole and dt * threads * 0.5 < 30.0:  # one core: skipped where it would take too long
         t0 = clock()
         fast.reshard(wl["spec"], wl["src"], dst_lay, host_src, dst, threads=1)
         dt1 = clock() - t0
@@ -268,7 +278,7 @@ class Run:
                 self.first_s.append(t2b - t2)
                 self.freed.append(before - after)
                 say(a, "%s step: kernel %.3f ms, swap-out %.1f GB/s, swap-in %.1f GB/s" % (
-                    self.wl["name"], self.kernel_ms[-1], self.src_bytes / (t1 - t0) / 1e9, self.src_bytes / (t3 - t2) / 1e9))
+                    self.wl["name"], self.kernel_ms[-1], self.src_bytes / (t1 - t0) / 1e9, self.src_bytes / (t3 - t2) / 1e9), detail=True)
 
     def repack_only(self, n):
         """n more executes back to back, event-timed one by one (no swap in between)."""
@@ -511,6 +521,48 @@ def streaming_flow(run, tuning):
     return out
 
 
+def ablation(a, run):
+    """The repack under several tunings on the same source and destination buffers, in turn.
+    Dispatch order (for reading a kernel trace of this run): one warm-up execute per variant in
+    the order given, then `rounds` rounds of one execute per variant in the same order."""
+    from paper_2507_19017_amd import Plan
+
+    wl, torch = run.wl, run.torch
+    variants = [v for v in a.ablate.split(";") if v]
+    plans = []
+    for v in variants:
+        tn = {k: int(x) for k, x in (kv.split("=") for kv in v.split(","))}
+        p = Plan(wl["spec"], wl["src"], wl["dst"], tuning=tn)
+        p.prepare()
+        plans.append(p)
+    for p in plans:
+        p.execute(run.ptrs(run.src), run.ptrs(run.dst), run.h)
+    torch.cuda.synchronize()
+    times = [[] for _ in plans]
+    for _ in range(a.ablate_rounds):
+        evs = []
+        for p in plans:
+            e0, e1 = run.events()
+            e0.record(run.stream)
+            p.execute(run.ptrs(run.src), run.ptrs(run.dst), run.h)
+            e1.record(run.stream)
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        for t, (e0, e1) in zip(times, evs):
+            t.append(e0.elapsed_time(e1))
+    moved = run.info["bytes_moved"]
+    base = sum(times[0]) / len(times[0])
+    out = []
+    for v, p, t in zip(variants, plans, times):
+        avg = sum(t) / len(t)
+        out.append({"tuning": v, "tiles": p.info()["num_tiles"], "kernel_ms_avg": round(avg, 4), "kernel_ms_min": round(min(t), 4),
+                    "GBps": round(2 * moved / avg / 1e6, 1), "frac": round(2 * moved / avg / 1e6 / HBM_PEAK_GBPS, 4),
+                    "vs_first_pct": round(100 * (base / avg - 1), 2)})
+        p.destroy()
+    return {"ablation": out, "workload": "%s: %s" % (wl["name"], wl["note"]), "bytes_moved_one_way": moved,
+            "rounds": a.ablate_rounds, "order": "one warm-up execute per variant, then rounds of one execute per variant, in the order given"}
+
+
 def recorded_traffic(name, tuning_now):
     """HBM bytes per execute from earlier rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, each scaled
     by the same counter's reading for a plain copy of known size), kept in profiles/.  A recorded
@@ -557,7 +609,12 @@ def main():
 
     # ------------------------------------------------------------ headline workload ----
     say(a, "filling", a.workload)
+    if a.ablate:
+        a.no_swap = True
     run = Run(a, a.workload, tuning)
+    if a.ablate:
+        print(json.dumps(ablation(a, run)))
+        return
     say(a, "warm-up")
     for _ in range(a.warmup):
         run.step(False)

@@ -45,6 +45,23 @@ __device__ __forceinline__ V ld(const char *p) {
     if (NT & 1) return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
     return *reinterpret_cast<const V *>(p);
 }
+// Every store of the repack kernels goes through st().  A build with RESHARD_COUNT_WRITES (a test
+// build, never the product) turns each of them into one increment per destination BYTE instead:
+// run on zeroed shadow buffers of the destinations' sizes, the same kernels, tiles and index
+// arithmetic then leave the number of times every byte would have been written (the byte's own
+// counter in the 32-bit word that holds it goes up by one; it wraps only after 255 writes).
+#ifdef RESHARD_COUNT_WRITES
+template <typename V, int NT>
+__device__ __forceinline__ void st(char *p, V) {
+    const uintptr_t a = reinterpret_cast<uintptr_t>(p);
+    if (sizeof(V) >= 4) {
+        for (size_t w = 0; w < sizeof(V) / 4; ++w) atomicAdd(reinterpret_cast<uint32_t *>(a) + w, 0x01010101u);
+    } else {
+        const uint32_t ones = sizeof(V) == 2 ? 0x0101u : 0x01u;
+        atomicAdd(reinterpret_cast<uint32_t *>(a & ~uintptr_t(3)), ones << (8 * (a & 3)));
+    }
+}
+#else
 template <typename V, int NT>
 __device__ __forceinline__ void st(char *p, V v) {
     if (NT & 2)
@@ -52,6 +69,7 @@ __device__ __forceinline__ void st(char *p, V v) {
     else
         *reinterpret_cast<V *>(p) = v;
 }
+#endif
 
 // Copies one tile: n = rows*row_units vector units; unit u is column u % row_units
 // of row u / row_units.  magic == 0 marks a single contiguous row.
@@ -230,7 +248,7 @@ __global__ __launch_bounds__(256) void repack_transpose_kernel(const Tile *__res
                 for (int j = 0; j < VE; ++j) e[j] = lds[(ig * VE + j) * PITCH + k];
                 u32x4 v;
                 __builtin_memcpy(&v, e, 16);
-                *reinterpret_cast<u32x4 *>(d + uint64_t(k) * t.dst_stride + ig * 16) = v;
+                st<u32x4, 0>(d + uint64_t(k) * t.dst_stride + ig * 16, v);
             }
         } else {
             for (uint32_t u = tid; u < TD * TD; u += 256) {
@@ -242,7 +260,7 @@ __global__ __launch_bounds__(256) void repack_transpose_kernel(const Tile *__res
             for (uint32_t u = tid; u < TD * TD; u += 256) {
                 const uint32_t k = u / TD, i = u % TD;
                 if (i < nr && k < nc)
-                    *reinterpret_cast<E *>(d + uint64_t(k) * t.dst_stride + i * sizeof(E)) = lds[i * PITCH + k];
+                    st<E, 0>(d + uint64_t(k) * t.dst_stride + i * sizeof(E), lds[i * PITCH + k]);
             }
         }
         __syncthreads();  // the tile buffer is reused by the next tile
@@ -324,7 +342,7 @@ void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, 
     for (int q = 0; q < ROUNDS * VE; ++q) {
         const uint32_t u = tid + q * THREADS, ic = u % IC, k = u / IC;
         const u32x4 v = lds[k * IC + (ic ^ ((k / VE) & 7))];
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(d + uint64_t(k) * t.dst_stride + ic * 16));
+        st<u32x4, 2>(d + uint64_t(k) * t.dst_stride + ic * 16, v);
     }
 }
 

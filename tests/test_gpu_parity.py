@@ -217,6 +217,70 @@ def test_degenerate_and_ragged_shapes(case):
     assert plan.info()["bytes_moved"] > 0
 
 
+def _count_writes_on_device(wl, tuning=None):
+    """Runs the plan's real kernels from the counting build on zeroed shadow destinations and
+    returns (per-byte write counts, the definition oracle's layout of the destination)."""
+    import contextlib
+
+    from paper_2507_19017_amd.build import COUNT_LIB
+
+    @contextlib.contextmanager
+    def counting_library():
+        keep = (binding._lib, binding._LIB_PATH)
+        binding._lib, binding._LIB_PATH = None, COUNT_LIB
+        try:
+            yield
+        finally:
+            binding._lib, binding._LIB_PATH = keep
+
+    with counting_library():
+        plan = Plan(wl["spec"], wl["src"], wl["dst"], tuning=tuning)
+        try:
+            src = G.device_sources(plan, wl, "raw16")
+            shadow = [torch.zeros(n // 2, dtype=torch.int16, device="cuda") if u else None
+                      for n, u in zip(plan.buf_bytes(1), plan.buf_used(1))]
+            plan.execute(G.ptrs(src), G.ptrs(shadow), G.stream_handle())
+            torch.cuda.synchronize()
+            counts = [None if s_ is None else s_.cpu().numpy().view(np.uint8) for s_ in shadow]
+        finally:
+            plan.destroy()  # by the library that made it
+    return counts, locate.Layout(wl["spec"], wl["dst"])
+
+
+@pytest.mark.parametrize("name", sorted(TINY) + ["C0"])
+def test_every_destination_byte_is_written_exactly_once_on_the_device(name):
+    """The kernels themselves, built with counting stores: every byte of every stored destination
+    tensor is written exactly once by the device code, and no byte of a gap or of vocabulary padding
+    is written at all.  Checked for the default tuning and for small tiles with the shared tail pool."""
+    wl = {**TINY, **WORKLOADS}[name]
+    print("case exactly once", name, flush=True)
+    for tuning in (None, dict(tile_bytes=4096, transpose_rows=64, transpose_cols=64, tail_pool_percent=20, tail_chunk_tiles=2)):
+        counts, D = _count_writes_on_device(wl, tuning)
+        for b, c in enumerate(counts):
+            if c is None:
+                continue
+            want = np.zeros(D.buf_bytes[b], dtype=np.uint8)
+            for off, nb in D.owned(b):
+                want[off:off + nb] = 1
+            assert np.array_equal(c, want), f"{name} buffer {b}: {int((c != want).sum())} bytes not written exactly once"
+
+
+def test_exactly_once_on_the_device_for_random_midsize_workloads():
+    """The same check on the random generator's workloads with widths scaled by 16 (every element
+    size, ragged ends, transposing tiles of several shapes)."""
+    for seed in range(0, 24):
+        wl = random_case(seed, 16)
+        print("case exactly once random x16", seed, flush=True)
+        counts, D = _count_writes_on_device(wl)
+        for b, c in enumerate(counts):
+            if c is None:
+                continue
+            want = np.zeros(D.buf_bytes[b], dtype=np.uint8)
+            for off, nb in D.owned(b):
+                want[off:off + nb] = 1
+            assert np.array_equal(c, want), f"seed {seed} buffer {b}"
+
+
 def test_copy_baseline_matches_memcpy():
     n = 64 * 1024 * 1024 + 4096 + 16
     a = fill_buffer(n, 7, "cuda", "raw16")
