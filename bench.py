@@ -330,6 +330,7 @@ class Run:
             "repack_GBps": round(2 * self.info["bytes_moved"] / k / 1e9, 1), "repack_kernel_ms_avg": round(k * 1e3, 4),
             "repack_frac_of_peak": round(2 * self.info["bytes_moved"] / k / 1e9 / HBM_PEAK_GBPS, 4),
             "swap_out_GBps": round(self.src_bytes / so / 1e9, 2),
+            "swap_out_GBps_best_step": round(self.src_bytes / min(out_s) / 1e9, 2),
             "concurrency_evidence": {
                 "kernel_done_ms_after_swap_out_was_queued": round(sum(kdone_ms) / n, 3),
                 "first_buffer_copy_done_ms_after_swap_out_was_queued": round(sum(first_ms) / n, 3),
@@ -415,6 +416,8 @@ class Run:
             so, si = sum(self.out_s) / len(self.out_s), sum(self.in_s) / len(self.in_s)
             out["swap"] = {"bytes_each_way": self.src_bytes, "out_GBps": round(self.src_bytes / so / 1e9, 2),
                            "in_GBps": round(self.src_bytes / si / 1e9, 2),
+                           "out_GBps_best_step": round(self.src_bytes / min(self.out_s) / 1e9, 2),
+                           "in_GBps_best_step": round(self.src_bytes / min(self.in_s) / 1e9, 2),
                            "in_first_buffer_ms": round(sum(self.first_s) / len(self.first_s) * 1e3, 2),
                            "in_all_buffers_ms": round(si * 1e3, 2)}
             if link:
@@ -669,7 +672,7 @@ def main():
         entry = r.summary(link)
         if a.overlap_steps > 0 and not a.no_swap:
             ov = r.overlap(min(2, a.overlap_steps))
-            entry["overlap"] = {k: ov[k] for k in ("repack_GBps", "repack_frac_of_peak", "swap_out_GBps")}
+            entry["overlap"] = {k: ov[k] for k in ("repack_GBps", "repack_frac_of_peak", "swap_out_GBps", "swap_out_GBps_best_step")}
         if not a.no_cpu_baseline and not a.no_swap:
             entry["cpu_baseline"] = cpu_baseline(r.wl, r.host_sources(), whole=False)
         r.close()

@@ -219,7 +219,12 @@ typedef struct reshard_tuning {
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
                                barrier between a tile's load burst and its store burst, bit 3: each XCD
                                walks a contiguous eighth of the tile table, bit 4: the copy kernel issues its
-                               loads at raised wave priority (with bits 0-2 all set; default 31); -1 = none.
+                               loads at raised wave priority (with bits 0-2 all set), bit 5: woven order for the
+                               copy tiles that are one contiguous run: the eight XCDs share every group of 8
+                               tiles, 1 KiB apart, instead of walking an eighth of the table each (1024-lane
+                               workgroups, two loads per lane whatever `unroll` says; tiles of several pitched
+                               rows keep the order bit 3 selects and go out in a launch of their own).
+                               Default 63 (all); -1 = none.
                                With unroll 1, 4 or 8 bits 0-2 must be all set or all clear.  A persistent
                                grid has no barrier and no raised priority, and its accesses are
                                non-temporal when bits 0 and 1 are both set */

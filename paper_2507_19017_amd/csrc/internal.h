@@ -65,9 +65,10 @@ struct Tuning {
     int block_threads = 1024;
     int blocks_per_cu = 0;        // 0: one tile per workgroup; > 0: persistent grid
     int unroll = 2;               // 22 VGPRs: two 1024-lane workgroups fit a compute unit (8 takes 69: one)
-    int flags = 31;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
+    int flags = 63;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
                                   // bit 3: each XCD walks a contiguous eighth of the tile table,
-                                  // bit 4: the copy kernel's load bursts run at raised wave priority
+                                  // bit 4: the copy kernel's load bursts run at raised wave priority,
+                                  // bit 5: copy tiles in the woven order (the XCDs share every group of 8 tiles)
     int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;
     int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size
     int tail_pool_percent = 0;    // copy kernel: share of every XCD's eighth of the table left to the shared tail pool
@@ -120,6 +121,9 @@ static_assert(uint64_t(generic_transpose_grid(0x7FFFFFF0u, 0xFFFFFFFFu)) * 256 <
 struct TileClass {
     int kind = 0;            // 0 strided copy, 1 register transpose of rows x cols elements, 2 generic transpose
     int rows = 0, cols = 0;  // kind 1 only
+    uint32_t max_units = 0;  // kind 0 only: the most vector units any of the tiles holds
+    uint32_t num_blocks = 0; // kind 0 only: the first num_blocks tiles hold several pitched rows each, the rest one contiguous row
+    bool runs_wide = true;   // kind 0 only: every single-row tile moves 16-byte units
     std::vector<Tile> tiles;
 };
 
@@ -158,7 +162,7 @@ struct reshard_plan {
     void *d_tiles = nullptr;  // the classes' tiles one after another
     int num_cus = 0;
     // streaming (created by the first execute_source): the tiles regrouped by source buffer
-    struct SrcSlice { std::vector<uint32_t> first, count; };  // per class
+    struct SrcSlice { std::vector<uint32_t> first, count; uint32_t copy_blocks = 0; };  // per class; row-block tiles leading the copy class
     std::vector<SrcSlice> src_slices;
     std::vector<reshard::Tile> by_src_tiles;
     void *d_by_src = nullptr;

@@ -213,7 +213,7 @@ int tuning_from_abi(const reshard_tuning *t, Tuning &out) {
                 return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 192, 256 or 512");
         if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
         if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
-        if (t->flags < -1 || t->flags > 31) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 31]");
+        if (t->flags < -1 || t->flags > 63) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 63]");
         // 0 keeps the default like every other field; -1 asks for plain loads and stores, no barrier
         if (t->flags > 0) n.flags = t->flags;
         if (t->flags == -1) n.flags = 0;
@@ -542,6 +542,7 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
     classes[1].cols = fast_cols;
     TileClass generic;
     generic.kind = 2;
+    std::vector<Tile> run_tiles, block_tiles;  // copy tiles of one contiguous row / of several pitched rows
     auto reg_class = [&](int ti, int tk) -> std::vector<Tile> & {
         for (size_t c = 1; c < classes.size(); ++c)
             if (classes[c].rows == ti && classes[c].cols == tk) return classes[c].tiles;
@@ -625,7 +626,8 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
             }
             continue;
         }
-        std::vector<Tile> &copy_tiles = classes[0].tiles;  // (no class is added below: the reference holds)
+        // single rows (contiguous runs) and row blocks are kept apart: the copy class lists the row blocks first
+        std::vector<Tile> &copy_tiles = d.rows == 1 ? run_tiles : block_tiles;
         // widest vector that every row start and the row length allow
         int vec = 16;
         auto misfit = [&](int v) {
@@ -665,6 +667,17 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
                 t.dst_off = uint64_t(d.dst_off + r * d.dst_stride);
                 copy_tiles.push_back(t);
             }
+        }
+    }
+    {
+        TileClass &c = classes[0];
+        c.num_blocks = uint32_t(block_tiles.size());
+        c.tiles = std::move(block_tiles);
+        c.tiles.insert(c.tiles.end(), run_tiles.begin(), run_tiles.end());
+        for (size_t i = 0; i < c.tiles.size(); ++i) {
+            const Tile &t = c.tiles[i];
+            c.max_units = std::max(c.max_units, t.rows * t.row_units);
+            if (i >= c.num_blocks) c.runs_wide = c.runs_wide && t.vec_log2 == 4;
         }
     }
     classes.push_back(std::move(generic));

@@ -190,6 +190,87 @@ __global__ __launch_bounds__(1024) void repack_copy_pool_kernel(const Tile *__re
     }
 }
 
+// Loads / stores one vector unit of 2^lg bytes (the same for a whole wave); narrower units ride in v[0].
+template <int NT>
+__device__ __forceinline__ u32x4 ld_unit(const char *p, uint32_t lg) {
+    u32x4 r = {0, 0, 0, 0};
+    switch (lg) {
+        case 4: r = ld<u32x4, NT>(p); break;
+        case 3: { const u32x2 t = ld<u32x2, NT>(p); r[0] = t[0]; r[1] = t[1]; break; }
+        case 2: r[0] = ld<uint32_t, NT>(p); break;
+        case 1: r[0] = ld<uint16_t, NT>(p); break;
+        default: r[0] = ld<uint8_t, NT>(p); break;
+    }
+    return r;
+}
+template <int NT>
+__device__ __forceinline__ void st_unit(char *p, u32x4 v, uint32_t lg) {
+    switch (lg) {
+        case 4: st<u32x4, NT>(p, v); break;
+        case 3: { u32x2 t; t[0] = v[0]; t[1] = v[1]; st<u32x2, NT>(p, t); break; }
+        case 2: st<uint32_t, NT>(p, v[0]); break;
+        case 1: st<uint16_t, NT>(p, uint16_t(v[0])); break;
+        default: st<uint8_t, NT>(p, uint8_t(v[0])); break;
+    }
+}
+
+// "Woven" order: the eight XCDs walk the table TOGETHER.  Workgroups 8g .. 8g+7 (one per XCD) share
+// tiles 8g .. 8g+7; a tile's vector units are cut into granules of 64 consecutive units (what one
+// wave moves with one instruction: 1 KiB for 16-byte units) and the workgroup on XCD x takes the
+// granules whose index is x modulo 8, of all eight tiles.  The chip then streams through ONE compact
+// window of the table with its XCDs interleaved 1 KiB apart, instead of eight windows an eighth of
+// the table apart.  `slots` = granules of one tile a workgroup may have to take (the same for the
+// whole launch, so every wave runs the same number of rounds and reaches every barrier): 4 for
+// tiles of at most 2048 units.  Wave w handles slots w, w + 16, ...; slot s is granule
+// x + 8 * (s % slots) of tile 8g + s / slots.
+// WIDE: every tile of the launch moves 16-byte units, so the loads and stores are straight-line code
+// and both loads of a wave are in flight together; with units of mixed widths the width is a
+// branch per unit, after which the compiler waits for the first load before it issues the second
+// (measured 10 % slower), so that form only serves the rare plans that have narrow units.
+template <int NT, bool WIDE>
+__global__ __launch_bounds__(1024) void repack_copy_woven_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, PtrTable ptrs,
+                                                                 uint32_t slots) {
+    const uint32_t x = blockIdx.x & 7, first_tile = (blockIdx.x >> 3) * 8;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const uint32_t nslots = slots * 8;
+    for (uint32_t s0 = 0; s0 < nslots; s0 += 32) {  // 16 waves x 2 slots per round; the same trip count for every lane
+        u32x4 v[2];
+        char *dp[2];
+        uint32_t lg[2];
+        if (NT & 8) __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint32_t s = __builtin_amdgcn_readfirstlane(s0 + wave + 16 * k);
+            const uint32_t ti = first_tile + s / slots;
+            dp[k] = nullptr;
+            lg[k] = 0;
+            if (s < nslots && ti < ntiles) {  // the same for every lane of the wave
+                const Tile t = tiles[ti];
+                const uint32_t n = t.rows * t.row_units;
+                const uint32_t u = (x + 8 * (s % slots)) * 64 + lane;
+                if (u < n) {
+                    const uint32_t row = __umulhi(u, t.magic);
+                    const uint32_t col = u - row * t.row_units;
+                    lg[k] = t.vec_log2;
+                    const uint32_t shift = WIDE ? 4u : uint32_t(t.vec_log2);
+                    const char *sp = ptrs.p[t.src_buf] + t.src_off + (uint64_t(row) * t.src_stride + (uint64_t(col) << shift));
+                    if (WIDE) v[k] = ld<u32x4, NT>(sp);
+                    else v[k] = ld_unit<NT>(sp, t.vec_log2);
+                    dp[k] = ptrs.p[t.dst_buf] + t.dst_off + (uint64_t(row) * t.dst_stride + (uint64_t(col) << shift));
+                }
+            }
+        }
+        if (NT & 8) __builtin_amdgcn_s_setprio(0);
+        if (NT & 4) __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (dp[k]) {
+                if (WIDE) st<u32x4, NT>(dp[k], v[k]);
+                else st_unit<NT>(dp[k], v[k], lg[k]);
+            }
+    }
+}
+
 __global__ void zero_words_kernel(uint32_t *p, uint32_t n) {
     if (threadIdx.x < n) p[threadIdx.x] = 0;
 }
@@ -502,15 +583,48 @@ int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
 // Launches `n` tiles of class `tc` (copy, register transpose of one shape, generic transpose)
 // starting at device address `t`.
 int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc, const Tile *t, uint32_t n,
-                 const PtrTable &pt, hipStream_t stream, uint32_t *pool_counters = nullptr) {
+                 const PtrTable &pt, hipStream_t stream, uint32_t n_blocks, uint32_t *pool_counters = nullptr) {
     if (!n) return RESHARD_OK;
     const int cls = tc.kind;
+    if (cls == 0 && (tn.flags & 32) && tn.block_threads == 1024 && n_blocks > 0 && n_blocks < n) {
+        // woven order for the contiguous runs only: tiles of several pitched rows go out first, in the XCD-contiguous order
+        Tuning blocks = tn;
+        blocks.flags &= ~32;
+        blocks.tail_pool_percent = 0;
+        if (int rc = launch_class(plan, blocks, tc, t, n_blocks, pt, stream, n_blocks)) return rc;
+        return launch_class(plan, tn, tc, t + n_blocks, n - n_blocks, pt, stream, 0);
+    }
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
     const uint32_t wanted = tn.blocks_per_cu ? uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu) : 0xFFFFFFFFu;
     const int by_xcd = (tn.flags & 8) ? 1 : 0;
     if (cls == 0 && tn.blocks_per_cu) {
         launch_copy(tn, dim3(std::min(n, wanted)), dim3(tn.block_threads), stream, t, n, pt);
         if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
+    } else if (cls == 0 && (tn.flags & 32) && tn.block_threads == 1024 && n_blocks == 0) {
+        // the woven order: 8 workgroups (one per XCD) per group of 8 tiles
+        const uint32_t slots = std::max<uint32_t>(1, (tc.max_units + 511) / 512);
+        const uint32_t per_launch = (0xFFFFFFFFu / 1024u) & ~7u;  // tiles per launch: a multiple of 8, within the lanes of one launch
+        for (uint32_t first = 0; first < n; first += per_launch) {
+            const uint32_t m = std::min(per_launch, n - first);
+            const dim3 grid((m + 7) / 8 * 8), block(1024);
+            // built for: plain accesses (with or without the barrier), non-temporal on both sides (without,
+            // with the barrier, with the barrier and raised load priority)
+            const int h = tn.flags & 7;
+            const int hints = h == 7 ? ((tn.flags & 16) ? 15 : 7) : h == 3 ? 3 : (h & 4) ? 4 : 0;
+#define RESHARD_WOVEN(NT)                                                                                                            \
+    if (tc.runs_wide) hipLaunchKernelGGL((repack_copy_woven_kernel<NT, true>), grid, block, 0, stream, t + first, m, pt, slots);    \
+    else hipLaunchKernelGGL((repack_copy_woven_kernel<NT, false>), grid, block, 0, stream, t + first, m, pt, slots);               \
+    break;
+            switch (hints) {
+                case 15: RESHARD_WOVEN(15)
+                case 7: RESHARD_WOVEN(7)
+                case 3: RESHARD_WOVEN(3)
+                case 4: RESHARD_WOVEN(4)
+                default: RESHARD_WOVEN(0)
+            }
+#undef RESHARD_WOVEN
+            if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the woven copy kernel");
+        }
     } else if (cls == 0 && pool_counters && tn.tail_pool_percent > 0 && by_xcd && tn.unroll == 2 && (tn.flags & 23) == 23 &&
                tn.block_threads == 1024 && uint64_t(n) * 1024 < 0xF0000000ull && n >= 64u * uint32_t(tn.tail_chunk_tiles)) {
         // the shared tail pool (default hints, one launch, tables long enough to have a tail worth sharing)
@@ -607,7 +721,7 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<char *>(plan->d_tiles) + size_t(plan->info.num_tiles) * sizeof(Tile));
     for (const TileClass &c : plan->classes) {
         const uint32_t n = uint32_t(c.tiles.size());
-        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream, counters)) return rc;
+        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream, c.num_blocks, counters)) return rc;
         tiles += n;
     }
     return RESHARD_OK;
@@ -663,7 +777,7 @@ int launch_repack_static(reshard_plan *plan, hipStream_t stream) {
     const Tile *tiles = reinterpret_cast<const Tile *>(base);
     for (const TileClass &c : plan->classes) {
         const uint32_t n = uint32_t(c.tiles.size());
-        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream)) return rc;
+        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream, c.num_blocks)) return rc;
         tiles += n;
     }
     return RESHARD_OK;
@@ -682,6 +796,8 @@ int ensure_by_source_table(reshard_plan *plan) {
     plan->src_slices.assign(ns, empty);
     for (size_t cls = 0; cls < nc; ++cls)
         for (const Tile &t : plan->classes[cls].tiles) ++plan->src_slices[t.src_buf].count[cls];
+    for (uint32_t i = 0; i < plan->classes[0].num_blocks; ++i)  // table order is kept inside a slice: its row blocks lead as well
+        ++plan->src_slices[plan->classes[0].tiles[i].src_buf].copy_blocks;
     uint32_t at = 0;
     for (size_t b = 0; b < ns; ++b)
         for (size_t cls = 0; cls < nc; ++cls) {
@@ -703,7 +819,7 @@ int launch_source(reshard_plan *plan, int src_index, hipStream_t stream) {
     const Tile *base = static_cast<const Tile *>(plan->d_by_src);
     const reshard_plan::SrcSlice &sl = plan->src_slices[size_t(plan->src_slot[size_t(src_index)])];
     for (size_t cls = 0; cls < plan->classes.size(); ++cls)
-        if (int rc = launch_class(plan, tn, plan->classes[cls], base + sl.first[cls], sl.count[cls], pt, stream)) return rc;
+        if (int rc = launch_class(plan, tn, plan->classes[cls], base + sl.first[cls], sl.count[cls], pt, stream, cls == 0 ? sl.copy_blocks : 0)) return rc;
     return RESHARD_OK;
 }
 

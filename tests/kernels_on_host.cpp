@@ -146,7 +146,9 @@ int main(int argc, char **argv) {
     moe.struct_size = sizeof moe;
     moe.family = RESHARD_MOE_GQA; moe.L = 1; moe.H = 336; moe.nq = 4; moe.nkv = 2; moe.d = 16; moe.V = 32; moe.has_embeddings = 1;
     moe.E = 2; moe.Ie = 208; moe.n_shared = 0;
-    reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{}, pooled{};
+    reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{}, pooled{}, woven{}, woven_small{};
+    woven.flags = 63;                                   // the XCDs share every group of 8 tiles
+    woven_small.flags = 36; woven_small.tile_bytes = 4096;  // plain accesses with the barrier, tiles of 256 units
     pooled.tile_bytes = 4096; pooled.tail_pool_percent = 30; pooled.tail_chunk_tiles = 1;  // 1024-lane workgroups, a shared tail
     wide192.transpose_rows = 192; wide192.transpose_cols = 192;
     small.tile_bytes = 4096; small.block_threads = 64; small.unroll = 1; small.transpose_rows = 64; small.transpose_cols = 64;
@@ -156,7 +158,7 @@ int main(int argc, char **argv) {
     for (int eb : {2, 1, 4, 8}) {
         dense.elem_bytes = moe.elem_bytes = eb;
         // every launch shape at 2 bytes; the default and the smallest shapes at the other sizes
-        std::vector<const reshard_tuning *> tunings{nullptr, &small};
+        std::vector<const reshard_tuning *> tunings{nullptr, &small, &woven, &woven_small};
         if (eb == 2) tunings.insert(tunings.end(), {&odd, &persistent, &plain_order, &wide192, &pooled});
         for (const reshard_tuning *tn : tunings) {
             bad += run(dense, lay(RESHARD_TRAIN, 2, 2, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), tn, false);

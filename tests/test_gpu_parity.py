@@ -119,6 +119,10 @@ TUNINGS = [
     dict(tile_bytes=4096, tail_pool_percent=25, tail_chunk_tiles=3),   # the shared tail pool: ragged last chunks
     dict(tile_bytes=8192, tail_pool_percent=50, tail_chunk_tiles=1),
     dict(tail_pool_percent=10),
+    dict(flags=63),                                         # the woven order (XCDs share every group of 8 tiles)
+    dict(flags=36, tile_bytes=4096),
+    dict(flags=35, tile_bytes=131072),
+    dict(flags=39, tile_bytes=8192),
 ]
 
 
