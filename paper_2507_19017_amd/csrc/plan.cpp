@@ -627,7 +627,6 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
             continue;
         }
         // single rows (contiguous runs) and row blocks are kept apart: the copy class lists the row blocks first
-        std::vector<Tile> &copy_tiles = d.rows == 1 ? run_tiles : block_tiles;
         // widest vector that every row start and the row length allow
         int vec = 16;
         auto misfit = [&](int v) {
@@ -646,16 +645,26 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
         t.vec_log2 = uint8_t(lg);
         const int64_t max_units = std::max<int64_t>(1, std::min<int64_t>(tile_bytes / vec, kMaxTileUnits));
         if (d.rows == 1 || units >= max_units || units == 1) {
-            // long rows: cut every row into runs
-            for (int64_t r = 0; r < d.rows; ++r)
-                for (int64_t u = 0; u < units; u += max_units) {
+            // long rows: cut every row into runs.  The cuts fall on multiples of the tile size in the DESTINATION
+            // buffer (a short first piece brings the row there), so that in the woven order, where the XCD on
+            // which a 1 KiB granule lands is its index in the tile modulo 8, an XCD always writes the same
+            // 1 KiB residues of every 8 KiB of the buffer, whatever run the tile belongs to.
+            const int64_t tile_span = max_units * vec;
+            for (int64_t r = 0; r < d.rows; ++r) {
+                const int64_t row_dst = d.dst_off + r * d.dst_stride;
+                int64_t head = ((tile_span - row_dst % tile_span) % tile_span) / vec;
+                if (head >= units) head = 0;
+                for (int64_t u = 0; u < units;) {
+                    const int64_t len = (u == 0 && head > 0) ? head : std::min(max_units, units - u);
                     t.rows = 1;
-                    t.row_units = uint32_t(std::min(max_units, units - u));
+                    t.row_units = uint32_t(len);
                     t.magic = 0;
                     t.src_off = uint64_t(d.src_off + r * d.src_stride + u * vec);
-                    t.dst_off = uint64_t(d.dst_off + r * d.dst_stride + u * vec);
-                    copy_tiles.push_back(t);
+                    t.dst_off = uint64_t(row_dst + u * vec);
+                    run_tiles.push_back(t);
+                    u += len;
                 }
+            }
         } else {
             // short rows: several whole rows per tile
             const int64_t rows_per_tile = std::max<int64_t>(1, max_units / units);
@@ -665,7 +674,7 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
                 t.magic = t.rows == 1 ? 0u : uint32_t((uint64_t(1) << 32) / uint64_t(units)) + 1u;
                 t.src_off = uint64_t(d.src_off + r * d.src_stride);
                 t.dst_off = uint64_t(d.dst_off + r * d.dst_stride);
-                copy_tiles.push_back(t);
+                (t.rows == 1 ? run_tiles : block_tiles).push_back(t);
             }
         }
     }

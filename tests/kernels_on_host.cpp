@@ -149,7 +149,7 @@ int main(int argc, char **argv) {
     reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{}, pooled{}, woven{}, woven_small{};
     woven.flags = 63;                                   // the XCDs share every group of 8 tiles
     woven_small.flags = 36; woven_small.tile_bytes = 4096;  // plain accesses with the barrier, tiles of 256 units
-    pooled.tile_bytes = 4096; pooled.tail_pool_percent = 30; pooled.tail_chunk_tiles = 1;  // 1024-lane workgroups, a shared tail
+    pooled.tile_bytes = 4096; pooled.flags = 31; pooled.tail_pool_percent = 30; pooled.tail_chunk_tiles = 1;  // 1024-lane workgroups, a shared tail
     wide192.transpose_rows = 192; wide192.transpose_cols = 192;
     small.tile_bytes = 4096; small.block_threads = 64; small.unroll = 1; small.transpose_rows = 64; small.transpose_cols = 64;
     odd.tile_bytes = 8192; odd.block_threads = 256; odd.unroll = 2; odd.flags = 11; odd.transpose_rows = 128; odd.transpose_cols = 64;

@@ -116,9 +116,9 @@ TUNINGS = [
     dict(tile_bytes=16384, block_threads=1024, unroll=1, flags=31),
     dict(tile_bytes=65536, block_threads=1024, unroll=4, flags=15),
     dict(tile_bytes=4096, block_threads=256, unroll=2, flags=8),
-    dict(tile_bytes=4096, tail_pool_percent=25, tail_chunk_tiles=3),   # the shared tail pool: ragged last chunks
-    dict(tile_bytes=8192, tail_pool_percent=50, tail_chunk_tiles=1),
-    dict(tail_pool_percent=10),
+    dict(tile_bytes=4096, flags=31, tail_pool_percent=25, tail_chunk_tiles=3),   # the shared tail pool: ragged last chunks
+    dict(tile_bytes=8192, flags=31, tail_pool_percent=50, tail_chunk_tiles=1),
+    dict(flags=31, tail_pool_percent=10),
     dict(flags=63),                                         # the woven order (XCDs share every group of 8 tiles)
     dict(flags=36, tile_bytes=4096),
     dict(flags=35, tile_bytes=131072),
@@ -258,7 +258,7 @@ def test_every_destination_byte_is_written_exactly_once_on_the_device(name):
     is written at all.  Checked for the default tuning and for small tiles with the shared tail pool."""
     wl = {**TINY, **WORKLOADS}[name]
     print("case exactly once", name, flush=True)
-    for tuning in (None, dict(tile_bytes=4096, transpose_rows=64, transpose_cols=64, tail_pool_percent=20, tail_chunk_tiles=2)):
+    for tuning in (None, dict(tile_bytes=4096, transpose_rows=64, transpose_cols=64, flags=31, tail_pool_percent=20, tail_chunk_tiles=2)):
         counts, D = _count_writes_on_device(wl, tuning)
         for b, c in enumerate(counts):
             if c is None:
@@ -821,7 +821,7 @@ def test_shared_tail_pool_at_full_size():
     one = G.device_destinations(plan)
     plan.execute(G.ptrs(src), G.ptrs(one), G.stream_handle())
     for pct, chunk in ((6, 16), (6, 16), (33, 5)):
-        plan.set_tuning(tail_pool_percent=pct, tail_chunk_tiles=chunk)
+        plan.set_tuning(flags=31, tail_pool_percent=pct, tail_chunk_tiles=chunk)
         two = G.device_destinations(plan)
         plan.execute(G.ptrs(src), G.ptrs(two), G.stream_handle())
         torch.cuda.synchronize()
