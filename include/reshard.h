@@ -218,8 +218,8 @@ typedef struct reshard_tuning {
     int32_t unroll;         /* 16-byte loads in flight per lane: 1, 2, 4 or 8 (default 2) */
     int32_t flags;          /* bit 0: non-temporal loads, bit 1: non-temporal stores, bit 2: workgroup
                                barrier between a tile's load burst and its store burst, bit 3: each XCD
-                               walks a contiguous eighth of the tile table, bit 4: the copy kernel issues its
-                               loads at raised wave priority (with bits 0-2 all set), bit 5: woven order for the
+                               walks a contiguous eighth of the tile table, bit 4: the one-tile copy kernel issues
+                               its loads at raised wave priority (with bits 0-2 all set), bit 5: woven order for the
                                copy tiles that are one contiguous run: the eight XCDs share every group of 8
                                tiles, 1 KiB apart, instead of walking an eighth of the table each (1024-lane
                                workgroups, two loads per lane whatever `unroll` says; tiles of several pitched

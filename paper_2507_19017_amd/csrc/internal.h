@@ -67,7 +67,7 @@ struct Tuning {
     int unroll = 2;               // 22 VGPRs: two 1024-lane workgroups fit a compute unit (8 takes 69: one)
     int flags = 63;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
                                   // bit 3: each XCD walks a contiguous eighth of the tile table,
-                                  // bit 4: the copy kernel's load bursts run at raised wave priority,
+                                  // bit 4: the one-tile copy kernel's load bursts run at raised wave priority,
                                   // bit 5: copy tiles in the woven order (the XCDs share every group of 8 tiles)
     int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;
     int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size

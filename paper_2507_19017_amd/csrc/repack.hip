@@ -237,7 +237,6 @@ __global__ __launch_bounds__(1024) void repack_copy_woven_kernel(const Tile *__r
         u32x4 v[2];
         char *dp[2];
         uint32_t lg[2];
-        if (NT & 8) __builtin_amdgcn_s_setprio(3);
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const uint32_t s = __builtin_amdgcn_readfirstlane(s0 + wave + 16 * k);
@@ -260,7 +259,6 @@ __global__ __launch_bounds__(1024) void repack_copy_woven_kernel(const Tile *__r
                 }
             }
         }
-        if (NT & 8) __builtin_amdgcn_s_setprio(0);
         if (NT & 4) __syncthreads();
 #pragma unroll
         for (int k = 0; k < 2; ++k)
@@ -400,7 +398,7 @@ void repack_transpose16_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, 
     char *d = ptrs.p[t.dst_buf] + t.dst_off;
     const uint32_t tid = threadIdx.x;
     u32x4 r[ROUNDS][VE];
-    __builtin_amdgcn_s_setprio(3);  // like the copy kernel: waves that issue loads go first
+    __builtin_amdgcn_s_setprio(3);  // like the one-tile copy kernel: waves that issue loads go first (no measurable effect here)
 #pragma unroll
     for (int q = 0; q < ROUNDS; ++q) {
         const uint32_t b = tid + q * THREADS, kb = b % KB, ib = b / KB;
@@ -607,16 +605,16 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc
         for (uint32_t first = 0; first < n; first += per_launch) {
             const uint32_t m = std::min(per_launch, n - first);
             const dim3 grid((m + 7) / 8 * 8), block(1024);
-            // built for: plain accesses (with or without the barrier), non-temporal on both sides (without,
-            // with the barrier, with the barrier and raised load priority)
+            // built for: plain accesses (with or without the barrier), non-temporal on both sides (with or without
+            // it).  Never at raised load priority: with it this kernel ran 2 to 4.5 % slower and unevenly
+            // (C2, C3P), while the one-tile kernel next to it gains from it (C1: 3 %).
             const int h = tn.flags & 7;
-            const int hints = h == 7 ? ((tn.flags & 16) ? 15 : 7) : h == 3 ? 3 : (h & 4) ? 4 : 0;
+            const int hints = h == 7 ? 7 : h == 3 ? 3 : (h & 4) ? 4 : 0;
 #define RESHARD_WOVEN(NT)                                                                                                            \
     if (tc.runs_wide) hipLaunchKernelGGL((repack_copy_woven_kernel<NT, true>), grid, block, 0, stream, t + first, m, pt, slots);    \
     else hipLaunchKernelGGL((repack_copy_woven_kernel<NT, false>), grid, block, 0, stream, t + first, m, pt, slots);               \
     break;
             switch (hints) {
-                case 15: RESHARD_WOVEN(15)
                 case 7: RESHARD_WOVEN(7)
                 case 3: RESHARD_WOVEN(3)
                 case 4: RESHARD_WOVEN(4)
