@@ -12,7 +12,8 @@ behind the repack, so that the kernel time in the record is the kernel alone and
 rocprofv3 trace of the same command agrees with it.  After the timed region the same
 workload runs a few steps with the swap-out queued BEFORE the repack (the two overlap:
 both only read the sources), and the other task workloads (C1, C3, C3P, C4) each run
-a few steps of their own; all of that goes into the same record.  Prints ONE JSON line.
+a few steps of their own, each in a fresh child process started once this one has given its
+buffers back; all of that goes into the same record.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--others C1,C3,C3P,C4]
 """
@@ -63,6 +64,9 @@ def parse():
                          "turn for --ablate-rounds rounds (so that all variants see the same physical placement); "
                          "prints one JSON line with the event-timed kernel time of each")
     ap.add_argument("--ablate-rounds", type=int, default=10)
+    ap.add_argument("--as-entry", action="store_true",
+                    help="(used by the bench itself for --others) measure --workload alone and print it as one entry of `workloads`")
+    ap.add_argument("--link", default="", help="(with --as-entry) the link probe's d2h,h2d GB/s from the parent run")
     return ap.parse_args()
 
 
@@ -168,29 +172,6 @@ def link_probe(nbytes=1 << 30):
             best[name] = max(best[name], nbytes / (clock() - t0) / 1e9)
     del dev, host
     return best
-
-
-def settle(link, limit_s=6.0):
-    """After a workload has given back tens of GB of HBM and pinned memory the driver is busy
-    for a second or two and copies run slow meanwhile; wait (bounded) until a plain pinned copy
-    is back at the link's rate, so that the next workload's figures are its own."""
-    import torch
-
-    if not link:
-        return 0.0
-    n = 256 << 20
-    dev = torch.empty(n, dtype=torch.uint8, device="cuda")
-    host = torch.empty(n, dtype=torch.uint8, pin_memory=True)
-    t_begin = clock()
-    while clock() - t_begin < limit_s:
-        torch.cuda.synchronize()
-        t0 = clock()
-        host.copy_(dev, non_blocking=True)
-        torch.cuda.synchronize()
-        if n / (clock() - t0) / 1e9 > 0.93 * link["d2h"]:
-            break
-    del dev, host
-    return clock() - t_begin
 
 
 def source_hash():
@@ -302,6 +283,7 @@ class Run:
         for _ in range(n):
             e0, e1 = self.events()
             torch.cuda.synchronize()
+            time.sleep(0.3)             # untimed: the copy engines go idle after the swap-in just before
             t0 = clock()
             plan.swap_out(h)            # D2H starts now on the side stream
             e0.record(self.stream)
@@ -568,6 +550,29 @@ def ablation(a, run):
             "rounds": a.ablate_rounds, "order": "one warm-up execute per variant, then rounds of (one untimed execute of the last variant, one timed execute per variant in the order given)"}
 
 
+def entry_of(a, run):
+    """One entry of the record's `workloads` array: a warm-up step and a few full steps, more executes of the
+    repack alone, the overlapped order, and the CPU oracle on a bounded sample."""
+    link = None
+    if a.link:
+        d2h, h2d = (float(x) for x in a.link.split(","))
+        link = {"d2h": d2h, "h2d": h2d}
+    for _ in range(a.warmup):
+        run.step(False)
+    for _ in range(a.steps):
+        run.step(True)
+    run.kernel_ms += run.repack_only(6)[1:]  # more samples of the kernel alone, back to back
+    entry = run.summary(link)
+    if a.overlap_steps > 0 and not a.no_swap:
+        ov = run.overlap(a.overlap_steps)
+        say(a, run.wl["name"], "overlap:", json.dumps(ov), detail=True)
+        entry["overlap"] = {k: ov[k] for k in ("repack_GBps", "repack_frac_of_peak", "swap_out_GBps", "swap_out_GBps_best_step")}
+    if not a.no_cpu_baseline and not a.no_swap:
+        entry["cpu_baseline"] = cpu_baseline(run.wl, run.host_sources(), whole=False)
+    run.close()
+    return entry
+
+
 def recorded_traffic(name, tuning_now):
     """HBM bytes per execute from earlier rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, each scaled
     by the same counter's reading for a plain copy of known size), kept in profiles/.  A recorded
@@ -620,6 +625,9 @@ def main():
     if a.ablate:
         print(json.dumps(ablation(a, run)))
         return
+    if a.as_entry:
+        print(json.dumps(entry_of(a, run)))
+        return
     say(a, "warm-up")
     for _ in range(a.warmup):
         run.step(False)
@@ -631,11 +639,13 @@ def main():
     total_s = clock() - t_begin
     say(a, "timed region done: %.2f s" % total_s)
 
-    driver_freed = None if a.no_swap else run.driver_free_check()
-    link = None if a.no_link_probe or a.no_swap else link_probe()
-    head = run.summary(link)
+    # the overlapped order comes before anything gives memory back to the driver: for some seconds after tens of
+    # GB were freed (the driver clears them) host copies on this machine run at half rate now and then
     overlap = run.overlap(a.overlap_steps) if (a.overlap_steps > 0 and not a.no_swap) else None
     say(a, "overlap done")
+    link = None if a.no_link_probe or a.no_swap else link_probe()
+    head = run.summary(link)
+    driver_freed = None if a.no_swap else run.driver_free_check()
     framework = framework_baseline(run) if a.framework_baseline else None
     streaming = streaming_flow(run, tuning) if a.streaming else None
     probes = run.probes()
@@ -662,23 +672,23 @@ def main():
     say(a, "headline workload done")
 
     # ------------------------------------------------------------ the other task workloads ----
+    # Each in a process of its own, one after the other (this one holds no buffers any more): the same conditions
+    # as the headline workload had, and nothing one workload frees disturbs the next one's copies.
+    import subprocess
+
     workloads = [dict(head, swap_overlaps_repack=False)]
     for name in others:
-        waited = settle(link)
-        say(a, "workload", name, "(waited %.2f s for the link to settle)" % waited)
-        r = Run(a, name, tuning)
-        r.step(False)
-        for _ in range(max(1, a.other_steps)):
-            r.step(True)
-        r.kernel_ms += r.repack_only(6)[1:]  # more samples of the kernel alone, back to back
-        entry = r.summary(link)
-        if a.overlap_steps > 0 and not a.no_swap:
-            ov = r.overlap(min(2, a.overlap_steps))
-            entry["overlap"] = {k: ov[k] for k in ("repack_GBps", "repack_frac_of_peak", "swap_out_GBps", "swap_out_GBps_best_step")}
-        if not a.no_cpu_baseline and not a.no_swap:
-            entry["cpu_baseline"] = cpu_baseline(r.wl, r.host_sources(), whole=False)
-        r.close()
-        workloads.append(entry)
+        say(a, "workload", name)
+        cmd = [sys.executable, os.path.abspath(__file__), "--as-entry", "--workload", name, "--steps", str(max(1, a.other_steps)),
+               "--warmup", "1", "--overlap-steps", str(min(2, a.overlap_steps))]
+        cmd += ["--tuning", a.tuning] if a.tuning else []
+        cmd += [flag for flag, on in (("--no-swap", a.no_swap), ("--no-cpu-baseline", a.no_cpu_baseline), ("--verbose", a.verbose)) if on]
+        if link:
+            cmd += ["--link", "%.3f,%.3f" % (link["d2h"], link["h2d"])]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)  # its progress lines go to this process's stderr
+        if res.returncode != 0:
+            raise SystemExit("bench.py: the run of workload %s failed with exit code %d" % (name, res.returncode))
+        workloads.append(json.loads(res.stdout.strip().splitlines()[-1]))
 
     out = {
         "metric": "reshard repack GB/s (read+write)",
