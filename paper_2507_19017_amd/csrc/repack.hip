@@ -3,14 +3,21 @@
 // Step 2 of the allgather-swap technique (paper section "Allgather-Swap
 // Technique": select and copy the weight slices needed for generation) is pure
 // data movement, so the bound is HBM bandwidth: there is no MFMA work here.
-// Design: the plan is a flat table of equal-work tiles, one workgroup of 1024
-// lanes per tile (a persistent grid is selectable; it measured slower), tiles
-// dealt so that each of the 8 XCDs walks one contiguous eighth of the table.  Copy
-// tiles move 16 bytes per lane per access with several loads in flight per lane
-// before the first store; rows shorter than a tile are addressed through a flat
-// unit index split by a multiply-high, so all 64 lanes of a wavefront stay busy
-// for any row length.  Transposing tiles are staged through LDS so that both the
-// global loads and the global stores stay contiguous.
+// Design: the plan is a flat table of equal-work tiles of three kinds, each with
+// a kernel of its own, all with 1024-lane workgroups and 16-byte non-temporal
+// accesses, two loads in flight per lane before the first store.
+//   - Contiguous runs (most of the bytes): the "woven" order.  The eight XCDs
+//     share every group of eight tiles, each taking the 1 KiB granules whose
+//     index is its own number modulo 8, so the chip walks one window of memory
+//     with every XCD on fixed 1 KiB residues of the address space.
+//   - Tiles of several pitched rows: one workgroup per tile (a persistent grid
+//     is selectable; it measured slower), each XCD walking one contiguous eighth
+//     of the table; rows shorter than a tile are addressed through a flat unit
+//     index split by a multiply-high, so all 64 lanes of a wavefront stay busy
+//     for any row length.
+//   - Transposing tiles: one workgroup per tile in the same XCD-contiguous
+//     order, 8 x 8 blocks transposed in registers and staged through LDS so that
+//     both the global loads and the global stores stay contiguous.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
