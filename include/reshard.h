@@ -226,8 +226,8 @@ typedef struct reshard_tuning {
                                rows keep the order bit 3 selects and go out in a launch of their own).
                                Default 63 (all); -1 = none.
                                With unroll 1, 4 or 8 bits 0-2 must be all set or all clear.  A persistent
-                               grid has no barrier and no raised priority, and its accesses are
-                               non-temporal when bits 0 and 1 are both set */
+                               grid moves 2 loads per lane, has no barrier and no raised priority, and its
+                               accesses are non-temporal when bits 0 and 1 are both set */
     int32_t transpose_rows; /* shape of a register-transposed tile in elements: source rows ... */
     int32_t transpose_cols; /* ... and source columns; each 64, 128, 192, 256 or 512.  0, or a shape the plan's
                              * element size does not allow (the tile must fit 128 KiB): the default for
@@ -320,8 +320,9 @@ int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshard_tile *out
 
 /*
  * Step 2 (slice selection and copy), run time: asynchronous kernel launches on `stream` (one for the
- * strided copies, one per transposing tile shape in use; three or fewer for most plans, a
- * dozen at most) that fill every used destination buffer from the source buffers.
+ * copy tiles of several pitched rows, one for the contiguous runs, one per transposing tile
+ * shape in use; three or fewer for most plans, a dozen at most) that fill every used destination
+ * buffer from the source buffers.
  * src_ptrs[num_src_bufs], dst_ptrs[num_dst_bufs]: device pointers, each aligned to
  * 256 bytes and at least buf_bytes long; NULL allowed only where used == 0.  The
  * two sets must not overlap.  The memory stays caller-owned and must remain valid

@@ -488,7 +488,8 @@ __global__ __launch_bounds__(1024) void write_probe_kernel(char *__restrict__ ds
 
 // The copy kernel is built for: every hint set (bits 0-2, and bit 4 on top of all three) at
 // 2 loads per lane, the default; none or all of them at 1, 4 and 8 loads per lane.  The persistent
-// grid has no barrier and no priority; its accesses are non-temporal when bits 0 and 1 are both set.
+// grid has 2 loads per lane, no barrier and no priority; its accesses are non-temporal when bits 0
+// and 1 are both set.
 template <int U, int NT>
 void launch_one_tile(dim3 block, hipStream_t st, const Tile *tiles, uint32_t n, const PtrTable &pt, int by_xcd) {
     hipLaunchKernelGGL((repack_copy_kernel<U, NT>), dim3(by_xcd ? (n + 7) / 8 * 8 : n), block, 0, st, tiles, n, pt, by_xcd);
@@ -507,14 +508,8 @@ void launch_persistent(bool nt, dim3 grid, dim3 block, hipStream_t st, const Til
 void launch_copy(const Tuning &tn, dim3 grid, dim3 block, hipStream_t st, const Tile *tiles,
                  uint32_t n, const PtrTable &pt) {
     const int by_xcd = (tn.flags & 8) ? 1 : 0;
-    if (grid.x != n) {  // persistent grid
-        const bool nt = (tn.flags & 3) == 3;
-        switch (tn.unroll) {
-            case 1: launch_persistent<1>(nt, grid, block, st, tiles, n, pt); break;
-            case 2: launch_persistent<2>(nt, grid, block, st, tiles, n, pt); break;
-            case 4: launch_persistent<4>(nt, grid, block, st, tiles, n, pt); break;
-            default: launch_persistent<8>(nt, grid, block, st, tiles, n, pt); break;
-        }
+    if (grid.x != n) {  // persistent grid, kept for comparison: two loads per lane whatever `unroll` says
+        launch_persistent<2>((tn.flags & 3) == 3, grid, block, st, tiles, n, pt);
         return;
     }
     // raised load priority exists on top of the full set of hints only
