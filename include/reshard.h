@@ -165,9 +165,20 @@ typedef struct reshard_desc {
  * kind 0: `rows` rows of `row_units` vectors of `vec_bytes` bytes each, row pitches as given.
  * kind 1: transposing tile of `rows` source rows x `row_units` elements of `vec_bytes` bytes:
  *     dst[dst_off + k*dst_stride + i*vec_bytes] = src[src_off + i*src_stride + k*vec_bytes]
+ * kind 2: gathering tile: `rows` consecutive vectors of `vec_bytes` bytes of the destination, made of
+ *     segments of `row_units` vectors taken from `sources` consecutive source buffers in turn
+ *     (the shards of a weight split along its rows' direction, merged side by side):
+ *     for u in [0, rows): w = phase + u, seg = w / row_units, c = w % row_units,
+ *         dst[dst_off + u*vec_bytes] = src(src_buf + seg % sources)[src_off + (seg / sources)*src_stride + c*vec_bytes]
+ *     (vec_bytes bytes each; dst_stride is 0).
  * tile_class: 0 copy kernel; 1 register-transpose kernel, a whole tile of the plan's preferred
  * shape; 2 register-transpose kernel, a whole tile of another shape the kernel is built for
  * (rows x row_units says which); 3 generic transpose kernel (at most 64 x 64, any extent).
+ * order: some bytes are in the table twice, cut two ways, and an execute launches one of the two:
+ *     0 launched by every execute; 1 launched unless the plan gathers; 2 launched only when it
+ *     does (the kind 2 tiles).  A plan gathers when its tuning has flags bits 5 and 6 set,
+ *     block_threads 1024 and blocks_per_cu 0.  The tiles of order 0 and 1
+ *     together, and those of order 0 and 2 together, each write every destination byte exactly once.
  */
 typedef struct reshard_tile {
     int32_t src_buf, dst_buf;
@@ -175,13 +186,14 @@ typedef struct reshard_tile {
     int64_t src_off, dst_off;
     int64_t rows, row_units;
     int64_t src_stride, dst_stride;
-    int32_t vec_bytes, reserved_;
+    int32_t vec_bytes, order;
+    int64_t sources, phase; /* kind 2 only (else 1 and 0) */
 } reshard_tile;
 
 typedef struct reshard_plan_info {
     int32_t num_src_bufs, num_dst_bufs;
     int64_t num_descs;      /* copy descriptors after merging */
-    int64_t num_tiles;      /* device work items the descriptors were cut into */
+    int64_t num_tiles;      /* records of the tile table (device work items; see reshard_tile.order) */
     int64_t num_transpose_tiles; /* of which transposing tiles (register path + generic path) */
     int64_t bytes_moved;    /* destination bytes written by one execute (== bytes read) */
     int64_t table_bytes;    /* device memory held by the plan (tile table) */
@@ -223,8 +235,12 @@ typedef struct reshard_tuning {
                                copy tiles that are one contiguous run: the eight XCDs share every group of 8
                                tiles, 1 KiB apart, instead of walking an eighth of the table each (1024-lane
                                workgroups, two loads per lane whatever `unroll` says; tiles of several pitched
-                               rows keep the order bit 3 selects and go out in a launch of their own).
-                               Default 63 (all); -1 = none.
+                               rows keep the order bit 3 selects and go out in a launch of their own),
+                               bit 6 (with bit 5): where shards are merged side by side, or narrower rows packed
+                               out of a wider source, into one contiguous stretch of the destination (rows of
+                               at least 1 KiB), that stretch goes out in the woven order as well, as gathered
+                               tiles that read the sources in turn, instead of as tiles of pitched rows.
+                               Default 127 (all); -1 = none.
                                With unroll 1, 4 or 8 bits 0-2 must be all set or all clear.  A persistent
                                grid moves 2 loads per lane, has no barrier and no raised priority, and its
                                accesses are non-temporal when bits 0 and 1 are both set */

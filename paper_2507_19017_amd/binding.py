@@ -51,7 +51,7 @@ class TileView(C.Structure):
     _fields_ = [("src_buf", C.c_int32), ("dst_buf", C.c_int32), ("kind", C.c_int32), ("tile_class", C.c_int32),
                 ("src_off", C.c_int64), ("dst_off", C.c_int64), ("rows", C.c_int64), ("row_units", C.c_int64),
                 ("src_stride", C.c_int64), ("dst_stride", C.c_int64), ("vec_bytes", C.c_int32),
-                ("reserved_", C.c_int32)]
+                ("order", C.c_int32), ("sources", C.c_int64), ("phase", C.c_int64)]
 
 
 class PlanInfo(C.Structure):

@@ -426,7 +426,21 @@ extern "C" int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshar
     out->src_stride = t.src_stride;
     out->dst_stride = t.dst_stride;
     out->vec_bytes = 1 << t.vec_log2;
-    out->reserved_ = 0;
+    out->order = 0;
+    out->sources = 1;
+    out->phase = 0;
+    if (c.kind == 0) {
+        // row blocks that have a gathered form go out in the XCD-contiguous order only, that form in the woven order only
+        if (at >= size_t(c.num_blocks - c.num_regathered) && at < size_t(c.num_blocks)) out->order = 1;
+        if (t.kind == 2) {
+            const uint32_t c0 = t.src_stride & 0xFFFFu, j0 = (t.src_stride >> 16) & 0xFFu, lk = t.src_stride >> 24;
+            out->order = 2;
+            out->sources = int64_t(1) << lk;
+            out->phase = int64_t(j0) * t.row_units + c0;
+            out->src_stride = int64_t(t.dst_stride) * 16;
+            out->dst_stride = 0;
+        }
+    }
     return RESHARD_OK;
 }
 

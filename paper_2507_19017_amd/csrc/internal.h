@@ -43,14 +43,17 @@ struct Side {
 struct alignas(16) Tile {
     uint64_t src_off;     // bytes from the start of the source buffer
     uint64_t dst_off;     // bytes from the start of the destination buffer
-    uint32_t src_stride;  // bytes between rows
-    uint32_t dst_stride;
-    uint32_t rows;        // copy: rows of the tile.  transpose: source rows (i extent)
-    uint32_t row_units;   // copy: vector units per row.  transpose: elements per source row (k extent)
-    uint32_t magic;       // copy: floor(2^32/row_units)+1, or 0 when rows == 1
-    uint16_t src_buf;
+    uint32_t src_stride;  // bytes between rows.  gather: c0 | j0 << 16 | log2(k) << 24 (see below)
+    uint32_t dst_stride;  //                      gather: 16-byte units between consecutive segments of one source
+    uint32_t rows;        // copy: rows of the tile.  transpose: source rows (i extent).  gather: units of the tile
+    uint32_t row_units;   // copy: vector units per row.  transpose: elements per source row (k extent).  gather: units per segment
+    uint32_t magic;       // copy and gather: floor(2^32/row_units)+1, or 0 when rows == 1
+    uint16_t src_buf;     // gather: the first of k consecutive entries of the pointer table
     uint16_t dst_buf;     // index into the pointer table (already offset past the sources)
-    uint8_t kind;         // 0 strided copy, 1 transposing copy
+    uint8_t kind;         // 0 strided copy, 1 transposing copy, 2 gathering copy: the tile is `rows` consecutive 16-byte
+                          // units of the destination, made of segments of row_units units that come from k = 2^n
+                          // sources in turn (source j of a group of k, then the next segment of every source);
+                          // the tile starts c0 units into a segment of source j0, and src_off is that segment's row
     uint8_t vec_log2;     // copy: log2 of the vector width in bytes.  transpose: log2(elem_bytes)
     uint8_t pad_[2];
 };
@@ -65,10 +68,11 @@ struct Tuning {
     int block_threads = 1024;
     int blocks_per_cu = 0;        // 0: one tile per workgroup; > 0: persistent grid
     int unroll = 2;               // 22 VGPRs: two 1024-lane workgroups fit a compute unit (8 takes 69: one)
-    int flags = 63;               // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
+    int flags = 127;              // bit 0/1: non-temporal loads/stores, bit 2: barrier between bursts,
                                   // bit 3: each XCD walks a contiguous eighth of the tile table,
                                   // bit 4: the one-tile copy kernel's load bursts run at raised wave priority,
-                                  // bit 5: copy tiles in the woven order (the XCDs share every group of 8 tiles)
+                                  // bit 5: copy tiles in the woven order (the XCDs share every group of 8 tiles),
+                                  // bit 6: with it, side-by-side merges as gathered tiles
     int transpose_rows = 0;       // register-transposed tiles: rows x cols of the source, in elements;
     int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size
     int tail_pool_percent = 0;    // copy kernel: share of every XCD's eighth of the table left to the shared tail pool
@@ -121,9 +125,13 @@ static_assert(uint64_t(generic_transpose_grid(0x7FFFFFF0u, 0xFFFFFFFFu)) * 256 <
 struct TileClass {
     int kind = 0;            // 0 strided copy, 1 register transpose of rows x cols elements, 2 generic transpose
     int rows = 0, cols = 0;  // kind 1 only
-    uint32_t max_units = 0;  // kind 0 only: the most vector units any of the tiles holds
-    uint32_t num_blocks = 0; // kind 0 only: the first num_blocks tiles hold several pitched rows each, the rest one contiguous row
-    bool runs_wide = true;   // kind 0 only: every single-row tile moves 16-byte units
+    // kind 0 only: tiles = [row blocks | row blocks that have a gathered form | runs | gathered].  The first
+    // num_blocks tiles hold pitched rows, the next num_runs one contiguous row each; those two parts are the
+    // whole work.  The last num_gathered tiles (Tile::kind 2) are the same bytes as the num_regathered last
+    // row blocks, cut along the contiguous destination instead: the woven order launches them in their place.
+    uint32_t max_units = 0;  // the most vector units any of the tiles holds
+    uint32_t num_blocks = 0, num_regathered = 0, num_runs = 0, num_gathered = 0;
+    bool runs_wide = true;   // every tile behind the row blocks moves 16-byte units
     std::vector<Tile> tiles;
 };
 
@@ -163,6 +171,7 @@ struct reshard_plan {
     int num_cus = 0;
     // streaming (created by the first execute_source): the tiles regrouped by source buffer
     struct SrcSlice { std::vector<uint32_t> first, count; uint32_t copy_blocks = 0; };  // per class; row-block tiles leading the copy class
+                                                                                        // (gathered tiles read several sources: not here)
     std::vector<SrcSlice> src_slices;
     std::vector<reshard::Tile> by_src_tiles;
     void *d_by_src = nullptr;

@@ -213,7 +213,7 @@ int tuning_from_abi(const reshard_tuning *t, Tuning &out) {
                 return fail(RESHARD_ERR_INVALID_ARG, "transpose_rows / transpose_cols must be 64, 128, 192, 256 or 512");
         if (t->transpose_rows) n.transpose_rows = t->transpose_rows;
         if (t->transpose_cols) n.transpose_cols = t->transpose_cols;
-        if (t->flags < -1 || t->flags > 63) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 63]");
+        if (t->flags < -1 || t->flags > 127) return fail(RESHARD_ERR_INVALID_ARG, "flags must be in [-1, 127]");
         // 0 keeps the default like every other field; -1 asks for plain loads and stores, no barrier
         if (t->flags > 0) n.flags = t->flags;
         if (t->flags == -1) n.flags = 0;
@@ -542,7 +542,9 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
     classes[1].cols = fast_cols;
     TileClass generic;
     generic.kind = 2;
-    std::vector<Tile> run_tiles, block_tiles;  // copy tiles of one contiguous row / of several pitched rows
+    // copy tiles of one contiguous row / of several pitched rows / pitched rows that also have a gathered form / that form
+    std::vector<Tile> run_tiles, block_tiles, regathered_tiles, gathered_tiles;
+    size_t group_left = 0;  // descriptors still to come of the gathered group being cut
     auto reg_class = [&](int ti, int tk) -> std::vector<Tile> & {
         for (size_t c = 1; c < classes.size(); ++c)
             if (classes[c].rows == ti && classes[c].cols == tk) return classes[c].tiles;
@@ -554,7 +556,28 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
         return classes.back().tiles;
     };
     auto fits32 = [](int64_t v) { return v >= 0 && v <= 0xFFFFFFFFll; };
-    for (const reshard_desc &d : descs) {
+    // Descriptors di .. di + k - 1 (k = 2^n, 1 <= k <= 256) whose rows of `units` 16-byte units interleave into ONE
+    // contiguous stretch of the destination: row r of the stretch is row r of source j0, j0 + 1, ... in turn (the
+    // shards of a row-parallel weight merged side by side; k == 1: rows packed from a pitched source).  Returns k,
+    // or 0 when the descriptors at di do not have that form.
+    auto gather_group = [&](size_t di, int64_t units) -> size_t {
+        const reshard_desc &d = descs[di];
+        const int64_t S = d.row_bytes;
+        if (units < 64 || S != units * 16 || d.dst_stride % S || d.src_stride < S) return 0;
+        const int64_t k = d.dst_stride / S;
+        if (k < 1 || k > 256 || (k & (k - 1)) || di + size_t(k) > descs.size()) return 0;
+        if (k == 1 && d.src_stride == S) return 0;
+        for (int64_t j = 1; j < k; ++j) {
+            const reshard_desc &e = descs[di + size_t(j)];
+            if (e.kind != 0 || e.rows != d.rows || e.row_bytes != S || e.src_stride != d.src_stride ||
+                e.dst_stride != d.dst_stride || e.dst_buf != d.dst_buf || e.src_buf != d.src_buf + j ||
+                e.src_off != d.src_off || e.dst_off != d.dst_off + j * S)
+                return 0;
+        }
+        return size_t(k);
+    };
+    for (size_t di = 0; di < descs.size(); ++di) {
+        const reshard_desc &d = descs[di];
         // a single row (a contiguous run of any length) has no pitch
         const bool pitched = d.rows > 1 || d.kind == 1;
         if (pitched && (!fits32(d.src_stride) || !fits32(d.dst_stride)))
@@ -565,6 +588,7 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
         t.src_stride = pitched ? uint32_t(d.src_stride) : 0;
         t.dst_stride = pitched ? uint32_t(d.dst_stride) : 0;
         if (d.kind == 1) {
+            if (group_left) return fail(RESHARD_ERR_UNSUPPORTED, "internal: a gathered group ends early");
             int lg = 0;
             while ((1 << lg) < d.elem_bytes) ++lg;
             const int E = d.elem_bytes;
@@ -649,6 +673,7 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
             // buffer (a short first piece brings the row there), so that in the woven order, where the XCD on
             // which a 1 KiB granule lands is its index in the tile modulo 8, an XCD always writes the same
             // 1 KiB residues of every 8 KiB of the buffer, whatever run the tile belongs to.
+            if (group_left) return fail(RESHARD_ERR_UNSUPPORTED, "internal: a gathered group ends early");
             const int64_t tile_span = max_units * vec;
             for (int64_t r = 0; r < d.rows; ++r) {
                 const int64_t row_dst = d.dst_off + r * d.dst_stride;
@@ -666,7 +691,36 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
                 }
             }
         } else {
-            // short rows: several whole rows per tile
+            // short rows.  Where the rows of this descriptor (and of the k - 1 that follow) fill one contiguous
+            // stretch of the destination, that stretch is ALSO cut like a run, into gathered tiles (same cuts on
+            // destination multiples of the tile size): the woven order takes those, the other orders the row blocks.
+            if (!group_left && vec == 16) {
+                const size_t k = gather_group(di, units);
+                if (k) {
+                    group_left = k;
+                    int lk = 0;
+                    while ((size_t(1) << lk) < k) ++lk;
+                    const int64_t total = d.rows * int64_t(k) * units, tile_span = max_units * 16;
+                    int64_t head = ((tile_span - d.dst_off % tile_span) % tile_span) / 16;
+                    if (head >= total) head = 0;
+                    Tile g = t;
+                    g.kind = 2;
+                    g.row_units = uint32_t(units);
+                    g.magic = uint32_t((uint64_t(1) << 32) / uint64_t(units)) + 1u;
+                    g.dst_stride = uint32_t(d.src_stride / 16);
+                    for (int64_t u = 0; u < total;) {
+                        const int64_t len = (u == 0 && head > 0) ? head : std::min(max_units, total - u);
+                        const int64_t seg = u / units, c0 = u % units, j0 = seg % int64_t(k), r0 = seg / int64_t(k);
+                        g.rows = uint32_t(len);
+                        g.src_stride = uint32_t(c0) | uint32_t(j0) << 16 | uint32_t(lk) << 24;
+                        g.src_off = uint64_t(d.src_off + r0 * d.src_stride);
+                        g.dst_off = uint64_t(d.dst_off + u * 16);
+                        gathered_tiles.push_back(g);
+                        u += len;
+                    }
+                }
+            }
+            // several whole rows per tile
             const int64_t rows_per_tile = std::max<int64_t>(1, max_units / units);
             for (int64_t r = 0; r < d.rows; r += rows_per_tile) {
                 t.rows = uint32_t(std::min(rows_per_tile, d.rows - r));
@@ -674,18 +728,24 @@ int cut_tiles(const std::vector<reshard_desc> &descs, int num_src_bufs, const Tu
                 t.magic = t.rows == 1 ? 0u : uint32_t((uint64_t(1) << 32) / uint64_t(units)) + 1u;
                 t.src_off = uint64_t(d.src_off + r * d.src_stride);
                 t.dst_off = uint64_t(d.dst_off + r * d.dst_stride);
-                (t.rows == 1 ? run_tiles : block_tiles).push_back(t);
+                (group_left ? regathered_tiles : t.rows == 1 ? run_tiles : block_tiles).push_back(t);
             }
+            if (group_left) --group_left;
         }
     }
     {
         TileClass &c = classes[0];
-        c.num_blocks = uint32_t(block_tiles.size());
+        c.num_regathered = uint32_t(regathered_tiles.size());
+        c.num_blocks = uint32_t(block_tiles.size()) + c.num_regathered;
+        c.num_runs = uint32_t(run_tiles.size());
+        c.num_gathered = uint32_t(gathered_tiles.size());
         c.tiles = std::move(block_tiles);
+        c.tiles.insert(c.tiles.end(), regathered_tiles.begin(), regathered_tiles.end());
         c.tiles.insert(c.tiles.end(), run_tiles.begin(), run_tiles.end());
+        c.tiles.insert(c.tiles.end(), gathered_tiles.begin(), gathered_tiles.end());
         for (size_t i = 0; i < c.tiles.size(); ++i) {
             const Tile &t = c.tiles[i];
-            c.max_units = std::max(c.max_units, t.rows * t.row_units);
+            c.max_units = std::max(c.max_units, t.kind == 2 ? t.rows : t.rows * t.row_units);
             if (i >= c.num_blocks) c.runs_wide = c.runs_wide && t.vec_log2 == 4;
         }
     }

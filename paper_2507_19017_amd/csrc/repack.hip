@@ -9,8 +9,10 @@
 //   - Contiguous runs (most of the bytes): the "woven" order.  The eight XCDs
 //     share every group of eight tiles, each taking the 1 KiB granules whose
 //     index is its own number modulo 8, so the chip walks one window of memory
-//     with every XCD on fixed 1 KiB residues of the address space.
-//   - Tiles of several pitched rows: one workgroup per tile (a persistent grid
+//     with every XCD on fixed 1 KiB residues of the address space.  Shards
+//     merged side by side into contiguous destination rows take the same order
+//     as "gathered" tiles: a run of the destination fed by k sources in turn.
+//   - Other tiles of several pitched rows: one workgroup per tile (a persistent grid
 //     is selectable; it measured slower), each XCD walking one contiguous eighth
 //     of the table; rows shorter than a tile are addressed through a flat unit
 //     index split by a multiply-high, so all 64 lanes of a wavefront stay busy
@@ -78,8 +80,30 @@ __device__ __forceinline__ void st(char *p, V v) {
 }
 #endif
 
+// A tile record as the copy kernels read it: the same 48 bytes as a Tile, as 32- and 64-bit words only, so
+// that every field arrives through scalar loads (the 8- and 16-bit fields of a Tile would come through vector
+// memory, and the wait for them is a wait for every data load in flight as well).
+struct TileRec {
+    uint64_t src_off, dst_off;
+    uint32_t src_stride, dst_stride, rows, row_units, magic, bufs, kinds, pad;
+    __device__ __forceinline__ uint32_t src_buf() const { return bufs & 0xFFFFu; }
+    __device__ __forceinline__ uint32_t dst_buf() const { return bufs >> 16; }
+    __device__ __forceinline__ uint32_t vec_log2() const { return (kinds >> 8) & 0xFFu; }
+};
+static_assert(sizeof(TileRec) == sizeof(Tile) && offsetof(Tile, magic) == 32 && offsetof(Tile, src_buf) == 36 &&
+                  offsetof(Tile, dst_buf) == 38 && offsetof(Tile, kind) == 40 && offsetof(Tile, vec_log2) == 41,
+              "TileRec mirrors Tile");
+__device__ __forceinline__ TileRec tile_record(const Tile *tiles, uint32_t i) {
+    return reinterpret_cast<const TileRec *>(tiles)[i];
+}
+
 // Copies one tile: n = rows*row_units vector units; unit u is column u % row_units
 // of row u / row_units.  magic == 0 marks a single contiguous row.
+// A round computes every address first, then issues its UNROLL loads back to back as straight-line code,
+// then stores.  A lane past the tile's end loads the tile's last unit again (and stores nothing): with
+// the loads inside `if (u < n)` blocks the compiler waited for each load before it issued the next
+// (it has to assume a skipped block left the registers of the round before in flight), so a lane never
+// had more than one load outstanding.
 template <typename V, int UNROLL, int NT>
 __device__ __forceinline__ void copy_tile(const char *__restrict__ s, char *__restrict__ d,
                                           uint32_t n, uint32_t row_units, uint32_t magic,
@@ -90,25 +114,24 @@ __device__ __forceinline__ void copy_tile(const char *__restrict__ s, char *__re
     for (uint32_t first = 0; first < n; first += step) {
         const uint32_t base = first + tid;
         V v[UNROLL];
+        const char *sp[UNROLL];
         uint64_t doff[UNROLL];
-        if (NT & 8) __builtin_amdgcn_s_setprio(3);  // waves that issue loads go first
 #pragma unroll
         for (int k = 0; k < UNROLL; ++k) {
-            const uint32_t u = base + k * nthreads;
-            if (u < n) {
-                const uint32_t row = __umulhi(u, magic);
-                const uint32_t col = u - row * row_units;
-                v[k] = ld<V, NT>(s + (uint64_t(row) * sstride + uint64_t(col) * sizeof(V)));
-                doff[k] = uint64_t(row) * dstride + uint64_t(col) * sizeof(V);
-            }
+            const uint32_t u = min(base + k * nthreads, n - 1);
+            const uint32_t row = __umulhi(u, magic);
+            const uint32_t col = u - row * row_units;
+            sp[k] = s + (uint64_t(row) * sstride + uint64_t(col) * sizeof(V));
+            doff[k] = uint64_t(row) * dstride + uint64_t(col) * sizeof(V);
         }
+        if (NT & 8) __builtin_amdgcn_s_setprio(3);  // waves that issue loads go first
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) v[k] = ld<V, NT>(sp[k]);
         if (NT & 8) __builtin_amdgcn_s_setprio(0);
         if (NT & 4) __syncthreads();
 #pragma unroll
-        for (int k = 0; k < UNROLL; ++k) {
-            const uint32_t u = base + k * nthreads;
-            if (u < n) st<V, NT>(d + doff[k], v[k]);
-        }
+        for (int k = 0; k < UNROLL; ++k)
+            if (base + k * nthreads < n) st<V, NT>(d + doff[k], v[k]);
     }
 }
 
@@ -125,12 +148,12 @@ __device__ __forceinline__ uint32_t tile_of_workgroup(uint32_t b, uint32_t ntile
 }
 
 template <int UNROLL, int NT>
-__device__ __forceinline__ void run_copy_tile(const Tile &t, const PtrTable &ptrs, uint32_t tid,
+__device__ __forceinline__ void run_copy_tile(const TileRec &t, const PtrTable &ptrs, uint32_t tid,
                                               uint32_t nthreads) {
-    const char *s = ptrs.p[t.src_buf] + t.src_off;
-    char *d = ptrs.p[t.dst_buf] + t.dst_off;
+    const char *s = ptrs.p[t.src_buf()] + t.src_off;
+    char *d = ptrs.p[t.dst_buf()] + t.dst_off;
     const uint32_t n = t.rows * t.row_units;
-    switch (t.vec_log2) {
+    switch (t.vec_log2()) {
         case 4: copy_tile<u32x4, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
         case 3: copy_tile<u32x2, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
         case 2: copy_tile<uint32_t, UNROLL, NT>(s, d, n, t.row_units, t.magic, t.src_stride, t.dst_stride, tid, nthreads); break;
@@ -152,7 +175,7 @@ __global__ __launch_bounds__(1024) void repack_copy_kernel(const Tile *__restric
                                                            uint32_t ntiles, PtrTable ptrs, int by_xcd) {
     const uint32_t ti = tile_of_workgroup(blockIdx.x, ntiles, by_xcd != 0);
     if (ti >= ntiles) return;
-    const Tile t = tiles[ti];  // uniform address: scalar loads
+    const TileRec t = tile_record(tiles, ti);  // uniform address: scalar loads
     run_copy_tile<UNROLL, NT>(t, ptrs, threadIdx.x, blockDim.x);
 }
 
@@ -172,7 +195,7 @@ __global__ __launch_bounds__(1024) void repack_copy_pool_kernel(const Tile *__re
     if (b < stat * 8) {
         const uint32_t ti = x * per + (b >> 3);
         if (ti >= ntiles) return;
-        const Tile t = tiles[ti];
+        const TileRec t = tile_record(tiles, ti);
         run_copy_tile<UNROLL, NT>(t, ptrs, threadIdx.x, blockDim.x);
         return;
     }
@@ -190,7 +213,7 @@ __global__ __launch_bounds__(1024) void repack_copy_pool_kernel(const Tile *__re
             if (c >= nchunks) break;
             const uint32_t first = lo + c * ct, last = min(first + ct, hi);
             for (uint32_t ti = first; ti < last; ++ti) {
-                const Tile t = tiles[ti];
+                const TileRec t = tile_record(tiles, ti);
                 run_copy_tile<UNROLL, NT>(t, ptrs, threadIdx.x, blockDim.x);
             }
         }
@@ -230,46 +253,77 @@ __device__ __forceinline__ void st_unit(char *p, u32x4 v, uint32_t lg) {
 // whole launch, so every wave runs the same number of rounds and reaches every barrier): 4 for
 // tiles of at most 2048 units.  Wave w handles slots w, w + 16, ...; slot s is granule
 // x + 8 * (s % slots) of tile 8g + s / slots.
-// WIDE: every tile of the launch moves 16-byte units, so the loads and stores are straight-line code
-// and both loads of a wave are in flight together; with units of mixed widths the width is a
-// branch per unit, after which the compiler waits for the first load before it issues the second
-// (measured 10 % slower), so that form only serves the rare plans that have narrow units.
-template <int NT, bool WIDE>
+// WIDE: every tile of the launch moves 16-byte units, so the two loads of a wave are two instructions
+// back to back; with units of mixed widths the width is a branch per unit, after which the compiler
+// waits for the first load before it issues the second (measured 10 % slower), so that form only
+// serves the rare plans that have narrow units.
+// GATHER: every tile of the launch is a gathered tile (Tile::kind 2; always 16-byte units); otherwise none is.
+// A gathered tile is written exactly like a run (same granules, same residues of the destination);
+// only where a unit comes from differs.
+template <int NT, bool WIDE, bool GATHER>
 __global__ __launch_bounds__(1024) void repack_copy_woven_kernel(const Tile *__restrict__ tiles, uint32_t ntiles, PtrTable ptrs,
                                                                  uint32_t slots) {
-    const uint32_t x = blockIdx.x & 7, first_tile = (blockIdx.x >> 3) * 8;
+    const uint32_t x = blockIdx.x & 7, first_tile = (blockIdx.x >> 3) * 8;  // first_tile < ntiles (the grid is ntiles rounded up to 8)
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const uint32_t nslots = slots * 8;
     for (uint32_t s0 = 0; s0 < nslots; s0 += 32) {  // 16 waves x 2 slots per round; the same trip count for every lane
-        u32x4 v[2];
+        // Both addresses first, for every lane, then both loads back to back as straight-line code (see copy_tile):
+        // a slot past the group's end takes the group's first tile, a lane past a tile's end the tile's last unit,
+        // and neither stores.
+        const char *sp[2];
         char *dp[2];
         uint32_t lg[2];
+        bool live[2];
+        TileRec rec[2];
+        uint32_t slot[2];
+        bool have[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {  // both records first: their scalar loads travel together
+            slot[k] = __builtin_amdgcn_readfirstlane(s0 + wave + 16 * k);
+            const uint32_t ti = first_tile + slot[k] / slots;
+            have[k] = slot[k] < nslots && ti < ntiles;  // the same for every lane of the wave
+            rec[k] = tile_record(tiles, have[k] ? ti : first_tile);
+        }
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
-            const uint32_t s = __builtin_amdgcn_readfirstlane(s0 + wave + 16 * k);
-            const uint32_t ti = first_tile + s / slots;
-            dp[k] = nullptr;
-            lg[k] = 0;
-            if (s < nslots && ti < ntiles) {  // the same for every lane of the wave
-                const Tile t = tiles[ti];
-                const uint32_t n = t.rows * t.row_units;
-                const uint32_t u = (x + 8 * (s % slots)) * 64 + lane;
-                if (u < n) {
-                    const uint32_t row = __umulhi(u, t.magic);
-                    const uint32_t col = u - row * t.row_units;
-                    lg[k] = t.vec_log2;
-                    const uint32_t shift = WIDE ? 4u : uint32_t(t.vec_log2);
-                    const char *sp = ptrs.p[t.src_buf] + t.src_off + (uint64_t(row) * t.src_stride + (uint64_t(col) << shift));
-                    if (WIDE) v[k] = ld<u32x4, NT>(sp);
-                    else v[k] = ld_unit<NT>(sp, t.vec_log2);
-                    dp[k] = ptrs.p[t.dst_buf] + t.dst_off + (uint64_t(row) * t.dst_stride + (uint64_t(col) << shift));
-                }
+            const TileRec &t = rec[k];
+            const uint32_t n = GATHER ? t.rows : t.rows * t.row_units;
+            const uint32_t u0 = (x + 8 * (slot[k] % slots)) * 64;
+            live[k] = have[k] && u0 + lane < n;
+            const uint32_t u = min(u0 + lane, n - 1);
+            const uint32_t shift = WIDE ? 4u : t.vec_log2();
+            lg[k] = t.vec_log2();
+            if (GATHER) {
+                // A granule of 64 units touches at most two segments (a segment has at least 64 units): the one
+                // its first unit lies in and the next.  Their source pointers and row offsets are the same for
+                // the whole wave (scalar loads and arithmetic); a lane only picks one of the two.
+                const uint32_t c0 = t.src_stride & 0xFFFFu, j0 = (t.src_stride >> 16) & 0xFFu, lk = t.src_stride >> 24;
+                const uint32_t g0 = min(u0, n - 1);                  // the granule's first unit (clamped like the lanes)
+                const uint32_t seg0 = __umulhi(c0 + g0, t.magic);   // segments from the tile's first to the granule's
+                const uint32_t ja = j0 + seg0, jb = ja + 1, km = (1u << lk) - 1u;
+                const uint64_t pitch = uint64_t(t.dst_stride) << 4;
+                const char *a = ptrs.p[t.src_buf() + (ja & km)] + t.src_off + uint64_t(ja >> lk) * pitch;
+                const char *b = ptrs.p[t.src_buf() + (jb & km)] + t.src_off + uint64_t(jb >> lk) * pitch;
+                const uint32_t w = c0 + u - seg0 * t.row_units;  // units from the start of the granule's first segment
+                sp[k] = w < t.row_units ? a + (uint64_t(w) << 4) : b + (uint64_t(w - t.row_units) << 4);
+                dp[k] = ptrs.p[t.dst_buf()] + t.dst_off + (uint64_t(u) << 4);
+            } else {
+                const uint32_t row = __umulhi(u, t.magic);
+                const uint32_t col = u - row * t.row_units;
+                sp[k] = ptrs.p[t.src_buf()] + t.src_off + (uint64_t(row) * t.src_stride + (uint64_t(col) << shift));
+                dp[k] = ptrs.p[t.dst_buf()] + t.dst_off + (uint64_t(row) * t.dst_stride + (uint64_t(col) << shift));
             }
+        }
+        u32x4 v[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (WIDE) v[k] = ld<u32x4, NT>(sp[k]);
+            else v[k] = ld_unit<NT>(sp[k], lg[k]);
         }
         if (NT & 4) __syncthreads();
 #pragma unroll
         for (int k = 0; k < 2; ++k)
-            if (dp[k]) {
+            if (live[k]) {
                 if (WIDE) st<u32x4, NT>(dp[k], v[k]);
                 else st_unit<NT>(dp[k], v[k], lg[k]);
             }
@@ -286,12 +340,12 @@ template <int UNROLL, int NT>
 __global__ __launch_bounds__(1024) void repack_copy_persistent_kernel(const Tile *__restrict__ tiles,
                                                                       uint32_t ntiles, PtrTable ptrs) {
     if (blockIdx.x >= ntiles) return;
-    Tile next = tiles[blockIdx.x];
+    TileRec next = tile_record(tiles, blockIdx.x);
     for (uint32_t ti = blockIdx.x; ti < ntiles; ti += gridDim.x) {
-        const Tile t = next;
+        const TileRec t = next;
         // fetch the following record while this tile's data is in flight
         const uint32_t tn = ti + gridDim.x;
-        next = tiles[tn < ntiles ? tn : ti];
+        next = tile_record(tiles, tn < ntiles ? tn : ti);
         run_copy_tile<UNROLL, NT>(t, ptrs, threadIdx.x, blockDim.x);
     }
 }
@@ -580,27 +634,48 @@ int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
     return RESHARD_OK;
 }
 
+// Parts of a copy class's table (or of one source's slice of it) as they lie behind one another in
+// device memory: row blocks, of which the last `regathered` also exist as gathered tiles, runs, gathered tiles.
+struct CopyParts {
+    uint32_t blocks = 0, regathered = 0, runs = 0, gathered = 0;
+};
+
 // Launches `n` tiles of class `tc` (copy, register transpose of one shape, generic transpose)
-// starting at device address `t`.
+// starting at device address `t`.  Copy tiles in the woven order (see launch_copy_class) must all be
+// contiguous in the destination.
 int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc, const Tile *t, uint32_t n,
-                 const PtrTable &pt, hipStream_t stream, uint32_t n_blocks, uint32_t *pool_counters = nullptr) {
+                 const PtrTable &pt, hipStream_t stream, uint32_t *pool_counters = nullptr, bool gathered = false);
+
+// The copy class: which kernel takes which part.
+int launch_copy_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc, const Tile *t, const CopyParts &parts,
+                      const PtrTable &pt, hipStream_t stream, uint32_t *pool_counters = nullptr) {
+    const bool woven = (tn.flags & 32) && tn.block_threads == 1024 && tn.blocks_per_cu == 0;
+    if (!woven)  // one launch over row blocks and runs
+        return launch_class(plan, tn, tc, t, parts.blocks + parts.runs, pt, stream, pool_counters);
+    // the woven order serves what is contiguous in the destination (runs, and the gathered form of the row blocks
+    // that have one); the other row blocks go out first, in the XCD-contiguous order
+    Tuning blocks = tn;
+    blocks.flags &= ~32;
+    blocks.tail_pool_percent = 0;
+    const bool gather = (tn.flags & 64) != 0;
+    const uint32_t pure = gather ? parts.blocks - parts.regathered : parts.blocks;
+    if (int rc = launch_class(plan, blocks, tc, t, pure, pt, stream)) return rc;
+    if (int rc = launch_class(plan, tn, tc, t + parts.blocks, parts.runs, pt, stream)) return rc;
+    if (!gather) return RESHARD_OK;
+    return launch_class(plan, tn, tc, t + parts.blocks + parts.runs, parts.gathered, pt, stream, nullptr, true);
+}
+
+int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc, const Tile *t, uint32_t n,
+                 const PtrTable &pt, hipStream_t stream, uint32_t *pool_counters, bool gathered) {
     if (!n) return RESHARD_OK;
     const int cls = tc.kind;
-    if (cls == 0 && (tn.flags & 32) && tn.block_threads == 1024 && n_blocks > 0 && n_blocks < n) {
-        // woven order for the contiguous runs only: tiles of several pitched rows go out first, in the XCD-contiguous order
-        Tuning blocks = tn;
-        blocks.flags &= ~32;
-        blocks.tail_pool_percent = 0;
-        if (int rc = launch_class(plan, blocks, tc, t, n_blocks, pt, stream, n_blocks)) return rc;
-        return launch_class(plan, tn, tc, t + n_blocks, n - n_blocks, pt, stream, 0);
-    }
     // blocks_per_cu == 0: one tile per workgroup; otherwise a persistent grid
     const uint32_t wanted = tn.blocks_per_cu ? uint32_t(plan->num_cus) * uint32_t(tn.blocks_per_cu) : 0xFFFFFFFFu;
     const int by_xcd = (tn.flags & 8) ? 1 : 0;
     if (cls == 0 && tn.blocks_per_cu) {
         launch_copy(tn, dim3(std::min(n, wanted)), dim3(tn.block_threads), stream, t, n, pt);
         if (hipError_t e = hipGetLastError()) return hip_fail(e, "launch of the copy kernel");
-    } else if (cls == 0 && (tn.flags & 32) && tn.block_threads == 1024 && n_blocks == 0) {
+    } else if (cls == 0 && (tn.flags & 32) && tn.block_threads == 1024) {
         // the woven order: 8 workgroups (one per XCD) per group of 8 tiles
         const uint32_t slots = std::max<uint32_t>(1, (tc.max_units + 511) / 512);
         const uint32_t per_launch = (0xFFFFFFFFu / 1024u) & ~7u;  // tiles per launch: a multiple of 8, within the lanes of one launch
@@ -612,9 +687,10 @@ int launch_class(const reshard_plan *plan, const Tuning &tn, const TileClass &tc
             // (C2, C3P), while the one-tile kernel next to it gains from it (C1: 3 %).
             const int h = tn.flags & 7;
             const int hints = h == 7 ? 7 : h == 3 ? 3 : (h & 4) ? 4 : 0;
-#define RESHARD_WOVEN(NT)                                                                                                            \
-    if (tc.runs_wide) hipLaunchKernelGGL((repack_copy_woven_kernel<NT, true>), grid, block, 0, stream, t + first, m, pt, slots);    \
-    else hipLaunchKernelGGL((repack_copy_woven_kernel<NT, false>), grid, block, 0, stream, t + first, m, pt, slots);               \
+#define RESHARD_WOVEN(NT)                                                                                                                   \
+    if (gathered) hipLaunchKernelGGL((repack_copy_woven_kernel<NT, true, true>), grid, block, 0, stream, t + first, m, pt, slots);          \
+    else if (tc.runs_wide) hipLaunchKernelGGL((repack_copy_woven_kernel<NT, true, false>), grid, block, 0, stream, t + first, m, pt, slots); \
+    else hipLaunchKernelGGL((repack_copy_woven_kernel<NT, false, false>), grid, block, 0, stream, t + first, m, pt, slots);                 \
     break;
             switch (hints) {
                 case 7: RESHARD_WOVEN(7)
@@ -721,7 +797,9 @@ int launch_repack(reshard_plan *plan, hipStream_t stream) {
     uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<char *>(plan->d_tiles) + size_t(plan->info.num_tiles) * sizeof(Tile));
     for (const TileClass &c : plan->classes) {
         const uint32_t n = uint32_t(c.tiles.size());
-        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream, c.num_blocks, counters)) return rc;
+        if (c.kind == 0) {
+            if (int rc = launch_copy_class(plan, tn, c, tiles, CopyParts{c.num_blocks, c.num_regathered, c.num_runs, c.num_gathered}, pt, stream, counters)) return rc;
+        } else if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream)) return rc;
         tiles += n;
     }
     return RESHARD_OK;
@@ -777,7 +855,9 @@ int launch_repack_static(reshard_plan *plan, hipStream_t stream) {
     const Tile *tiles = reinterpret_cast<const Tile *>(base);
     for (const TileClass &c : plan->classes) {
         const uint32_t n = uint32_t(c.tiles.size());
-        if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream, c.num_blocks)) return rc;
+        if (c.kind == 0) {
+            if (int rc = launch_copy_class(plan, tn, c, tiles, CopyParts{c.num_blocks, c.num_regathered, c.num_runs, c.num_gathered}, pt, stream)) return rc;
+        } else if (int rc = launch_class(plan, tn, c, tiles, n, pt, stream)) return rc;
         tiles += n;
     }
     return RESHARD_OK;
@@ -794,8 +874,13 @@ int ensure_by_source_table(reshard_plan *plan) {
     empty.first.assign(nc, 0);
     empty.count.assign(nc, 0);
     plan->src_slices.assign(ns, empty);
+    // of the copy class only row blocks and runs: a gathered tile reads several sources
+    auto sliced = [&](size_t cls) {
+        const TileClass &c = plan->classes[cls];
+        return c.kind == 0 ? size_t(c.num_blocks) + c.num_runs : c.tiles.size();
+    };
     for (size_t cls = 0; cls < nc; ++cls)
-        for (const Tile &t : plan->classes[cls].tiles) ++plan->src_slices[t.src_buf].count[cls];
+        for (size_t i = 0; i < sliced(cls); ++i) ++plan->src_slices[plan->classes[cls].tiles[i].src_buf].count[cls];
     for (uint32_t i = 0; i < plan->classes[0].num_blocks; ++i)  // table order is kept inside a slice: its row blocks lead as well
         ++plan->src_slices[plan->classes[0].tiles[i].src_buf].copy_blocks;
     uint32_t at = 0;
@@ -807,8 +892,10 @@ int ensure_by_source_table(reshard_plan *plan) {
     plan->by_src_tiles.resize(at);
     std::vector<uint32_t> fill(ns * nc, 0);
     for (size_t cls = 0; cls < nc; ++cls)
-        for (const Tile &t : plan->classes[cls].tiles)  // table order is kept inside every group
+        for (size_t i = 0; i < sliced(cls); ++i) {  // table order is kept inside every group
+            const Tile &t = plan->classes[cls].tiles[i];
             plan->by_src_tiles[plan->src_slices[t.src_buf].first[cls] + fill[size_t(t.src_buf) * nc + cls]++] = t;
+        }
     return upload({&plan->by_src_tiles}, &plan->d_by_src);
 }
 
@@ -818,8 +905,12 @@ int launch_source(reshard_plan *plan, int src_index, hipStream_t stream) {
     fill_ptrs(plan, pt);
     const Tile *base = static_cast<const Tile *>(plan->d_by_src);
     const reshard_plan::SrcSlice &sl = plan->src_slices[size_t(plan->src_slot[size_t(src_index)])];
-    for (size_t cls = 0; cls < plan->classes.size(); ++cls)
-        if (int rc = launch_class(plan, tn, plan->classes[cls], base + sl.first[cls], sl.count[cls], pt, stream, cls == 0 ? sl.copy_blocks : 0)) return rc;
+    for (size_t cls = 0; cls < plan->classes.size(); ++cls) {
+        const TileClass &c = plan->classes[cls];
+        if (c.kind == 0) {
+            if (int rc = launch_copy_class(plan, tn, c, base + sl.first[cls], CopyParts{sl.copy_blocks, 0, sl.count[cls] - sl.copy_blocks, 0}, pt, stream)) return rc;
+        } else if (int rc = launch_class(plan, tn, c, base + sl.first[cls], sl.count[cls], pt, stream)) return rc;
+    }
     return RESHARD_OK;
 }
 

@@ -203,6 +203,21 @@ TINY = {
         2003, "tiny MLA MoE TP2 EP8 -> TP1, rank 1 of EP2"),
 }
 
+# Mid-size dense shapes whose row-parallel weights (attention output, feed-forward down projection)
+# have shard rows of at least 1 KiB (64 and 88 vectors of 16 bytes at 2-byte elements): the row
+# lengths from which the library may cut a side-by-side merge as one contiguous stream.
+_MID_SPEC = make_spec(family="dense_gqa", L=1, H=256, nq=8, nkv=4, d=256, I=2816, V=256)
+MID = {
+    "mid_merge2": _wl("mid_merge2", _MID_SPEC, make_layout(kind="train", tp=4), make_layout(kind="gen", tp=2),
+                      2020, "mid-size dense, TP4 -> TP2: two shards side by side per destination row"),
+    "mid_merge4": _wl("mid_merge4", _MID_SPEC, make_layout(kind="train", tp=4, pp=1), make_layout(kind="gen", tp=1),
+                      2021, "mid-size dense, TP4 -> TP1: four shards side by side"),
+    "mid_merge8": _wl("mid_merge8", dict(_MID_SPEC, elem_bytes=4), make_layout(kind="train", tp=8), make_layout(kind="gen", tp=1),
+                      2022, "mid-size dense, 4-byte elements, TP8 -> TP1: eight shards side by side"),
+    "mid_split": _wl("mid_split", _MID_SPEC, make_layout(kind="train", tp=1), make_layout(kind="gen", tp=2),
+                     2023, "mid-size dense, TP1 -> TP2: destination rows packed out of wider source rows"),
+}
+
 
 def random_case(seed: int, scale: int = 1) -> dict:
     """A small random workload that the shape rules allow (divisibility only: no layout

@@ -20,6 +20,15 @@ static void run_tile(const reshard_plan *p, const Tile &t) {
     const char *s = static_cast<const char *>(p->src_ptrs[size_t(p->slot_buf[t.src_buf])]) + t.src_off;
     char *d = static_cast<char *>(p->dst_ptrs[size_t(p->slot_buf[t.dst_buf])]) + t.dst_off;
     const size_t v = size_t(1) << t.vec_log2;
+    if (t.kind == 2) {  // gathered: consecutive units of the destination, from 2^lk sources in turn
+        const uint32_t c0 = t.src_stride & 0xFFFFu, j0 = (t.src_stride >> 16) & 0xFFu, lk = t.src_stride >> 24;
+        for (uint32_t u = 0; u < t.rows; ++u) {
+            const uint64_t w = uint64_t(j0) * t.row_units + c0 + u, seg = w / t.row_units, c = w % t.row_units;
+            const char *sj = static_cast<const char *>(p->src_ptrs[size_t(p->slot_buf[t.src_buf + (seg & ((1u << lk) - 1))])]) + t.src_off;
+            std::memcpy(d + size_t(u) * 16, sj + (seg >> lk) * t.dst_stride * 16 + c * 16, 16);
+        }
+        return;
+    }
     for (uint32_t i = 0; i < t.rows; ++i)
         for (uint32_t k = 0; k < t.row_units; ++k)
             if (t.kind == 0) std::memcpy(d + size_t(i) * t.dst_stride + k * v, s + size_t(i) * t.src_stride + k * v, v);
@@ -34,15 +43,21 @@ int ensure_by_source_table(reshard_plan *p) {
     return RESHARD_OK;
 }
 int launch_repack(reshard_plan *p, hipStream_t) {
+    const bool woven = (p->tuning.flags & 96) == 96 && p->tuning.block_threads == 1024 && p->tuning.blocks_per_cu == 0;
     for (const TileClass &c : p->classes)
-        for (const Tile &t : c.tiles) run_tile(p, t);
+        for (size_t i = 0; i < c.tiles.size(); ++i) {
+            // the copy class holds some bytes twice: as row blocks and as gathered tiles
+            if (c.kind == 0 && woven && i >= c.num_blocks - c.num_regathered && i < c.num_blocks) continue;
+            if (c.kind == 0 && !woven && i >= size_t(c.num_blocks) + c.num_runs) continue;
+            run_tile(p, c.tiles[i]);
+        }
     return RESHARD_OK;
 }
 int launch_repack_static(reshard_plan *p, hipStream_t s) { return launch_repack(p, s); }
 int launch_source(reshard_plan *p, int src_index, hipStream_t) {
     for (const TileClass &c : p->classes)
         for (const Tile &t : c.tiles)
-            if (p->slot_buf[t.src_buf] == src_index && t.src_buf < p->num_src_slots) run_tile(p, t);
+            if (t.kind != 2 && p->slot_buf[t.src_buf] == src_index && t.src_buf < p->num_src_slots) run_tile(p, t);
     return RESHARD_OK;
 }
 }  // namespace reshard

@@ -147,8 +147,8 @@ int main(int argc, char **argv) {
     moe.family = RESHARD_MOE_GQA; moe.L = 1; moe.H = 336; moe.nq = 4; moe.nkv = 2; moe.d = 16; moe.V = 32; moe.has_embeddings = 1;
     moe.E = 2; moe.Ie = 208; moe.n_shared = 0;
     reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{}, pooled{}, woven{}, woven_small{};
-    woven.flags = 63;                                   // the XCDs share every group of 8 tiles
-    woven_small.flags = 36; woven_small.tile_bytes = 4096;  // plain accesses with the barrier, tiles of 256 units
+    woven.flags = 127;                                  // the XCDs share every group of 8 tiles
+    woven_small.flags = 100; woven_small.tile_bytes = 4096;  // plain accesses with the barrier, tiles of 256 units
     pooled.tile_bytes = 4096; pooled.flags = 31; pooled.tail_pool_percent = 30; pooled.tail_chunk_tiles = 1;  // 1024-lane workgroups, a shared tail
     wide192.transpose_rows = 192; wide192.transpose_cols = 192;
     small.tile_bytes = 4096; small.block_threads = 64; small.unroll = 1; small.transpose_rows = 64; small.transpose_cols = 64;
@@ -178,6 +178,37 @@ int main(int argc, char **argv) {
         for (int twice = 0; twice < 2; ++twice)  // once through the plan's own table (pooled), once through the static array (not)
             bad += run(wide, lay(RESHARD_TRAIN, 2, 1, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), &pooled, false);
         if (host_simt::launches - before != 3) { std::printf("the tail pool was not used (%ld launches)\n", host_simt::launches - before); bad += 1; }
+    }
+    if (!bad) {
+        // shards of row-parallel weights with rows of 64 and 88 vectors: the side-by-side merge (and the packing of
+        // narrower rows out of a pitched source) also exists as gathered tiles, which the woven order launches
+        reshard_model_spec g = dense;
+        g.L = 1; g.H = 64; g.nq = 8; g.nkv = 2; g.d = 128; g.I = 1408; g.V = 64; g.qkv_bias = 0;
+        reshard_tuning blocks{};
+        blocks.flags = 31;  // the same plans through the row blocks
+        for (const reshard_tuning *tn : {static_cast<const reshard_tuning *>(nullptr), static_cast<const reshard_tuning *>(&woven_small),
+                                         static_cast<const reshard_tuning *>(&blocks)}) {
+            g.elem_bytes = 2;
+            bad += run(g, lay(RESHARD_TRAIN, 2, 1, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), tn, false);  // two sources per row
+            bad += run(g, lay(RESHARD_TRAIN, 1, 1, 1, 0), lay(RESHARD_GEN, 2, 1, 1, 0), tn, false);  // one pitched source
+            g.elem_bytes = 4;
+            bad += run(g, lay(RESHARD_TRAIN, 4, 1, 1, 0), lay(RESHARD_GEN, 1, 1, 1, 0), tn, tn == nullptr);  // four
+        }
+        {   // the plans above do hold gathered tiles
+            reshard_plan *plan = nullptr;
+            const reshard_layout a = lay(RESHARD_TRAIN, 4, 1, 1, 0), b = lay(RESHARD_GEN, 1, 1, 1, 0);
+            reshard_plan_info info{};
+            int64_t gathered = 0;
+            if (reshard_plan_create(&g, &a, &b, &plan) != RESHARD_OK || reshard_plan_get_info(plan, &info) != RESHARD_OK) bad += 1;
+            for (int64_t q = 0; !bad && q < info.num_tiles; ++q) {
+                reshard_tile t;
+                if (reshard_plan_tile(plan, q, &t) != RESHARD_OK) { bad += 1; break; }
+                gathered += t.kind == 2 && t.sources == 4 && t.order == 2;
+            }
+            if (!gathered) { std::printf("no gathered tiles in the plan meant to have them\n"); bad += 1; }
+            reshard_plan_destroy(plan);
+        }
+        std::printf("gathered tiles done: %ld launches so far\n", host_simt::launches);
     }
     std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
     return bad ? 1 : 0;

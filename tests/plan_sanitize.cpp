@@ -47,13 +47,32 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
     }
     if (rc) return 0;
     // bytes of the tiles equal bytes of the descriptors; every access stays inside its buffer
-    long long dbytes = 0, tbytes = 0;
+    long long dbytes = 0, tbytes = 0, again_blocks = 0, again_gathered = 0;
     for (const reshard_desc &d : descs) dbytes += d.rows * d.row_bytes;
-    auto check = [&](const std::vector<Tile> &v) {
-        for (const Tile &t : v) {
+    auto check = [&](const TileClass &c) {
+        const std::vector<Tile> &v = c.tiles;
+        for (size_t i = 0; i < v.size(); ++i) {
+            const Tile &t = v[i];
             const long long unit = 1ll << t.vec_log2;
-            tbytes += (long long)t.rows * t.row_units * unit;
             const long long sb = S.buf_bytes[t.src_buf], db = D.buf_bytes[t.dst_buf - S.buf_bytes.size()];
+            if (t.kind == 2) {
+                // gathered tiles (behind the row blocks and runs of the copy class): the same bytes as the row
+                // blocks they stand for, every unit inside the buffer of the source it comes from
+                const uint32_t c0 = t.src_stride & 0xFFFFu, j0 = (t.src_stride >> 16) & 0xFFu, lk = t.src_stride >> 24;
+                const bool placed = c.kind == 0 && i >= size_t(c.num_blocks) + c.num_runs && unit == 16 && t.row_units >= 64 &&
+                                    c0 < t.row_units && j0 < (1u << lk) && t.src_buf + (1u << lk) <= S.buf_bytes.size();
+                if (!placed) { std::printf("a gathered tile of a wrong form or place\n"); std::exit(1); }
+                again_gathered += (long long)t.rows * 16;
+                for (uint32_t u = 0; u < t.rows; ++u) {
+                    const unsigned long long w = (unsigned long long)j0 * t.row_units + c0 + u, seg = w / t.row_units;
+                    const long long at = (long long)t.src_off + (long long)(seg >> lk) * t.dst_stride * 16 + (long long)(w % t.row_units) * 16;
+                    if (at + 16 > S.buf_bytes[t.src_buf + (seg & ((1u << lk) - 1))]) { std::printf("tile leaves its buffer\n"); std::exit(1); }
+                }
+                if ((long long)t.dst_off + (long long)t.rows * 16 > db) { std::printf("tile leaves its buffer\n"); std::exit(1); }
+                continue;
+            }
+            tbytes += (long long)t.rows * t.row_units * unit;
+            if (c.kind == 0 && i >= size_t(c.num_blocks - c.num_regathered) && i < c.num_blocks) again_blocks += (long long)t.rows * t.row_units * unit;
             long long s_end, d_end;
             if (t.kind == 0) {
                 s_end = (long long)t.src_off + (long long)(t.rows - 1) * t.src_stride + t.row_units * unit;
@@ -66,7 +85,7 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
         }
     };
     for (const TileClass &c : classes) {
-        check(c.tiles);
+        check(c);
         // register-path tiles are whole tiles of their class's shape, in a shape the kernel is built for
         if (c.kind == 1)
             for (const Tile &t : c.tiles)
@@ -75,6 +94,7 @@ static int run(const reshard_model_spec &s, const reshard_layout &a, const resha
                     return 1;
                 }
     }
+    if (again_blocks != again_gathered) { std::printf("gathered bytes %lld != bytes of the row blocks they stand for %lld\n", again_gathered, again_blocks); return 1; }
     if (dbytes != tbytes) { std::printf("tile bytes %lld != descriptor bytes %lld\n", tbytes, dbytes); return 1; }
     return 0;
 }

@@ -8,7 +8,7 @@ import torch
 import gpu_util as G
 from oracle import fast, locate
 from paper_2507_19017_amd import Plan, ReshardError, binding, copy_baseline, read_baseline, set_tuning, write_baseline
-from synth_inputs import TINY, WORKLOADS, fill_buffer, make_layout, make_spec, random_case
+from synth_inputs import MID, TINY, WORKLOADS, fill_buffer, make_layout, make_spec, random_case
 
 pytestmark = pytest.mark.gpu
 
@@ -120,6 +120,7 @@ TUNINGS = [
     dict(tile_bytes=8192, flags=31, tail_pool_percent=50, tail_chunk_tiles=1),
     dict(flags=31, tail_pool_percent=10),
     dict(flags=63),                                         # the woven order (XCDs share every group of 8 tiles)
+    dict(flags=127, tile_bytes=16384),                      # with gathered tiles where the plan has them
     dict(flags=36, tile_bytes=4096),
     dict(flags=35, tile_bytes=131072),
     dict(flags=39, tile_bytes=8192),
@@ -132,6 +133,50 @@ def test_every_launch_shape_gives_the_same_bits(tuning):
     for name in ("tiny_dense", "tiny_moe_grouped"):
         run_case(TINY[name], "raw16", tuning=tuning)
     run_case(WORKLOADS["C0"], "raw16", tuning=tuning)
+
+
+GATHER_TUNINGS = [None, dict(flags=127, tile_bytes=4096), dict(flags=100, tile_bytes=8192), dict(flags=99, tile_bytes=131072),
+                  dict(flags=103, tile_bytes=524288), dict(flags=63), dict(flags=31), dict(flags=95), dict(flags=127, block_threads=512),
+                  dict(flags=127, blocks_per_cu=2)]
+
+
+@pytest.mark.parametrize("name", sorted(MID))
+def test_side_by_side_merges_as_gathered_tiles(name):
+    """Row-parallel shards with rows of 64 and 88 vectors, merged 2, 4 and 8 abreast or packed out
+    of a wider source: in the woven order these bytes go out as gathered tiles (one contiguous
+    stream of the destination fed by the sources in turn), in every other launch shape as row
+    blocks.  Every shape gives the oracle's bits, so does the one-source-at-a-time path (row
+    blocks only) and the entry point that reads the table from the static array; and the counting
+    build shows every byte written exactly once in the woven order."""
+    wl = MID[name]
+    for tuning in GATHER_TUNINGS:
+        print("case", name, tuning, flush=True)
+        plan, src, dst = run_case(wl, "raw16", tuning=tuning)
+        if tuning is None:
+            assert plan.get_tuning()["flags"] == 127
+            tiles = plan.tiles()
+            assert any(t["kind"] == 2 for t in tiles) and any(t["order"] == 1 for t in tiles)
+            again = G.device_destinations(plan)
+            plan.execute_noalloc(G.ptrs(src), G.ptrs(again), G.stream_handle())
+            torch.cuda.synchronize()
+            for a, b in zip(dst, again):
+                assert (a is None and b is None) or torch.equal(a, b)
+            by_source = G.device_destinations(plan)
+            for i, buf in enumerate(src):
+                if buf is not None:
+                    plan.execute_source(i, buf.data_ptr(), G.ptrs(by_source), G.stream_handle())
+            torch.cuda.synchronize()
+            for a, b in zip(dst, by_source):
+                assert (a is None and b is None) or torch.equal(a, b)
+    for tuning in (None, dict(flags=127, tile_bytes=4096)):
+        counts, D = _count_writes_on_device(wl, tuning)
+        for b, c in enumerate(counts):
+            if c is None:
+                continue
+            want = np.zeros(D.buf_bytes[b], dtype=np.uint8)
+            for off, nb in D.owned(b):
+                want[off:off + nb] = 1
+            assert np.array_equal(c, want), f"{name} buffer {b}: {int((c != want).sum())} bytes not written exactly once"
 
 
 def test_two_plans_with_different_tunings_interleave():

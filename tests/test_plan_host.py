@@ -17,7 +17,7 @@ import pytest
 import np_pack
 from oracle import fast, locate
 from paper_2507_19017_amd import Plan, ReshardError, binding, get_tuning, set_tuning
-from synth_inputs import TINY, WORKLOADS, make_layout, make_spec
+from synth_inputs import MID, TINY, WORKLOADS, make_layout, make_spec
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SENT = 0xA5
@@ -50,11 +50,28 @@ def run_descs(descs, src, dst, counts=None):
                 np.add.at(counts[d["dst_buf"]], b, 1)
 
 
-def run_tiles(tiles, src, dst, counts):
-    """Interpret the device tile table on byte arrays, as reshard.h words it."""
+def run_tiles(tiles, src, dst, counts, woven=True):
+    """Interpret the device tile table on byte arrays, as reshard.h words it: the tiles every
+    execute launches plus those of the one order (woven or not)."""
     for t in tiles:
+        if t["order"] == (1 if woven else 2):
+            continue
         s, d = src[t["src_buf"]], dst[t["dst_buf"]]
         v = t["vec_bytes"]
+        if t["kind"] == 2:
+            w = t["phase"] + np.arange(t["rows"])
+            seg, c = w // t["row_units"], w % t["row_units"]
+            j, r = seg % t["sources"], seg // t["sources"]
+            a0 = t["src_off"] + r * t["src_stride"] + c * v
+            e = np.arange(v)
+            b = (t["dst_off"] + np.arange(t["rows"])[:, None] * v + e).ravel()
+            vals = np.empty((t["rows"], v), dtype=np.uint8)
+            for jj in np.unique(j):
+                m = j == jj
+                vals[m] = src[t["src_buf"] + int(jj)][(a0[m][:, None] + e)]
+            d[b] = vals.ravel()
+            np.add.at(counts[t["dst_buf"]], b, 1)
+            continue
         if t["kind"] == 0:
             i, u, e = np.meshgrid(np.arange(t["rows"]), np.arange(t["row_units"]), np.arange(v), indexing="ij")
             a = (t["src_off"] + i * t["src_stride"] + u * v + e).ravel()
@@ -77,6 +94,9 @@ TILE_CASES += [("big_moe_grouped", eb, t) for eb, t in [
     (2, dict()), (4, dict()), (4, dict(transpose_rows=256, transpose_cols=64)), (8, dict()),
     (8, dict(transpose_rows=64, transpose_cols=256))]]
 TILE_CASES += [("mid_moe_grouped", eb, dict()) for eb in (1, 4, 8)]
+# side-by-side merges that also exist as gathered tiles, at several tile sizes (rows of 64 and 88 vectors)
+TILE_CASES += [(n, MID[n]["spec"]["elem_bytes"], t) for n in sorted(MID)
+               for t in (dict(), dict(tile_bytes=4096), dict(tile_bytes=8192), dict(tile_bytes=131072))]
 
 
 def transpose_shape(eb, tuning):
@@ -94,7 +114,7 @@ def transpose_shape(eb, tuning):
 def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, eb, tuning):
     """The cut into device tiles (rows per tile, runs of long rows, vector width, the three
     levels of transposing tiles) moves exactly what the descriptors say."""
-    w = {**TINY, **WORKLOADS}[name]
+    w = {**TINY, **MID, **WORKLOADS}[name]
     spec = with_eb(w["spec"], eb)
     try:
         set_tuning(**tuning)
@@ -108,20 +128,30 @@ def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, eb, t
     cnt = [np.zeros(n, dtype=np.int32) for n in D.buf_bytes]
     tiles = plan.tiles()
     assert len(tiles) == plan.info()["num_tiles"]
-    run_tiles(tiles, src, dst, cnt)
     want = [np.full(n, SENT, dtype=np.uint8) for n in D.buf_bytes]
     fast.reshard(spec, w["src"], w["dst"], [x.view(np.uint16) for x in src], [x.view(np.uint16) for x in want])
-    for b in range(D.nbufs):
-        assert np.array_equal(dst[b], want[b]), f"buffer {b}"
-        owned = np.zeros(D.buf_bytes[b], dtype=bool)
-        for off, nb in D.owned(b):
-            owned[off:off + nb] = True
-        assert np.all(cnt[b][owned] == 1) and np.all(cnt[b][~owned] == 0)
+    for woven in (True, False):  # the table holds some bytes cut two ways; either order is the whole work
+        for b in range(D.nbufs):
+            dst[b][:] = SENT
+            cnt[b][:] = 0
+        run_tiles(tiles, src, dst, cnt, woven)
+        for b in range(D.nbufs):
+            assert np.array_equal(dst[b], want[b]), f"buffer {b}"
+            owned = np.zeros(D.buf_bytes[b], dtype=bool)
+            for off, nb in D.owned(b):
+                owned[off:off + nb] = True
+            assert np.all(cnt[b][owned] == 1) and np.all(cnt[b][~owned] == 0)
+    assert sum(t["order"] == 1 for t in tiles) > 0 or all(t["order"] == 0 for t in tiles)
     shape = transpose_shape(eb, tuning)
     for t in tiles:
         units = t["rows"] * t["row_units"]
         assert units >= 1 and t["vec_bytes"] in (1, 2, 4, 8, 16)
-        if t["kind"] == 0:
+        if t["kind"] == 2:
+            assert t["tile_class"] == 0 and t["order"] == 2 and t["vec_bytes"] == 16 and 1 <= t["rows"] <= 32768
+            assert 64 <= t["row_units"] and t["sources"] in (1, 2, 4, 8, 16, 32, 64, 128, 256)
+            assert 0 <= t["phase"] < t["sources"] * t["row_units"]
+            assert (t["src_off"] | t["dst_off"] | t["src_stride"]) % 16 == 0 and t["src_stride"] >= 16 * t["row_units"]
+        elif t["kind"] == 0:
             assert t["tile_class"] == 0 and units <= 32768
             assert (t["src_off"] | t["dst_off"]) % t["vec_bytes"] == 0
             if t["rows"] > 1:
@@ -137,6 +167,11 @@ def test_tile_table_reproduces_the_oracle_and_writes_every_byte_once(name, eb, t
             else:
                 assert t["rows"] <= 64 and t["row_units"] <= 64
     classes = {t["tile_class"] for t in tiles}
+    if name in MID:  # the gathered form exists exactly where a tile holds more than one segment of a row
+        gathered = sum(t["rows"] * 16 for t in tiles if t["kind"] == 2)
+        assert gathered == sum(t["rows"] * t["row_units"] * 16 for t in tiles if t["order"] == 1)
+        assert gathered > 0
+        assert {t["sources"] for t in tiles if t["kind"] == 2} <= {{"mid_merge2": 2, "mid_merge4": 4, "mid_merge8": 8, "mid_split": 1}[name]}
     if name == "mid_moe_grouped" and eb == 2:  # 320 x 200 and 200 x 320 matrices: register path and ragged rest
         assert 0 in classes and 3 in classes and classes & {1, 2}
     if name == "big_moe_grouped":  # the preferred shape, smaller shapes on the strips, a ragged rest
@@ -439,7 +474,7 @@ def test_state_machine_errors_without_a_device():
 def test_tuning_is_validated():
     set_tuning()
     base = get_tuning()
-    assert base == dict(tile_bytes=32768, block_threads=1024, blocks_per_cu=0, unroll=2, flags=63, transpose_rows=0,
+    assert base == dict(tile_bytes=32768, block_threads=1024, blocks_per_cu=0, unroll=2, flags=127, transpose_rows=0,
                         transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16)
     set_tuning(tile_bytes=8192, unroll=4)
     assert get_tuning()["tile_bytes"] == 8192 and get_tuning()["unroll"] == 4
@@ -449,7 +484,7 @@ def test_tuning_is_validated():
     n32 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
     assert n8 > 3.5 * n32
     for bad in (dict(tile_bytes=1000), dict(block_threads=96), dict(unroll=3), dict(unroll=16), dict(blocks_per_cu=100),
-                dict(unroll=8, flags=5), dict(flags=64)):
+                dict(unroll=8, flags=5), dict(flags=128)):
         with pytest.raises(ReshardError):
             set_tuning(**bad)
     assert get_tuning() == base
@@ -467,7 +502,7 @@ def test_every_plan_keeps_its_own_tuning():
         c = Plan(w["spec"], w["src"], w["dst"])
     finally:
         set_tuning()
-    assert a.get_tuning() == dict(tile_bytes=4096, block_threads=256, blocks_per_cu=0, unroll=1, flags=63,
+    assert a.get_tuning() == dict(tile_bytes=4096, block_threads=256, blocks_per_cu=0, unroll=1, flags=127,
                                   transpose_rows=0, transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16)
     assert b.get_tuning()["tile_bytes"] == 32768 and b.get_tuning()["unroll"] == 2
     assert c.get_tuning()["tile_bytes"] == 8192 and c.get_tuning()["unroll"] == 4 and c.get_tuning()["flags"] == 7

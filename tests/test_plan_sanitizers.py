@@ -53,9 +53,10 @@ def test_random_and_mutated_cases_under_asan_and_ubsan(tmp_path):
     never a crash, an overflow or a tile outside its buffer)."""
     import random
 
-    from synth_inputs import random_case
+    from synth_inputs import MID, random_case
 
-    lines = []
+    # mid-size shapes whose side-by-side merges are also cut as gathered tiles, and wide random ones
+    lines = [case_line(1, w["spec"], w["src"], w["dst"]) for w in list(MID.values()) + [random_case(seed, 16) for seed in range(16)]]
     for seed in range(120):
         w = random_case(seed, 1 if seed < 96 else 4)
         lines.append(case_line(1, w["spec"], w["src"], w["dst"]))
@@ -71,7 +72,7 @@ def test_random_and_mutated_cases_under_asan_and_ubsan(tmp_path):
     exe, env = build(tmp_path)
     res = subprocess.run([exe, str(path)], capture_output=True, text=True, env=env, timeout=600)
     assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
-    assert "600 cases from file" in res.stdout and res.stdout.strip().endswith("ok")
+    assert "620 cases from file" in res.stdout and res.stdout.strip().endswith("ok")
 
 
 @pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
