@@ -331,14 +331,16 @@ double reshard_redundant_memory_bytes(int gen_dp, double tp_weight_bytes, int up
 /* Plan statistics and the descriptor table (copied into caller memory). */
 int reshard_plan_get_info(const reshard_plan *plan, reshard_plan_info *out);
 int reshard_plan_desc(const reshard_plan *plan, int64_t index, reshard_desc *out);
-/* Tile `index` in launch order (0 <= index < num_tiles). */
+/* Record `index` of the tile table, in table order (0 <= index < num_tiles): the copy tiles (tiles of
+ * pitched rows, then contiguous runs, then gathered tiles), then the transposing tiles by shape.
+ * See reshard_tile.order for which records an execute launches. */
 int reshard_plan_tile(const reshard_plan *plan, int64_t index, reshard_tile *out);
 
 /*
  * Step 2 (slice selection and copy), run time: asynchronous kernel launches on `stream` (one for the
- * copy tiles of several pitched rows, one for the contiguous runs, one per transposing tile
- * shape in use; three or fewer for most plans, a dozen at most) that fill every used destination
- * buffer from the source buffers.
+ * copy tiles of several pitched rows, one for the contiguous runs, one for the gathered tiles, one
+ * per transposing tile shape in use, each only where the plan has such tiles; three or fewer for
+ * most plans, a dozen at most) that fill every used destination buffer from the source buffers.
  * src_ptrs[num_src_bufs], dst_ptrs[num_dst_bufs]: device pointers, each aligned to
  * 256 bytes and at least buf_bytes long; NULL allowed only where used == 0.  The
  * two sets must not overlap.  The memory stays caller-owned and must remain valid
