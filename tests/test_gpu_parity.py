@@ -168,6 +168,14 @@ def test_side_by_side_merges_as_gathered_tiles(name):
             torch.cuda.synchronize()
             for a, b in zip(dst, by_source):
                 assert (a is None and b is None) or torch.equal(a, b)
+            # the same plan switched between its two forms from one execute to the next
+            for flags in (63, 127, 31, 127):
+                plan.set_tuning(flags=flags)
+                other = G.device_destinations(plan)
+                plan.execute(G.ptrs(src), G.ptrs(other), G.stream_handle())
+                torch.cuda.synchronize()
+                for a, b in zip(dst, other):
+                    assert (a is None and b is None) or torch.equal(a, b), flags
     for tuning in (None, dict(flags=127, tile_bytes=4096)):
         counts, D = _count_writes_on_device(wl, tuning)
         for b, c in enumerate(counts):
