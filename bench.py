@@ -643,6 +643,9 @@ def main():
     # GB were freed (the driver clears them) host copies on this machine run at half rate now and then
     overlap = run.overlap(a.overlap_steps) if (a.overlap_steps > 0 and not a.no_swap) else None
     say(a, "overlap done")
+    # the same kernel with nothing between the executes: in a step it starts after seconds of link copies during
+    # which the shader engines sat idle
+    b2b = run.repack_only(7)[1:]
     link = None if a.no_link_probe or a.no_swap else link_probe()
     head = run.summary(link)
     driver_freed = None if a.no_swap else run.driver_free_check()
@@ -711,6 +714,10 @@ def main():
     }
     if probes:
         out["roofline"]["frac_of_mixed_bound"] = round(head["GBps"] / probes["mixed_bound_GBps"], 4)
+    b2b_s = sum(b2b) / len(b2b) / 1e3
+    out["roofline"]["back_to_back"] = {"what": "executes queued back to back after the timed region, event-timed one by one (not `value`)",
+                                       "samples": len(b2b), "kernel_ms_avg": round(b2b_s * 1e3, 4),
+                                       "GBps": round(2 * moved / b2b_s / 1e9, 1), "frac": round(2 * moved / b2b_s / 1e9 / HBM_PEAK_GBPS, 4)}
     if "swap" in head:
         out["swap"] = dict(head["swap"], link_probe_GBps=None if link is None else {k: round(v, 2) for k, v in link.items()})
     if overlap:
