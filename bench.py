@@ -64,6 +64,9 @@ def parse():
                          "turn for --ablate-rounds rounds (so that all variants see the same physical placement); "
                          "prints one JSON line with the event-timed kernel time of each")
     ap.add_argument("--ablate-rounds", type=int, default=10)
+    ap.add_argument("--ablate-repeat", type=int, default=1,
+                    help="executes of one variant in a row inside a round, all timed (shows what depends on the execute before "
+                         "being the same plan's, e.g. table_copies=1)")
     ap.add_argument("--as-entry", action="store_true",
                     help="(used by the bench itself for --others) measure --workload alone and print it as one entry of `workloads`")
     ap.add_argument("--link", default="", help="(with --as-entry) the link probe's d2h,h2d GB/s from the parent run")
@@ -528,15 +531,16 @@ def ablation(a, run):
     for _ in range(a.ablate_rounds):
         evs = []
         plans[-1].execute(run.ptrs(run.src), run.ptrs(run.dst), run.h)  # untimed: the first launch after a host wait runs slow
-        for p in plans:
-            e0, e1 = run.events()
-            e0.record(run.stream)
-            p.execute(run.ptrs(run.src), run.ptrs(run.dst), run.h)
-            e1.record(run.stream)
-            evs.append((e0, e1))
+        for i, p in enumerate(plans):
+            for _ in range(max(1, a.ablate_repeat)):
+                e0, e1 = run.events()
+                e0.record(run.stream)
+                p.execute(run.ptrs(run.src), run.ptrs(run.dst), run.h)
+                e1.record(run.stream)
+                evs.append((i, e0, e1))
         torch.cuda.synchronize()
-        for t, (e0, e1) in zip(times, evs):
-            t.append(e0.elapsed_time(e1))
+        for i, e0, e1 in evs:
+            times[i].append(e0.elapsed_time(e1))
     moved = run.info["bytes_moved"]
     base = sum(times[0]) / len(times[0])
     out = []
@@ -545,9 +549,17 @@ def ablation(a, run):
         out.append({"tuning": v, "tiles": p.info()["num_tiles"], "kernel_ms_avg": round(avg, 4), "kernel_ms_min": round(min(t), 4),
                     "GBps": round(2 * moved / avg / 1e6, 1), "frac": round(2 * moved / avg / 1e6 / HBM_PEAK_GBPS, 4),
                     "vs_first_pct": round(100 * (base / avg - 1), 2)})
+        rep = max(1, a.ablate_repeat)
+        if rep > 1:  # the first execute of a row follows another plan's, the later ones this plan's own
+            lead, rest = t[0::rep], [x for i, x in enumerate(t) if i % rep]
+            out[-1]["GBps_first_in_row"] = round(2 * moved / (sum(lead) / len(lead)) / 1e6, 1)
+            out[-1]["GBps_later_in_row"] = round(2 * moved / (sum(rest) / len(rest)) / 1e6, 1)
+            out[-1]["table_copies"] = p.get_tuning()["table_copies"]
         p.destroy()
     return {"ablation": out, "workload": "%s: %s" % (wl["name"], wl["note"]), "bytes_moved_one_way": moved,
-            "rounds": a.ablate_rounds, "order": "one warm-up execute per variant, then rounds of (one untimed execute of the last variant, one timed execute per variant in the order given)"}
+            "rounds": a.ablate_rounds, "repeat": max(1, a.ablate_repeat),
+            "order": "one warm-up execute per variant, then rounds of (one untimed execute of the last variant, `repeat` timed "
+                     "executes in a row per variant in the order given)"}
 
 
 def entry_of(a, run):

@@ -196,7 +196,8 @@ typedef struct reshard_plan_info {
     int64_t num_tiles;      /* records of the tile table (device work items; see reshard_tile.order) */
     int64_t num_transpose_tiles; /* of which transposing tiles (register path + generic path) */
     int64_t bytes_moved;    /* destination bytes written by one execute (== bytes read) */
-    int64_t table_bytes;    /* device memory held by the plan (tile table) */
+    int64_t table_bytes;    /* bytes of one copy of the tile table; the plan holds reshard_tuning.table_copies copies
+                               (see there) of table_bytes + 256 bytes each on the device once it is prepared */
 } reshard_plan_info;
 
 /* Swap / residency state of the source (training-side) buffers of a plan. */
@@ -252,6 +253,13 @@ typedef struct reshard_tuning {
                                   every eighth goes to a pool that the last workgroups of the grid drain in chunks, so
                                   XCDs that finish early take over work of the slower ones (default launch shape only) */
     int32_t tail_chunk_tiles;  /* tiles a pool workgroup takes per fetch, 1..1024 (default 16) */
+    int32_t table_copies;      /* copies of the tile table the plan keeps on the device, 1..64; execute number n reads copy
+                                  n mod table_copies.  Why: the woven copy kernel runs 3 to 4 % slower when the records it
+                                  reads are still in the 256 MB memory-side cache from the execute before, which happens
+                                  when executes follow each other with less than that much other cached traffic in
+                                  between.  0 (default): as many copies as make 512 MiB of tables, at most 32, and one
+                                  for a table under 1 MiB.  Fixed once the table is on the device (first execute or
+                                  prepare); reshard_execute_source and reshard_execute_noalloc read a single copy */
 } reshard_tuning;
 
 /* Thread-local message of the last failing call on this thread ("" if none). */

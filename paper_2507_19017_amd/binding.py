@@ -67,7 +67,7 @@ class MemStats(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("tile_bytes", "block_threads", "blocks_per_cu", "unroll", "flags", "transpose_rows", "transpose_cols",
-                                          "tail_pool_percent", "tail_chunk_tiles")]
+                                          "tail_pool_percent", "tail_chunk_tiles", "table_copies")]
 
 
 class ReshardError(RuntimeError):

@@ -324,6 +324,7 @@ extern "C" int reshard_plan_set_tuning(reshard_plan *p, const reshard_tuning *t)
     n.tile_bytes = p->tuning.tile_bytes;
     n.transpose_rows = p->tuning.transpose_rows;
     n.transpose_cols = p->tuning.transpose_cols;
+    if (p->d_tiles || !(t && t->table_copies)) n.table_copies = p->tuning.table_copies;  // fixed once the table is on the device
     p->tuning = n;
     return RESHARD_OK;
 }

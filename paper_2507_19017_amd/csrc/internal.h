@@ -77,6 +77,8 @@ struct Tuning {
     int transpose_cols = 0;       // 0 (or a shape the element size does not allow): the default for that size
     int tail_pool_percent = 0;    // copy kernel: share of every XCD's eighth of the table left to the shared tail pool
     int tail_chunk_tiles = 16;    // tiles a pool workgroup takes per fetch
+    int table_copies = 0;         // copies of the tile table on the device that successive executes rotate through
+                                  // (0: as many as make 512 MiB, at most 32; one for tables under 1 MiB)
 };
 // The process-wide default that new plans copy (every plan then keeps its own).
 Tuning current_tuning();
@@ -175,6 +177,12 @@ struct reshard_plan {
     std::vector<SrcSlice> src_slices;
     std::vector<reshard::Tile> by_src_tiles;
     void *d_by_src = nullptr;
+    // d_tiles holds table_copies copies of the table, table_stride bytes apart; execute number n reads copy
+    // n mod table_copies, so that the records an execute reads are not still in the memory-side cache from the
+    // execute before (the woven kernel runs 3 to 4 % slower when they are)
+    int table_copies = 1;
+    size_t table_stride = 0;
+    uint64_t executes = 0;
 
     // bound pointers
     std::vector<const void *> src_ptrs;

@@ -225,6 +225,8 @@ int tuning_from_abi(const reshard_tuning *t, Tuning &out) {
                 return fail(RESHARD_ERR_INVALID_ARG, "tail_chunk_tiles must be in [1, 1024]");
             n.tail_chunk_tiles = t->tail_chunk_tiles;
         }
+        if (t->table_copies < 0 || t->table_copies > 64) return fail(RESHARD_ERR_INVALID_ARG, "table_copies must be in [0, 64]");
+        if (t->table_copies) n.table_copies = t->table_copies;  // 0 keeps what the defaults say (built in: chosen from the table size)
         // the one-tile copy kernel is built for every hint set at unroll 2, for none or all at the others
         const int hints = n.flags & 7;
         if (n.blocks_per_cu == 0 && n.unroll != 2 && hints != 0 && hints != 7)
@@ -244,6 +246,7 @@ void tuning_to_abi(const Tuning &t, reshard_tuning *out) {
     out->transpose_cols = t.transpose_cols;
     out->tail_pool_percent = t.tail_pool_percent;
     out->tail_chunk_tiles = t.tail_chunk_tiles;
+    out->table_copies = t.table_copies;
 }
 
 int build_side(const reshard_model_spec &s, const reshard_layout &l, bool is_source, Side &out) {

@@ -612,12 +612,14 @@ int query_device(reshard_plan *plan) {
     return RESHARD_OK;
 }
 
-int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
+// `copies` copies of the table, `*stride` bytes apart (the first from the host, the others from the first).
+int upload(const std::vector<const std::vector<Tile> *> &lists, void **out, int copies = 1, size_t *stride = nullptr) {
     size_t total = 0;
     for (auto *l : lists) total += l->size();
     void *mem = nullptr;
-    // 256 bytes behind the table hold the counters of the copy kernel's shared tail pool
-    if (hipError_t e = hipMalloc(&mem, total * sizeof(Tile) + 256)) {
+    // 256 bytes behind each table hold the counters of the copy kernel's shared tail pool
+    const size_t one = ((total * sizeof(Tile) + 255) & ~size_t(255)) + 256;
+    if (hipError_t e = hipMalloc(&mem, one * size_t(copies))) {
         (void)hipGetLastError();
         return fail(RESHARD_ERR_OOM, std::string("hipMalloc of the tile table: ") + hipGetErrorString(e));
     }
@@ -630,6 +632,12 @@ int upload(const std::vector<const std::vector<Tile> *> &lists, void **out) {
         }
         at += l->size();
     }
+    for (int k = 1; k < copies; ++k)
+        if (hipError_t e = hipMemcpy(static_cast<char *>(mem) + size_t(k) * one, mem, total * sizeof(Tile), hipMemcpyDeviceToDevice)) {
+            (void)hipFree(mem);
+            return hip_fail(e, "hipMemcpy of a copy of the tile table");
+        }
+    if (stride) *stride = one;
     *out = mem;
     return RESHARD_OK;
 }
@@ -786,15 +794,25 @@ int ensure_device_table(reshard_plan *plan) {
     if (plan->d_tiles || plan->info.num_tiles == 0) return RESHARD_OK;
     std::vector<const std::vector<Tile> *> lists;
     for (const TileClass &c : plan->classes) lists.push_back(&c.tiles);
-    return upload(lists, &plan->d_tiles);
+    // copies to rotate through: what the tuning names, else enough to make 512 MiB (a single one for a small table)
+    int copies = plan->tuning.table_copies;
+    if (copies <= 0) {
+        const int64_t bytes = plan->info.table_bytes;
+        copies = bytes < (int64_t(1) << 20) ? 1 : int(std::min<int64_t>(32, ((int64_t(512) << 20) + bytes - 1) / bytes));
+    }
+    if (int rc = upload(lists, &plan->d_tiles, copies, &plan->table_stride)) return rc;
+    plan->table_copies = plan->tuning.table_copies = copies;
+    return RESHARD_OK;
 }
 
 int launch_repack(reshard_plan *plan, hipStream_t stream) {
     const Tuning &tn = plan->tuning;
     PtrTable pt;
     fill_ptrs(plan, pt);
-    const Tile *tiles = static_cast<const Tile *>(plan->d_tiles);
-    uint32_t *counters = reinterpret_cast<uint32_t *>(static_cast<char *>(plan->d_tiles) + size_t(plan->info.num_tiles) * sizeof(Tile));
+    // this execute's copy of the table: the one least recently read
+    char *table = static_cast<char *>(plan->d_tiles) + size_t(plan->executes++ % uint64_t(plan->table_copies)) * plan->table_stride;
+    const Tile *tiles = reinterpret_cast<const Tile *>(table);
+    uint32_t *counters = reinterpret_cast<uint32_t *>(table + plan->table_stride - 256);
     for (const TileClass &c : plan->classes) {
         const uint32_t n = uint32_t(c.tiles.size());
         if (c.kind == 0) {

@@ -12,7 +12,7 @@ struct fakeStream { int id; };
 struct fakeEvent { long recorded; };
 typedef fakeStream *hipStream_t;
 typedef fakeEvent *hipEvent_t;
-enum hipMemcpyKind { hipMemcpyHostToDevice = 1, hipMemcpyDeviceToHost = 2 };
+enum hipMemcpyKind { hipMemcpyHostToDevice = 1, hipMemcpyDeviceToHost = 2, hipMemcpyDeviceToDevice = 3 };
 enum { hipStreamNonBlocking = 1, hipEventDisableTiming = 2, hipHostMallocDefault = 0 };
 
 extern long fake_hip_host_limit;   // bytes hipHostMalloc may hand out in total (-1 = no limit)

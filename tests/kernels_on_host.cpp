@@ -58,16 +58,6 @@ static int run(const reshard_model_spec &spec, const reshard_layout &src, const 
         std::memset(D[size_t(j)], 0xA5, n);
         std::memset(W[size_t(j)], 0xA5, n);
     }
-    if (by_source) {
-        for (int i = 0; i < ns; ++i)
-            if (S[size_t(i)]) REQUIRE(reshard_execute_source(plan, i, S[size_t(i)], D.data(), nullptr) == RESHARD_OK);
-    } else {
-        // alternately through the plan's own table and through the static array (which the
-        // previous case's table still fills: a new table must replace it)
-        static int flip = 0;
-        std::vector<const void *> sp(S.begin(), S.end());
-        REQUIRE(((flip++ & 1) ? reshard_execute_noalloc : reshard_execute)(plan, sp.data(), D.data(), nullptr) == RESHARD_OK);
-    }
     // what the descriptor table says, byte by byte
     reshard_plan_info info;
     REQUIRE(reshard_plan_get_info(plan, &info) == RESHARD_OK);
@@ -85,12 +75,29 @@ static int run(const reshard_model_spec &spec, const reshard_layout &src, const 
                     std::memcpy(w + k * d.dst_stride + i * d.elem_bytes, s + i * d.src_stride + k * d.elem_bytes, size_t(d.elem_bytes));
         }
     }
+    // A plan that keeps several copies of its tile table reads another one at every execute: run it through all
+    // of them and once round, every execute from sentinel-filled destinations and checked like the first.
+    const int executes = (tn && tn->table_copies > 1 && !by_source) ? tn->table_copies + 1 : 1;
     int bad = 0;
-    for (int j = 0; j < nd; ++j)
-        if (D[size_t(j)] && std::memcmp(D[size_t(j)], W[size_t(j)], size_t(reshard_plan_buf_bytes(plan, 1, j)))) {
-            std::printf("destination buffer %d differs from the descriptor table's result\n", j);
-            bad = 1;
+    for (int rep = 0; rep < executes && !bad; ++rep) {
+        for (int j = 0; j < nd; ++j)
+            if (D[size_t(j)]) std::memset(D[size_t(j)], 0xA5, size_t(reshard_plan_buf_bytes(plan, 1, j)));
+        if (by_source) {
+            for (int i = 0; i < ns; ++i)
+                if (S[size_t(i)]) REQUIRE(reshard_execute_source(plan, i, S[size_t(i)], D.data(), nullptr) == RESHARD_OK);
+        } else {
+            // alternately through the plan's own table and through the static array (which the
+            // previous case's table still fills: a new table must replace it)
+            static int flip = 0;
+            std::vector<const void *> sp(S.begin(), S.end());
+            REQUIRE(((executes == 1 && (flip++ & 1)) ? reshard_execute_noalloc : reshard_execute)(plan, sp.data(), D.data(), nullptr) == RESHARD_OK);
         }
+        for (int j = 0; j < nd; ++j)
+            if (D[size_t(j)] && std::memcmp(D[size_t(j)], W[size_t(j)], size_t(reshard_plan_buf_bytes(plan, 1, j)))) {
+                std::printf("destination buffer %d differs from the descriptor table's result (execute %d)\n", j, rep);
+                bad = 1;
+            }
+    }
     REQUIRE(reshard_plan_destroy(plan) == RESHARD_OK);
     for (void *p : S) std::free(p);
     for (void *p : D) std::free(p);
@@ -132,7 +139,9 @@ int main(int argc, char **argv) {
     if (argc > 1) {
         reshard_tuning tiny{};
         tiny.tile_bytes = 4096; tiny.block_threads = 128; tiny.unroll = 1;
-        bad = run_file(argv[1], &tiny);  // 128-lane workgroups: cheap to emulate
+        // 128-lane workgroups are cheap to emulate; "default" as a second argument runs the default launch shape
+        // (1024 lanes, woven order) instead
+        bad = run_file(argv[1], argc > 2 && !std::strcmp(argv[2], "default") ? nullptr : &tiny);
         std::printf(bad ? "FAILED %d\n" : "ok\n", bad);
         return bad ? 1 : 0;
     }
@@ -147,6 +156,7 @@ int main(int argc, char **argv) {
     moe.family = RESHARD_MOE_GQA; moe.L = 1; moe.H = 336; moe.nq = 4; moe.nkv = 2; moe.d = 16; moe.V = 32; moe.has_embeddings = 1;
     moe.E = 2; moe.Ie = 208; moe.n_shared = 0;
     reshard_tuning small{}, odd{}, persistent{}, plain_order{}, wide192{}, pooled{}, woven{}, woven_small{};
+    small.table_copies = 3;  // three copies of the tile table, read in turn
     woven.flags = 127;                                  // the XCDs share every group of 8 tiles
     woven_small.flags = 100; woven_small.tile_bytes = 4096;  // plain accesses with the barrier, tiles of 256 units
     pooled.tile_bytes = 4096; pooled.flags = 31; pooled.tail_pool_percent = 30; pooled.tail_chunk_tiles = 1;  // 1024-lane workgroups, a shared tail

@@ -187,6 +187,38 @@ def test_side_by_side_merges_as_gathered_tiles(name):
             assert np.array_equal(c, want), f"{name} buffer {b}: {int((c != want).sum())} bytes not written exactly once"
 
 
+def test_successive_executes_rotate_through_the_copies_of_the_tile_table():
+    """A plan keeps several copies of its tile table on the device and every execute reads the next
+    one (so that the records are not still in the memory-side cache from the execute before).  Every
+    copy gives the oracle's bits; the count is what the tuning says, or chosen from the table size
+    (one for a small table), and is fixed once the table is on the device."""
+    wl = MID["mid_merge2"]
+    plan, src, dst = run_case(wl, "raw16", tuning=dict(table_copies=3))
+    assert plan.get_tuning()["table_copies"] == 3
+    plan.set_tuning(table_copies=7, flags=127)  # the launch shape changes, the copies stay
+    assert plan.get_tuning()["table_copies"] == 3 and plan.get_tuning()["flags"] == 127
+    for n in range(7):
+        again = G.device_destinations(plan)
+        plan.execute(G.ptrs(src), G.ptrs(again), G.stream_handle())
+        torch.cuda.synchronize()
+        for a, b in zip(dst, again):
+            assert (a is None and b is None) or torch.equal(a, b), n
+    small = Plan(WORKLOADS["C0"]["spec"], WORKLOADS["C0"]["src"], WORKLOADS["C0"]["dst"])
+    assert small.get_tuning()["table_copies"] == 0
+    small.prepare()
+    assert small.get_tuning()["table_copies"] == 1
+    big = Plan(WORKLOADS["C1"]["spec"], WORKLOADS["C1"]["src"], WORKLOADS["C1"]["dst"])
+    big.prepare()  # 29.9 MB of table: 18 copies make 512 MiB
+    assert big.get_tuning()["table_copies"] == 18
+    before = torch.cuda.mem_get_info()[0]
+    big.destroy()
+    assert torch.cuda.mem_get_info()[0] - before >= 18 * big_table_bytes(wl=WORKLOADS["C1"]) - (64 << 20)
+
+
+def big_table_bytes(wl):
+    return Plan(wl["spec"], wl["src"], wl["dst"]).info()["table_bytes"]
+
+
 def test_two_plans_with_different_tunings_interleave():
     """Tuning belongs to the plan: two plans of one workload cut into different tile sizes and launched
     with different shapes run alternately on one stream, one of them changes its launch shape in

@@ -475,7 +475,7 @@ def test_tuning_is_validated():
     set_tuning()
     base = get_tuning()
     assert base == dict(tile_bytes=32768, block_threads=1024, blocks_per_cu=0, unroll=2, flags=127, transpose_rows=0,
-                        transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16)
+                        transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16, table_copies=0)
     set_tuning(tile_bytes=8192, unroll=4)
     assert get_tuning()["tile_bytes"] == 8192 and get_tuning()["unroll"] == 4
     w = WORKLOADS["C1"]
@@ -484,7 +484,7 @@ def test_tuning_is_validated():
     n32 = Plan(w["spec"], w["src"], w["dst"]).info()["num_tiles"]
     assert n8 > 3.5 * n32
     for bad in (dict(tile_bytes=1000), dict(block_threads=96), dict(unroll=3), dict(unroll=16), dict(blocks_per_cu=100),
-                dict(unroll=8, flags=5), dict(flags=128)):
+                dict(unroll=8, flags=5), dict(flags=128), dict(table_copies=65), dict(table_copies=-1)):
         with pytest.raises(ReshardError):
             set_tuning(**bad)
     assert get_tuning() == base
@@ -503,7 +503,7 @@ def test_every_plan_keeps_its_own_tuning():
     finally:
         set_tuning()
     assert a.get_tuning() == dict(tile_bytes=4096, block_threads=256, blocks_per_cu=0, unroll=1, flags=127,
-                                  transpose_rows=0, transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16)
+                                  transpose_rows=0, transpose_cols=0, tail_pool_percent=0, tail_chunk_tiles=16, table_copies=0)
     assert b.get_tuning()["tile_bytes"] == 32768 and b.get_tuning()["unroll"] == 2
     assert c.get_tuning()["tile_bytes"] == 8192 and c.get_tuning()["unroll"] == 4 and c.get_tuning()["flags"] == 7
     assert a.info()["num_tiles"] > c.info()["num_tiles"] >= b.info()["num_tiles"]

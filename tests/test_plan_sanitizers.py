@@ -133,3 +133,12 @@ def test_the_real_kernels_run_on_the_host_under_asan(tmp_path):
     res = subprocess.run([exe, str(path)], capture_output=True, text=True, env=env, timeout=900)
     assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
     assert "24 cases from file" in res.stdout and res.stdout.strip().endswith("ok")
+    # and at the DEFAULT launch shape (1024 lanes, woven order): the tiny models, which include plans with
+    # unused buffers (the tile records index a table of the used buffers only), and random ones
+    from synth_inputs import TINY
+
+    wls = [w for n, w in sorted(TINY.items()) if n != "big_moe_grouped"] + [random_case(seed) for seed in range(24, 40)]
+    path.write_text("\n".join(case_line(1, w["spec"], w["src"], w["dst"]) for w in wls) + "\n")
+    res = subprocess.run([exe, str(path), "default"], capture_output=True, text=True, env=env, timeout=900)
+    assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
+    assert "%d cases from file" % len(wls) in res.stdout and res.stdout.strip().endswith("ok")
