@@ -721,6 +721,7 @@ def main():
                          **(probes or {})),
         "pct_hbm_peak": round(100 * head["frac"], 2),
         "peak_hbm_bytes": {"ledger": stats["peak_device"], "torch_max_allocated": head["torch_max_allocated"],
+                           "plan_tile_tables": plan_tuning["table_copies"] * (info["table_bytes"] + 256),
                            "freed_after_swap_out": (sum(freed) // len(freed)) if freed else None,
                            "returned_to_driver_after_swap_out": driver_freed},
     }
