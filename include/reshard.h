@@ -257,8 +257,8 @@ typedef struct reshard_tuning {
                                   n mod table_copies.  Why: the woven copy kernel runs 3 to 4 % slower when the records it
                                   reads are still in the 256 MB memory-side cache from the execute before, which happens
                                   when executes follow each other with less than that much other cached traffic in
-                                  between.  0 (default): as many copies as make 512 MiB of tables, at most 32, and one
-                                  for a table under 1 MiB.  Fixed once the table is on the device (first execute or
+                                  between.  0 (default): as many copies as make 512 MiB of tables, and one for a table
+                                  under 16 MiB (32 copies would not get there, and fewer than that buy nothing).  Fixed once the table is on the device (first execute or
                                   prepare); reshard_execute_source and reshard_execute_noalloc read a single copy */
 } reshard_tuning;
 

@@ -78,7 +78,7 @@ struct Tuning {
     int tail_pool_percent = 0;    // copy kernel: share of every XCD's eighth of the table left to the shared tail pool
     int tail_chunk_tiles = 16;    // tiles a pool workgroup takes per fetch
     int table_copies = 0;         // copies of the tile table on the device that successive executes rotate through
-                                  // (0: as many as make 512 MiB, at most 32; one for tables under 1 MiB)
+                                  // (0: as many as make 512 MiB; one for a table under 16 MiB, where 32 would not)
 };
 // The process-wide default that new plans copy (every plan then keeps its own).
 Tuning current_tuning();

@@ -794,11 +794,12 @@ int ensure_device_table(reshard_plan *plan) {
     if (plan->d_tiles || plan->info.num_tiles == 0) return RESHARD_OK;
     std::vector<const std::vector<Tile> *> lists;
     for (const TileClass &c : plan->classes) lists.push_back(&c.tiles);
-    // copies to rotate through: what the tuning names, else enough to make 512 MiB (a single one for a small table)
+    // copies to rotate through: what the tuning names, else enough to make 512 MiB (twice the memory-side cache);
+    // a single one where 32 copies would not get there (a table under 16 MiB: fewer copies than that buy nothing)
     int copies = plan->tuning.table_copies;
     if (copies <= 0) {
-        const int64_t bytes = plan->info.table_bytes;
-        copies = bytes < (int64_t(1) << 20) ? 1 : int(std::min<int64_t>(32, ((int64_t(512) << 20) + bytes - 1) / bytes));
+        const int64_t bytes = plan->info.table_bytes, want = ((int64_t(512) << 20) + bytes - 1) / std::max<int64_t>(bytes, 1);
+        copies = want <= 32 ? int(want) : 1;
     }
     if (int rc = upload(lists, &plan->d_tiles, copies, &plan->table_stride)) return rc;
     plan->table_copies = plan->tuning.table_copies = copies;
