@@ -259,7 +259,8 @@ typedef struct reshard_tuning {
                                   when executes follow each other with less than that much other cached traffic in
                                   between.  0 (default): as many copies as make 512 MiB of tables, and one for a table
                                   under 16 MiB (32 copies would not get there, and fewer than that buy nothing).  Fixed once the table is on the device (first execute or
-                                  prepare); reshard_execute_source and reshard_execute_noalloc read a single copy */
+                                  prepare); reshard_execute_source and reshard_execute_noalloc read a single copy, and an
+                                  execute recorded into a HIP graph reads, at every replay, the copy it was recorded with */
 } reshard_tuning;
 
 /* Thread-local message of the last failing call on this thread ("" if none). */
